@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the EfQAT backward hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input, for every layer of
+the workload: activation statistic + fake-quant, weight statistic + fake-quant, channel importance +
+Top-K, then the restricted backward (dX product with fused STE / S_x, Z_x gradients; gathered dW
+product; mask + S_w gradients).  The headline value is the backward TFLOP/s at the headline update
+fraction, 2*T*C_in*(C_out + k) per layer (Eq. 7 of the paper times 2*T), over the whole step time.
+A sweep over update fractions (backward call only) is attached, with the speedup over the full
+(r = 100 %) backward, which is the quantity the paper reports (1.44-1.64x on A10 / A100, whole
+networks, as context only).
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg5"])
+    ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
+    ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device buffers of one layer, all allocated up front (nothing is allocated in a timed region)."""
+
+    def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth):
+        self.name, self.T, self.c_in, self.c_out = name, T, c_in, c_out
+        self.a_bits, self.w_bits, self.layout = a_bits, w_bits, layout
+        X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype)
+        self.host = (X, W, dY)
+        tdt = torch.bfloat16 if act_dtype == "bf16" else torch.float32
+        self.x = torch.from_numpy(X).to(tdt).cuda()
+        self.w = torch.from_numpy(W).cuda()
+        dyh = dY if layout == 0 else dY.T.copy()
+        self.dy = torch.from_numpy(dyh).to(tdt).cuda()
+        dev = self.x.device
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        self.fx = dict(codes=e((T, c_in), torch.uint8), clip_bits=e((T, (c_in + 31) // 32), torch.int32),
+                       scale=e(1, torch.float32), zero_point=e(1, torch.float32))
+        self.fw = dict(codes=e((c_out, c_in), torch.int8), clip_bits=e((c_out, (c_in + 31) // 32), torch.int32),
+                       scale=e(c_out, torch.float32))
+        self.scores = e(c_out, torch.float64)
+        self.idx_full = e(c_out, torch.int32)
+        self.dx = e((T, c_in), tdt)
+        self.dw = e((c_out, c_in), torch.float32)       # compact [k, c_in] uses the first k rows
+        self.ds_w = e(c_out, torch.float32)
+        self.ds_x, self.dz_x = e(1, torch.float32), e(1, torch.float32)
+        L = ef.lib()
+        dyd = 1 if act_dtype == "bf16" else 0
+        need = max(L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, c_out, dyd, layout),
+                   L.efqat_fakequant_fwd_workspace_bytes(T, c_in, 0),
+                   L.efqat_channel_select_workspace_bytes(c_out))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    def forward_quant(self, ef):
+        ef.fakequant_fwd(self.x, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=self.fx)
+        ef.fakequant_fwd(self.w, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws, out=self.fw)
+
+    def select(self, ef, k):
+        idx = self.idx_full[:k]
+        ef.channel_select(self.w, k, ws=self.ws, out=dict(scores=self.scores, idx=idx))
+        return idx
+
+    def backward(self, ef, idx):
+        k = int(idx.numel())
+        out = dict(dx=self.dx, dw=self.dw[:max(k, 1)], ds_w=self.ds_w[:max(k, 1)], ds_x=self.ds_x, dz_x=self.dz_x)
+        ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
+                      self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
+                      idx if k else None, dy_layout=self.layout, ws=self.ws, out=out)
+
+    def flops(self, k):
+        return 2.0 * self.T * self.c_in * (self.c_out + k)
+
+
+def time_region(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(layers, num, den, a_bits, w_bits):
+    """The oracle, as it stands, on the host cores: one backward of the first layer on a token sample."""
+    import numpy as np
+    from oracle import efqat_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    lay = layers[0]
+    X, W, dY = lay.host
+    Ts = min(lay.T, 4096)
+    X, dY = X[:Ts], dY[:Ts]
+    t0 = time.perf_counter()
+    sx, zx = orc.act_qparams_minmax(X, a_bits)
+    sw = orc.weight_scale_minmax(W, w_bits)
+    k = orc.k_from_ratio(lay.c_out, num, den)
+    idx = orc.top_k_channels(orc.channel_importance(W), k)
+    orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
+    dt = time.perf_counter() - t0
+    fl = 2.0 * Ts * lay.c_in * (lay.c_out + k)
+    return dict(value=fl / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
+                sample="layer %s, first %d of %d tokens, r=%d/%d, whole hot path (quantize, select, backward), "
+                       "fp64 NumPy, %.2f s" % (lay.name, Ts, lay.T, num, den, dt))
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by tokens; see DESIGN.md); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2411_11038_amd as ef
+    from workloads import synth
+
+    if not os.path.exists(ef.lib_path()):
+        from paper_2411_11038_amd import build as b
+        b.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg5": synth.CFG5}[args.workload]
+    w_bits = cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0]
+    layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
+                    args.dy_layout, synth) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
+    if args.fraction:
+        num, den = (int(t) for t in args.fraction.split("/"))
+    else:
+        num, den = 1, 4
+    ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
+
+    def step():
+        for l, k in zip(layers, ks):
+            l.forward_quant(ef)
+            idx = l.select(ef, k)
+            l.backward(ef, idx)
+
+    for _ in range(args.warmup):
+        step()
+    ef.profile_enable(True)
+    sec = time_region(torch, step, args.steps)
+    dx_ms, dx_n = ef.profile_read(0)
+    dw_ms, dw_n = ef.profile_read(1)
+    ef.profile_enable(False)
+    flops = sum(l.flops(k) for l, k in zip(layers, ks))
+    value = flops / sec / 1e12
+
+    # dominant kernel: the dX product (always the full C_out); algorithmic flops per launch
+    dx_flops = sum(2.0 * l.T * l.c_in * l.c_out for l in layers) / len(layers)
+    dx_avg_s = dx_ms / max(dx_n, 1) / 1e3
+    achieved = dx_flops / dx_avg_s / 1e12 if dx_n else 0.0
+    roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None, kernel="k_gemm_nt<dX epilogue>",
+                    avg_kernel_ms=dx_avg_s * 1e3, launches=int(dx_n),
+                    dw_kernel_avg_ms=(dw_ms / dw_n) if dw_n else None)
+
+    sweep = []
+    if not args.no_sweep:
+        for l in layers:
+            l.forward_quant(ef)
+        fr = list(cfg["fractions"])
+        if (1, 1) not in fr:
+            fr.append((1, 1))
+        times = {}
+        for (n_, d_) in fr:
+            kk = [ef.k_from_ratio(l.c_out, n_, d_) for l in layers]
+            idxs = [l.select(ef, k) for l, k in zip(layers, kk)]
+
+            def bwd():
+                for l, idx in zip(layers, idxs):
+                    l.backward(ef, idx)
+            for _ in range(max(2, args.warmup // 2)):
+                bwd()
+            ef.profile_enable(True)
+            t = time_region(torch, bwd, max(3, args.steps // 2))
+            pdx, ndx = ef.profile_read(0)
+            pdw, ndw = ef.profile_read(1)
+            ef.profile_enable(False)
+            times[(n_, d_)] = t
+            fl = sum(l.flops(k) for l, k in zip(layers, kk))
+            sweep.append(dict(r="%d/%d" % (n_, d_), k=kk, ms=t * 1e3, tflops=fl / t / 1e12,
+                              dx_kernel_ms=pdx / max(ndx, 1) * len(layers),
+                              dw_kernel_ms=(pdw / ndw * len(layers)) if ndw else 0.0))
+        full = times[(1, 1)]
+        for row, key in zip(sweep, fr):
+            row["speedup_vs_full"] = full / times[key]
+
+    out = dict(metric="QAT backward time + TFLOP/s per layer vs update fraction; speedup over full bwd",
+               value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
+               data="synthetic",
+               config=dict(workload="%s: %s, r=%d/%d, W%dA%d, dY %s-major" % (
+                   args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
+                   num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
+                   k=ks, step="fakequant(X,W) + select + restricted backward, every layer"),
+               roofline=roofline, sweep=sweep,
+               paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, num, den, cfg["a_bits"], w_bits)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,207 @@
+/*
+ * efqat.h -- C ABI of the EfQAT backward hot path for AMD MI355X (gfx950).
+ *
+ * EfQAT (arXiv 2411.11038) speeds up quantization-aware training by computing the
+ * weight gradient of a quantized linear / convolution layer only for the k most
+ * important output channels, while the input gradient stays complete (Alg. 1,
+ * Fig. 1).  This library is that layer-level path:
+ *
+ *   efqat_fakequant_fwd    Eq. 1-4   codes, straight-through clip masks, scales
+ *   efqat_channel_select   Eq. 6 + Top-K (Sec. 3.2), k = floor(r*C_out) (Sec. 3.4)
+ *   efqat_linear_bwd       Eq. 5 restricted as in Alg. 1, plus S_x / Z_x / S_w gradients
+ *   efqat_conv_bwd         the same two contractions with Eq. 8's shapes
+ *
+ * Conventions common to every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *     allocates nothing and keeps no state between calls.  Scratch memory comes in
+ *     through (ws, ws_bytes); the matching *_workspace_bytes() query gives the size
+ *     needed (a host-only computation).  ws must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue kernels on it and return without synchronising.  Two calls that share
+ *     a workspace must be ordered on one stream.
+ *   - Return value: 0 on success, a negative EFQAT_ERR_* otherwise.  Arguments are
+ *     checked on the host before anything is launched, so a failing call has touched
+ *     no device memory (EFQAT_ERR_HIP, a failed launch, excepted).
+ *   - Layouts are dense row-major with the last index fastest.  Linear weights are
+ *     W[C_out][C_in] (Y = X W^T, the convention the paper follows); conv activations
+ *     are NHWC, conv weights OHWI, conv output gradients [N][H_out][W_out][C_out].
+ *   - Clip masks are bit arrays: one row of ceil(cols/32) 32-bit words per tensor row;
+ *     bit (j % 32) of word (j / 32) is 1 when element j was NOT clipped, i.e. its
+ *     un-clamped integer code lies inside the closed code range (the gradient passes
+ *     straight through), 0 when it was clipped.  Unused high bits of the last word are 0.
+ *   - Rounding is to nearest, ties to even.  The integer code is decided on the
+ *     correctly rounded single-precision quotient x / scale.
+ */
+#ifndef EFQAT_H_
+#define EFQAT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EFQAT_VERSION 100
+
+/* element types of activation / gradient tensors */
+#define EFQAT_F32 0
+#define EFQAT_BF16 1
+
+/* quantizer kinds for efqat_fakequant_fwd */
+#define EFQAT_QUANT_ACT_PER_TENSOR_ASYM 0 /* Eq. 1 / Eq. 2 */
+#define EFQAT_QUANT_W_PER_ROW_SYM 1       /* Eq. 3 / Eq. 4 */
+
+/* layout of the output gradient handed to the backward calls */
+#define EFQAT_DY_TOKEN_MAJOR 0   /* [T][C_out]  (conv: [N][Ho][Wo][C_out]) */
+#define EFQAT_DY_CHANNEL_MAJOR 1 /* [C_out][T]  (conv: [C_out][N][Ho][Wo]): the rows of the
+                                    output-gradient matrix that Alg. 1 extracts are contiguous */
+
+#define EFQAT_OK 0
+#define EFQAT_ERR_NULL_PTR (-1)
+#define EFQAT_ERR_BAD_SHAPE (-2)
+#define EFQAT_ERR_BAD_BITS (-3)
+#define EFQAT_ERR_BAD_K (-4)
+#define EFQAT_ERR_BAD_LAYOUT (-5)
+#define EFQAT_ERR_WORKSPACE (-6)
+#define EFQAT_ERR_HIP (-7)
+#define EFQAT_ERR_BAD_DTYPE (-8)
+#define EFQAT_ERR_ALIGNMENT (-9)
+
+int efqat_version(void);
+/* Static string for an error code (never NULL). */
+const char* efqat_strerror(int code);
+
+/* Sec. 3.4: number of updated rows floor(r * C_out) for r = num/den, in integer
+ * arithmetic.  Returns -1 for c_out < 0, num < 0, den <= 0 or num > den. */
+int64_t efqat_k_from_ratio(int64_t c_out, int64_t num, int64_t den);
+
+/* ------------------------------------------------------------------ fake-quant forward
+ * Eq. 1 (mode ACT_PER_TENSOR_ASYM) or Eq. 3 with its bounds un-swapped, i.e.
+ * clamp(round(w/S_w), -(2^(b-1)-1), 2^(b-1)-1) (mode W_PER_ROW_SYM), over a [rows][cols]
+ * tensor.  For a conv weight pass rows = C_out, cols = KH*KW*C_in.
+ *
+ *   x           in   [rows][cols], dtype F32 or BF16
+ *   bits        2..8
+ *   init_minmax 1: first compute the quantizer parameters from the data -- Eq. 2 with
+ *                  [alpha, beta] = [min x, max x] (one S_x, Z_x), or Eq. 4 per row -- and
+ *                  write them to scale / zero_point; 0: read them as given.
+ *                  A zero range (max == min, all-zero row) yields scale 1.
+ *   scale       in/out  float[1] (act) or float[rows] (weights)
+ *   zero_point  in/out  float[1] (act; may be non-integer after training: the forward
+ *                  uses round(Z_x)); ignored (may be NULL) for weights, Z_w = 0
+ *   codes       out  uint8 [rows][cols] (act) or int8 [rows][cols] (weights; b-bit values
+ *                  are stored one per byte)
+ *   clip_bits   out  uint32 [rows][ceil(cols/32)]
+ *   xq          out, nullable  bf16 [rows][cols] de-quantised values S*(code - Z)
+ */
+size_t efqat_fakequant_fwd_workspace_bytes(int64_t rows, int64_t cols, int mode);
+int efqat_fakequant_fwd(const void* x, int dtype, int64_t rows, int64_t cols, int mode, int bits,
+                        int init_minmax, float* scale, float* zero_point, void* codes,
+                        uint32_t* clip_bits, void* xq, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ channel select
+ * Eq. 6 with one block per output channel, I[c] = mean_j |w[c][j]| over `block` master
+ * weights (C_in, or KH*KW*C_in for a conv), accumulated in double precision; then the
+ * Top-K of Sec. 3.2: the k channels with the largest I, equal scores going to the lower
+ * index, written in ascending index order.
+ *
+ *   w       in   float [c_out][block]
+ *   k       0..c_out  (0 is valid: nothing is written to idx)
+ *   scores  out, nullable  double[c_out]
+ *   idx     out  int32[k]  (may be NULL when k == 0)
+ */
+size_t efqat_channel_select_workspace_bytes(int64_t c_out);
+int efqat_channel_select(const float* w, int64_t c_out, int64_t block, int64_t k, double* scores,
+                         int32_t* idx, void* ws, size_t ws_bytes, void* stream);
+
+/* EfQAT-CWPN (Table 2): one Top-K over the channels of several layers together.
+ *   scores      in   double[total] = the per-layer score arrays of efqat_channel_select,
+ *                    concatenated in layer order (device)
+ *   layer_off   in   int64[n_layers+1] (device), ascending prefix offsets into scores,
+ *                    layer_off[0] = 0, layer_off[n_layers] = total
+ *   k_total     0..total
+ *   idx         out  int32[k_total]: selected channels, layer by layer, ascending channel
+ *                    index within each layer (index local to its layer)
+ *   k_per_layer out  int32[n_layers] (device): how many channels of each layer were selected
+ * Ties go to the earlier layer, then the lower channel.  EfQAT-LWPN is the same call on one
+ * score per layer (n_layers = total). */
+size_t efqat_network_select_workspace_bytes(int64_t total);
+int efqat_network_select(const double* scores, const int64_t* layer_off, int64_t n_layers,
+                         int64_t total, int64_t k_total, int32_t* idx, int32_t* k_per_layer,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ linear backward
+ * Backward step of Alg. 1 for one layer Y = X_q W_q^T, X_q = S_x (x_codes - Z_x),
+ * W_q[c][:] = S_w[c] w_codes[c][:]:
+ *
+ *   dX      = (dY W_q) with clipped activations zeroed            (Eq. 5 left; all channels)
+ *   dW[id]  = (dY[:, id]^T X_q) with clipped weights zeroed       (Eq. 5 right, rows id only)
+ *   dS_w[id], dS_x, dZ_x: gradients of the quantizer parameters through Eq. 1 / Eq. 3 with
+ *   d round(u)/du = 1:  in range  d X_q/d S_x = round(x/S_x) - x/S_x, d X_q/d Z_x = 0;
+ *   clipped  d X_q/d S_x = code - Z_x, d X_q/d Z_x = -S_x; weights alike with Z_w = 0.
+ *   S_w gradients exist only for the updated rows (Sec. 3.2, quantization granularity).
+ *
+ * The products run on bf16 matrix cores with fp32 accumulation: dY and W_q are rounded
+ * to bf16 (x_codes - Z_x is exact in bf16).
+ *
+ *   dy        in  [T][c_out] or [c_out][T] per dy_layout, dtype dy_dtype
+ *   x_codes   in  uint8 [T][c_in];   x_clip  in  uint32 [T][ceil(c_in/32)]
+ *   x         in  [T][c_in] original activations (dtype x_dtype), for dS_x
+ *   s_x, z_x  in  float[1] each, device
+ *   w_codes   in  int8 [c_out][c_in]; w_clip in uint32 [c_out][ceil(c_in/32)]
+ *   w         in  float [c_out][c_in] master weights, for dS_w;  s_w in float[c_out]
+ *   idx       in  int32[k], strictly ascending, each in [0, c_out) (not checked on the
+ *                 device: out-of-range entries are the caller's error); NULL iff k == 0
+ *   dx        out [T][c_in], dtype dx_dtype
+ *   dw        out float: scatter == 0 -> [k][c_in], row m is channel idx[m];
+ *                        scatter == 1 -> [c_out][c_in], only rows idx are written
+ *   ds_w      out float: [k] (scatter == 0) or [c_out] with only entries idx written
+ *   ds_x,dz_x out float[1] each
+ *   dw / ds_w may be NULL when k == 0 (dX, dS_x, dZ_x are still produced).
+ */
+size_t efqat_linear_bwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out, int64_t k,
+                                        int dy_dtype, int dy_layout);
+int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                     int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
+                     int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
+                     const uint32_t* w_clip, const float* w, const float* s_w, const int32_t* idx,
+                     int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
+                     float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ conv backward
+ * Same as efqat_linear_bwd for Y[n][ho][wo][co] = sum_{kh,kw,ci}
+ * X_q[n][ho*stride+kh-pad][wo*stride+kw-pad][ci] * W_q[co][kh][kw][ci] (zero outside the
+ * image), the contraction sizes of Eq. 8.  x_codes/x/dx are [N][H][W][c_in]; x_clip has one
+ * bit row per pixel ([N*H*W][ceil(c_in/32)]); w_codes/w/dw are [..][KH][KW][c_in] with
+ * w_clip rows of ceil(KH*KW*c_in/32) words; dy is [N][Ho][Wo][c_out] (token major) or
+ * [c_out][N][Ho][Wo] (channel major), Ho = (H + 2 pad - KH)/stride + 1.
+ */
+size_t efqat_conv_bwd_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
+                                      int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                                      int64_t k, int dy_dtype, int dy_layout);
+int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                   int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride,
+                   int64_t pad, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
+                   int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
+                   const uint32_t* w_clip, const float* w, const float* s_w, const int32_t* idx,
+                   int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
+                   float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ kernel timing (benchmarks)
+ * The two products of Eq. 5 dominate the backward pass; to report them against the matrix-core
+ * roofline a benchmark can have every product kernel bracketed by HIP events on the stream it is
+ * launched on.  This is the only process-wide state of the library; it is off by default and not
+ * thread-safe.
+ *   efqat_profile_enable(on)  on != 0 starts a new measurement (counters reset), 0 stops it.
+ *                             At most 4096 launches per product are recorded.
+ *   efqat_profile_read(which, total_ms, launches)  which = 0: input-gradient product (dX),
+ *                             1: weight-gradient product (dW).  Waits for the recorded events
+ *                             (host pointers out: summed kernel time in ms, number of launches). */
+int efqat_profile_enable(int on);
+int efqat_profile_read(int which, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EFQAT_H_ */

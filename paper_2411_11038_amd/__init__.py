@@ -1,0 +1,12 @@
+"""Python binding of libefqat.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device
+memory and streams, nothing else), passes their pointers through the C ABI declared in
+include/efqat.h and returns the library's outputs.  There is no CPU fallback: without the
+built library (or without a GPU for the compute calls) these functions raise.
+"""
+from .binding import (  # noqa: F401
+    EfqatError, lib, lib_path, k_from_ratio, fakequant_fwd, channel_select, network_select,
+    linear_bwd, conv_bwd, F32, BF16, ACT_PER_TENSOR_ASYM, W_PER_ROW_SYM, DY_TOKEN_MAJOR,
+    DY_CHANNEL_MAJOR, EXPORTS, profile_enable, profile_read,
+)

@@ -1,0 +1,261 @@
+"""ctypes loader and thin wrappers for libefqat.so (see include/efqat.h for the contract)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+F32, BF16 = 0, 1
+ACT_PER_TENSOR_ASYM, W_PER_ROW_SYM = 0, 1
+DY_TOKEN_MAJOR, DY_CHANNEL_MAJOR = 0, 1
+
+EXPORTS = [
+    "efqat_version", "efqat_strerror", "efqat_k_from_ratio",
+    "efqat_fakequant_fwd_workspace_bytes", "efqat_fakequant_fwd",
+    "efqat_channel_select_workspace_bytes", "efqat_channel_select",
+    "efqat_network_select_workspace_bytes", "efqat_network_select",
+    "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
+    "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd",
+    "efqat_profile_enable", "efqat_profile_read",
+]
+
+
+class EfqatError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib().efqat_strerror(code).decode()} ({code})")
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "lib", "libefqat.so")
+
+
+_LIB = None
+
+
+def lib():
+    """Load libefqat.so (built by paper_2411_11038_amd/build.py).  Raises if it is missing."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not built: run `python -m paper_2411_11038_amd.build`")
+    L = C.CDLL(path)
+    i64, sz, vp, ci = C.c_int64, C.c_size_t, C.c_void_p, C.c_int
+    L.efqat_version.restype = ci
+    L.efqat_strerror.restype = C.c_char_p
+    L.efqat_strerror.argtypes = [ci]
+    L.efqat_k_from_ratio.restype = i64
+    L.efqat_k_from_ratio.argtypes = [i64, i64, i64]
+    L.efqat_fakequant_fwd_workspace_bytes.restype = sz
+    L.efqat_fakequant_fwd_workspace_bytes.argtypes = [i64, i64, ci]
+    L.efqat_fakequant_fwd.restype = ci
+    L.efqat_fakequant_fwd.argtypes = [vp, ci, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.efqat_channel_select_workspace_bytes.restype = sz
+    L.efqat_channel_select_workspace_bytes.argtypes = [i64]
+    L.efqat_channel_select.restype = ci
+    L.efqat_channel_select.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.efqat_network_select_workspace_bytes.restype = sz
+    L.efqat_network_select_workspace_bytes.argtypes = [i64]
+    L.efqat_network_select.restype = ci
+    L.efqat_network_select.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.efqat_linear_bwd_workspace_bytes.restype = sz
+    L.efqat_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+    L.efqat_linear_bwd.restype = ci
+    L.efqat_linear_bwd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
+                                   + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_conv_bwd_workspace_bytes.restype = sz
+    L.efqat_conv_bwd_workspace_bytes.argtypes = [i64] * 10 + [ci, ci]
+    L.efqat_conv_bwd.restype = ci
+    L.efqat_conv_bwd.argtypes = ([vp, ci, ci] + [i64] * 9 + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
+                                 + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_profile_enable.restype = ci
+    L.efqat_profile_enable.argtypes = [ci]
+    L.efqat_profile_read.restype = ci
+    L.efqat_profile_read.argtypes = [ci, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    _LIB = L
+    return L
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _p(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(nbytes: int, like: torch.Tensor) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise EfqatError(rc, where)
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().efqat_profile_enable(int(bool(on))), "efqat_profile_enable")
+
+
+def profile_read(which: int):
+    """(total kernel ms, launches) of the dX (which=0) or dW (which=1) product since profile_enable(True)."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(lib().efqat_profile_read(which, C.byref(ms), C.byref(n)), "efqat_profile_read")
+    return ms.value, n.value
+
+
+def k_from_ratio(c_out: int, num: int, den: int) -> int:
+    return int(lib().efqat_k_from_ratio(c_out, num, den))
+
+
+def fakequant_fwd(x: torch.Tensor, mode: int, bits: int, init_minmax: bool = True, scale=None,
+                  zero_point=None, want_xq: bool = False, ws=None, out=None):
+    """Returns dict(codes, clip_bits, scale, zero_point, xq).  x is [rows, cols] (leading dims are
+    flattened into rows; a conv weight [C_out, KH, KW, C_in] is rows = C_out).  `out` may carry
+    preallocated codes / clip_bits / xq tensors."""
+    L = lib()
+    cols = x.shape[-1] if mode == ACT_PER_TENSOR_ASYM else x[0].numel()
+    rows = x.numel() // cols
+    dev = x.device
+    out = out or {}
+    if scale is None:
+        scale = out.get("scale")
+    if scale is None:
+        scale = torch.empty(1 if mode == ACT_PER_TENSOR_ASYM else rows, dtype=torch.float32, device=dev)
+    if zero_point is None:
+        zero_point = out.get("zero_point")
+    if zero_point is None and mode == ACT_PER_TENSOR_ASYM:
+        zero_point = torch.empty(1, dtype=torch.float32, device=dev)
+    codes = out.get("codes")
+    if codes is None:
+        codes = torch.empty(x.shape, dtype=torch.uint8 if mode == ACT_PER_TENSOR_ASYM else torch.int8, device=dev)
+    clip = out.get("clip_bits")
+    if clip is None:
+        clip = torch.empty((rows, (cols + 31) // 32), dtype=torch.int32, device=dev)
+    xq = out.get("xq")
+    if xq is None and want_xq:
+        xq = torch.empty(x.shape, dtype=torch.bfloat16, device=dev)
+    if ws is None:
+        ws = _ws(L.efqat_fakequant_fwd_workspace_bytes(rows, cols, mode), x)
+    rc = L.efqat_fakequant_fwd(_p(x), _dt(x), rows, cols, mode, bits, int(bool(init_minmax)), _p(scale),
+                               _p(zero_point), _p(codes), _p(clip), _p(xq), _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_fakequant_fwd")
+    return dict(codes=codes, clip_bits=clip, scale=scale, zero_point=zero_point, xq=xq)
+
+
+def channel_select(w: torch.Tensor, k: int, want_scores: bool = True, ws=None, out=None):
+    """Returns (idx int32[k], scores float64[c_out] or None).  w is [c_out, ...] fp32."""
+    L = lib()
+    c_out = w.shape[0]
+    block = w[0].numel()
+    out = out or {}
+    scores = out.get("scores")
+    if scores is None and want_scores:
+        scores = torch.empty(c_out, dtype=torch.float64, device=w.device)
+    idx = out.get("idx")
+    if idx is None:
+        idx = torch.empty(max(k, 0), dtype=torch.int32, device=w.device)
+    if ws is None:
+        ws = _ws(L.efqat_channel_select_workspace_bytes(c_out), w)
+    rc = L.efqat_channel_select(_p(w), c_out, block, k, _p(scores), _p(idx) if k > 0 else None, _p(ws),
+                                ws.numel(), _stream())
+    _check(rc, "efqat_channel_select")
+    return idx, scores
+
+
+def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, ws=None):
+    """Returns (idx int32[k_total] of layer-local channel indices, k_per_layer int32[n_layers])."""
+    L = lib()
+    total = scores.numel()
+    n_layers = layer_off.numel() - 1
+    idx = torch.empty(max(k_total, 0), dtype=torch.int32, device=scores.device)
+    kpl = torch.empty(n_layers, dtype=torch.int32, device=scores.device)
+    if ws is None:
+        ws = _ws(L.efqat_network_select_workspace_bytes(total), scores)
+    rc = L.efqat_network_select(_p(scores), _p(layer_off), n_layers, total, k_total,
+                                _p(idx) if k_total > 0 else None, _p(kpl), _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_network_select")
+    return idx, kpl
+
+
+def _bwd_outputs(x, w, k, dx_dtype, scatter):
+    dev = x.device
+    c_out = w.shape[0]
+    dx = torch.empty(x.shape, dtype=dx_dtype, device=dev)
+    if scatter:
+        dw = torch.zeros(w.shape, dtype=torch.float32, device=dev)
+        ds_w = torch.zeros(c_out, dtype=torch.float32, device=dev)
+    else:
+        dw = torch.empty((k,) + tuple(w.shape[1:]), dtype=torch.float32, device=dev)
+        ds_w = torch.empty(k, dtype=torch.float32, device=dev)
+    ds_x = torch.empty(1, dtype=torch.float32, device=dev)
+    dz_x = torch.empty(1, dtype=torch.float32, device=dev)
+    return dx, dw, ds_w, ds_x, dz_x
+
+
+def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, dy_layout=DY_TOKEN_MAJOR,
+               dx_dtype=None, scatter=False, ws=None, out=None):
+    """Backward of one quantized linear layer restricted to the rows idx.  Returns
+    dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys)."""
+    L = lib()
+    T, c_in = x_codes.shape
+    c_out = w_codes.shape[0]
+    k = 0 if idx is None else int(idx.numel())
+    dx_dtype = dx_dtype or (torch.bfloat16 if dy.dtype == torch.bfloat16 else torch.float32)
+    if out is None:
+        dx, dw, ds_w, ds_x, dz_x = _bwd_outputs(x, w, k, dx_dtype, scatter)
+    else:
+        dx, dw, ds_w, ds_x, dz_x = out["dx"], out["dw"], out["ds_w"], out["ds_x"], out["dz_x"]
+    need = L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, _dt(dy), dy_layout)
+    if ws is None:
+        ws = _ws(need, x)
+    rc = L.efqat_linear_bwd(_p(dy), _dt(dy), dy_layout, T, c_in, c_out, _p(x_codes), _p(x_clip), _p(x), _dt(x),
+                            _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
+                            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
+                            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x), _p(ws),
+                            ws.numel(), _stream())
+    _check(rc, "efqat_linear_bwd")
+    return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)
+
+
+def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, stride=1, pad=0,
+             dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None):
+    """Backward of one quantized conv layer (x NHWC, w OHWI) restricted to output channels idx."""
+    L = lib()
+    N, H, W, c_in = x_codes.shape
+    c_out, KH, KW, _ = w_codes.shape
+    k = 0 if idx is None else int(idx.numel())
+    dx_dtype = dx_dtype or (torch.bfloat16 if dy.dtype == torch.bfloat16 else torch.float32)
+    if out is None:
+        dx, dw, ds_w, ds_x, dz_x = _bwd_outputs(x, w, k, dx_dtype, scatter)
+    else:
+        dx, dw, ds_w, ds_x, dz_x = out["dx"], out["dw"], out["ds_w"], out["ds_x"], out["dz_x"]
+    need = L.efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, _dt(dy), dy_layout)
+    if ws is None:
+        ws = _ws(need, x)
+    rc = L.efqat_conv_bwd(_p(dy), _dt(dy), dy_layout, N, H, W, c_in, c_out, KH, KW, stride, pad, _p(x_codes),
+                          _p(x_clip), _p(x), _dt(x), _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
+                          _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
+                          int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x), _p(ws), ws.numel(),
+                          _stream())
+    _check(rc, "efqat_conv_bwd")
+    return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)

@@ -1,0 +1,446 @@
+// EfQAT backward of one quantized layer (Alg. 1 backward step, Eq. 5): operand preparation,
+// the two MFMA contractions, and the fused / second-pass epilogues that apply the straight-through
+// clip masks and reduce the quantizer-parameter gradients.
+#include "common.hpp"
+
+namespace efqat {
+
+// ------------------------------------------------------------------------------------------------
+// element readers
+template <typename T> __device__ __forceinline__ float rd(const T* p, int64_t i);
+template <> __device__ __forceinline__ float rd<float>(const float* p, int64_t i) { return p[i]; }
+template <> __device__ __forceinline__ float rd<bf16_t>(const bf16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+template <> __device__ __forceinline__ float rd<int8_t>(const int8_t* p, int64_t i) { return (float)p[i]; }
+template <> __device__ __forceinline__ float rd<uint8_t>(const uint8_t* p, int64_t i) { return (float)p[i]; }
+
+// Tiled transpose with conversion to bf16:
+//   out[j][i] = bf16( (in[i][cm(j)] - sub) * rs(i) ),  i < R, j < Cn;  out[j][i] = 0 for R <= i < i_pad.
+//   cm(j) = colmap ? colmap[j] : j     (gather of selected channels when dY is token major)
+//   rs(i) = rowscale ? rowscale[i] : 1 (per-output-channel weight scale)
+//   sub   = subz ? round(subz[0]) : 0  (activation zero point)
+// `out` row j starts at out + j*ldo + out_off (ldo = pitch in elements).
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in, int64_t ld_in, int64_t R,
+                                                        int64_t Cn, const int32_t* __restrict__ colmap,
+                                                        const float* __restrict__ rowscale,
+                                                        const float* __restrict__ subz, bf16_t* __restrict__ out,
+                                                        int64_t ldo, int64_t out_off, int64_t i_pad) {
+  __shared__ bf16_t tile[64][66];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
+  const float sub = subz ? rintf(subz[0]) : 0.0f;
+  const int64_t j = j0 + tx;
+  const int64_t jc = (j < Cn) ? (colmap ? (int64_t)colmap[j] : j) : 0;
+#pragma unroll 4
+  for (int rr = 0; rr < 16; ++rr) {
+    const int li = ty + 4 * rr;
+    const int64_t i = i0 + li;
+    float v = 0.0f;
+    if (i < R && j < Cn) {
+      v = rd<T>(in, i * ld_in + jc) - sub;
+      if (rowscale) v *= rowscale[i];
+    }
+    tile[li][tx] = f32_to_bf16(v);
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (int rr = 0; rr < 16; ++rr) {
+    const int lj = ty + 4 * rr;
+    const int64_t jo = j0 + lj, io = i0 + tx;
+    if (jo < Cn && io < i_pad) out[jo * ldo + out_off + io] = tile[tx][lj];
+  }
+}
+
+// Row-wise cast/copy to bf16 with zero-padded pitch: out[m][j] = bf16(in[rm(m)][j]), j < Cn; 0 up to ldo.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rows_bf16(const T* __restrict__ in, int64_t ld_in, int64_t R, int64_t Cn,
+                                                   const int32_t* __restrict__ rowmap, bf16_t* __restrict__ out,
+                                                   int64_t ldo) {
+  const int64_t total = R * ldo;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t m = e / ldo, j = e - m * ldo;
+    float v = 0.0f;
+    if (j < Cn) v = rd<T>(in, (rowmap ? (int64_t)rowmap[m] : m) * ld_in + j);
+    out[e] = f32_to_bf16(v);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// conv helpers (explicit im2col into workspace; the contractions then run on the same GEMM core)
+struct ConvGeom {
+  int N, H, W, c_in, c_out, KH, KW, stride, pad, Ho, Wo;
+};
+
+// dX operand: colA[(n,h,w)][tap*ldc + co] = dYn[(n,ho,wo)][co] with ho*stride + kh - pad = h (else 0).
+// dYn is the token-major bf16 copy of dY with pitch ldc (multiple of 8).
+__global__ __launch_bounds__(256) void k_im2col_dy(const bf16_t* __restrict__ dyn, int64_t ldc, ConvGeom g,
+                                                   bf16_t* __restrict__ col) {
+  const int64_t ch = ldc >> 3;                        // 16-byte chunks per tap
+  const int taps = g.KH * g.KW;
+  const int64_t total = (int64_t)g.N * g.H * g.W * taps * ch;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t c8 = e % ch;
+    int64_t r = e / ch;
+    const int tap = (int)(r % taps);
+    r /= taps;                                        // pixel index (n,h,w)
+    const int w = (int)(r % g.W);
+    const int h = (int)((r / g.W) % g.H);
+    const int n = (int)(r / ((int64_t)g.W * g.H));
+    const int kh = tap / g.KW, kw = tap % g.KW;
+    const int hn = h + g.pad - kh, wn = w + g.pad - kw;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (hn >= 0 && wn >= 0 && hn % g.stride == 0 && wn % g.stride == 0) {
+      const int ho = hn / g.stride, wo = wn / g.stride;
+      if (ho < g.Ho && wo < g.Wo)
+        v = *reinterpret_cast<const uint4*>(dyn + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * ldc + c8 * 8);
+    }
+    *reinterpret_cast<uint4*>(col + (r * taps + tap) * ldc + c8 * 8) = v;
+  }
+}
+
+// dW operand: colXT[(tap,ci)][(n,ho,wo)] = x_codes[n][ho*s+kh-p][wo*s+kw-p][ci] - round(Z_x)  (0 outside the
+// image: the padding is zero in the de-quantised domain).  Tiled transpose, blockIdx.z = tap.
+__global__ __launch_bounds__(256) void k_im2colT_x(const uint8_t* __restrict__ xc, const float* __restrict__ z_x,
+                                                   ConvGeom g, bf16_t* __restrict__ out, int64_t ldk) {
+  __shared__ bf16_t tile[64][66];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int tap = blockIdx.z, kh = tap / g.KW, kw = tap % g.KW;
+  const int64_t Kp = (int64_t)g.N * g.Ho * g.Wo;
+  const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
+  const float z = rintf(z_x[0]);
+  const int64_t j = j0 + tx;
+#pragma unroll 4
+  for (int rr = 0; rr < 16; ++rr) {
+    const int li = ty + 4 * rr;
+    const int64_t i = i0 + li;                        // (n,ho,wo)
+    float v = 0.0f;
+    if (i < Kp && j < g.c_in) {
+      const int wo = (int)(i % g.Wo);
+      const int ho = (int)((i / g.Wo) % g.Ho);
+      const int n = (int)(i / ((int64_t)g.Wo * g.Ho));
+      const int h = ho * g.stride + kh - g.pad, w = wo * g.stride + kw - g.pad;
+      if (h >= 0 && h < g.H && w >= 0 && w < g.W)
+        v = (float)xc[(((int64_t)n * g.H + h) * g.W + w) * g.c_in + j] - z;
+    }
+    tile[li][tx] = (bf16_t)(__float_as_uint(v) >> 16);  // small integers: exact
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (int rr = 0; rr < 16; ++rr) {
+    const int lj = ty + 4 * rr;
+    const int64_t jo = j0 + lj, io = i0 + tx;
+    if (jo < g.c_in && io < ldk) out[((int64_t)tap * g.c_in + jo) * ldk + io] = tile[tx][lj];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dS_x, dZ_x: ordered sum of the per-block partials written by the dX epilogue.
+__global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, int64_t n,
+                                                      float* __restrict__ ds_x, float* __restrict__ dz_x) {
+  double a = 0.0, b = 0.0;
+  for (int64_t i = threadIdx.x; i < n; i += 256) { a += (double)part[2 * i]; b += (double)part[2 * i + 1]; }
+  a = wave_sum(a); b = wave_sum(b);
+  __shared__ double sa[4], sb[4];
+  if ((threadIdx.x & 63) == 0) { sa[threadIdx.x >> 6] = a; sb[threadIdx.x >> 6] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ds_x[0] = (float)((sa[0] + sa[1]) + (sa[2] + sa[3]));
+    dz_x[0] = (float)((sb[0] + sb[1]) + (sb[2] + sb[3]));
+  }
+}
+
+// Second pass of the restricted weight gradient: ordered split-K sum, S_x scaling, straight-through mask
+// of the weight quantizer and the per-row scale gradient
+//   dW[c][j] = in range ? dW_q : 0,  dS_w[c] = sum_j dW_q * (in range ? code - w/S_w : code),  c = idx[m].
+__global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ part, int S, int64_t k, int64_t ncols,
+                                                   const float* __restrict__ s_x, const int8_t* __restrict__ w_codes,
+                                                   const uint32_t* __restrict__ w_clip, const float* __restrict__ w,
+                                                   const float* __restrict__ s_w, const int32_t* __restrict__ idx,
+                                                   float* __restrict__ dw, int scatter, float* __restrict__ ds_w) {
+  const int64_t m = blockIdx.x;
+  const int64_t c = idx[m];
+  const int64_t wpr = (ncols + 31) >> 5;
+  const float sx = s_x[0];
+  const float sw = s_w[c];
+  const int64_t orow = scatter ? c : m;
+  float acc = 0.0f;
+  for (int64_t j = threadIdx.x; j < ncols; j += 256) {
+    float a = 0.0f;
+    for (int s = 0; s < S; ++s) a += part[((int64_t)s * k + m) * ncols + j];
+    const float dwq = sx * a;
+    const bool inr = (w_clip[c * wpr + (j >> 5)] >> (j & 31)) & 1u;
+    const float code = (float)w_codes[c * ncols + j];
+    const float gs = inr ? (code - w[c * ncols + j] / sw) : code;
+    acc += dwq * gs;
+    dw[orow * ncols + j] = inr ? dwq : 0.0f;
+  }
+  acc = wave_sum(acc);
+  __shared__ float red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) ds_w[orow] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// ------------------------------------------------------------------------------------------------
+static inline unsigned grid1d(int64_t total, int per_block = 256) {
+  int64_t b = ceil_div(total, per_block);
+  if (b > 256 * 64) b = 256 * 64;
+  if (b < 1) b = 1;
+  return (unsigned)b;
+}
+
+template <typename T>
+static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, const int32_t* colmap,
+                             const float* rowscale, const float* subz, bf16_t* out, int64_t ldo, int64_t out_off,
+                             int64_t i_pad, hipStream_t st) {
+  dim3 grid((unsigned)ceil_div(i_pad, 64), (unsigned)ceil_div(Cn, 64));
+  if (grid.y > 65535) return EFQAT_ERR_BAD_SHAPE;
+  hipLaunchKernelGGL((k_transpose_bf16<T>), grid, dim3(256), 0, st, in, ld_in, R, Cn, colmap, rowscale, subz, out,
+                     ldo, out_off, i_pad);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+// Plan of one backward call: sizes of every workspace slice (shared by the size query and the call).
+struct BwdPlan {
+  int64_t Mx;      // rows of dX as a matrix (T, or N*H*W)
+  int64_t Kx;      // contraction length of the dX product (padded C_out, times taps for conv)
+  int64_t Nw;      // columns of dW as a matrix (C_in, or KH*KW*C_in)
+  int64_t Tw;      // contraction length of the dW product (T, or N*Ho*Wo)
+  int64_t ldc;     // C_out rounded up to 8
+  int64_t ldt;     // Tw rounded up to 8
+  bool need_dyn;   // token-major bf16 copy of dY needed
+  bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
+  int split_k;
+  size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, total;
+};
+
+static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, int taps, int64_t k,
+                         int dy_dtype, int dy_layout, bool im2col) {
+  BwdPlan p{};
+  p.Mx = T_in; p.Tw = T_out; p.Nw = (int64_t)taps * c_in;
+  p.ldc = round_up(c_out, 8); p.ldt = round_up(T_out, 8);
+  p.Kx = (int64_t)taps * p.ldc;
+  const bool direct_tok = dy_layout == EFQAT_DY_TOKEN_MAJOR && dy_dtype == EFQAT_BF16 && (c_out % 8) == 0;
+  p.need_dyn = !direct_tok;
+  const bool direct_rows = dy_layout == EFQAT_DY_CHANNEL_MAJOR && dy_dtype == EFQAT_BF16 && (T_out % 8) == 0;
+  p.need_sel = k > 0 && !direct_rows;
+  p.split_k = k > 0 ? gemm_pick_split_k(k, p.Nw, p.ldt) : 1;
+  WsCarver cv(nullptr);
+  p.b_wqT = (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
+  p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
+  p.b_colA = im2col ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
+  p.b_part_dx = (size_t)gemm_nt_grid_mn(p.Mx, c_in) * 2 * sizeof(float); cv.take(p.b_part_dx);
+  p.b_xcT = k > 0 ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
+  p.b_sel = p.need_sel ? (size_t)k * p.ldt * 2 : 0; cv.take(p.b_sel);
+  p.b_part_dw = k > 0 ? (size_t)p.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
+  p.total = cv.off;
+  return p;
+}
+
+struct BwdIo {
+  const void* dy; int dy_dtype; int dy_layout;
+  const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype; const float* s_x; const float* z_x;
+  const int8_t* w_codes; const uint32_t* w_clip; const float* w; const float* s_w; const int32_t* idx; int64_t k;
+  void* dx; int dx_dtype; float* dw; int scatter; float* ds_w; float* ds_x; float* dz_x;
+};
+
+// Shared driver.  For conv, T_in = N*H*W input pixels, T_out = N*Ho*Wo output pixels; for linear both are T.
+static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, const ConvGeom* cg,
+                   void* ws, hipStream_t st) {
+  const int taps = cg ? cg->KH * cg->KW : 1;
+  // a 1x1 / stride 1 / no-padding convolution is a linear layer over pixels: no im2col needed
+  const bool im2col = cg != nullptr && !(taps == 1 && cg->stride == 1 && cg->pad == 0);
+  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col);
+  WsCarver cv(ws);
+  bf16_t* wqT = (bf16_t*)cv.take(p.b_wqT);
+  bf16_t* dyn = (bf16_t*)cv.take(p.b_dyn);
+  bf16_t* colA = (bf16_t*)cv.take(p.b_colA);
+  float* part_dx = (float*)cv.take(p.b_part_dx);
+  bf16_t* xcT = (bf16_t*)cv.take(p.b_xcT);
+  bf16_t* sel = (bf16_t*)cv.take(p.b_sel);
+  float* part_dw = (float*)cv.take(p.b_part_dw);
+  int rc;
+
+  // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
+  for (int tap = 0; tap < taps; ++tap) {
+    rc = transpose_to_bf16<int8_t>(io.w_codes + (int64_t)tap * c_in, (int64_t)taps * c_in, c_out, c_in, nullptr,
+                                   io.s_w, nullptr, wqT, p.Kx, (int64_t)tap * p.ldc, p.ldc, st);
+    if (rc) return rc;
+  }
+
+  // ---- dY as a token-major bf16 matrix [T_out][ldc] (A operand of the dX product)
+  const bf16_t* dy_tok = (const bf16_t*)io.dy;
+  if (p.need_dyn) {
+    if (io.dy_layout == EFQAT_DY_TOKEN_MAJOR) {
+      if (io.dy_dtype == EFQAT_F32)
+        hipLaunchKernelGGL((k_rows_bf16<float>), dim3(grid1d(T_out * p.ldc)), dim3(256), 0, st, (const float*)io.dy,
+                           c_out, T_out, c_out, nullptr, dyn, p.ldc);
+      else
+        hipLaunchKernelGGL((k_rows_bf16<bf16_t>), dim3(grid1d(T_out * p.ldc)), dim3(256), 0, st,
+                           (const bf16_t*)io.dy, c_out, T_out, c_out, nullptr, dyn, p.ldc);
+      EFQAT_LAUNCH_CHECK();
+    } else {
+      // channel-major [c_out][T_out] -> [T_out][ldc]
+      if (io.dy_dtype == EFQAT_F32)
+        rc = transpose_to_bf16<float>((const float*)io.dy, T_out, c_out, T_out, nullptr, nullptr, nullptr, dyn,
+                                      p.ldc, 0, p.ldc, st);
+      else
+        rc = transpose_to_bf16<bf16_t>((const bf16_t*)io.dy, T_out, c_out, T_out, nullptr, nullptr, nullptr, dyn,
+                                       p.ldc, 0, p.ldc, st);
+      if (rc) return rc;
+    }
+    dy_tok = dyn;
+  }
+
+  // ---- dX product with the fused straight-through / qparam epilogue
+  const bf16_t* A = dy_tok;
+  int64_t lda = p.ldc;
+  if (im2col) {
+    hipLaunchKernelGGL(k_im2col_dy, dim3(grid1d(T_in * taps * (p.ldc / 8))), dim3(256), 0, st, dy_tok, p.ldc, *cg,
+                       colA);
+    EFQAT_LAUNCH_CHECK();
+    A = colA; lda = p.Kx;
+  }
+  GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
+  rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, 1, nullptr, &epi, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx, gemm_nt_grid_mn(p.Mx, c_in), io.ds_x,
+                     io.dz_x);
+  EFQAT_LAUNCH_CHECK();
+
+  if (io.k == 0) return EFQAT_OK;
+
+  // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16
+  if (im2col) {
+    dim3 grid((unsigned)ceil_div(p.ldt, 64), (unsigned)ceil_div(c_in, 64), (unsigned)taps);
+    hipLaunchKernelGGL(k_im2colT_x, grid, dim3(256), 0, st, io.x_codes, io.z_x, *cg, xcT, p.ldt);
+    EFQAT_LAUNCH_CHECK();
+  } else {
+    rc = transpose_to_bf16<uint8_t>(io.x_codes, c_in, T_out, c_in, nullptr, nullptr, io.z_x, xcT, p.ldt, 0, p.ldt, st);
+    if (rc) return rc;
+  }
+
+  // ---- A operand of the dW product: the selected rows of dY^T
+  const bf16_t* Aw; int64_t ldaw; const int32_t* a_rows;
+  if (!p.need_sel) {               // channel-major bf16: gather fused into the GEMM's A-tile loads
+    Aw = (const bf16_t*)io.dy; ldaw = T_out; a_rows = io.idx;
+  } else if (io.dy_layout == EFQAT_DY_CHANNEL_MAJOR) {
+    if (io.dy_dtype == EFQAT_F32)
+      hipLaunchKernelGGL((k_rows_bf16<float>), dim3(grid1d(io.k * p.ldt)), dim3(256), 0, st, (const float*)io.dy,
+                         T_out, io.k, T_out, io.idx, sel, p.ldt);
+    else
+      hipLaunchKernelGGL((k_rows_bf16<bf16_t>), dim3(grid1d(io.k * p.ldt)), dim3(256), 0, st, (const bf16_t*)io.dy,
+                         T_out, io.k, T_out, io.idx, sel, p.ldt);
+    EFQAT_LAUNCH_CHECK();
+    Aw = sel; ldaw = p.ldt; a_rows = nullptr;
+  } else {
+    // token major: sel[m][t] = dY[t][idx[m]]
+    if (io.dy_dtype == EFQAT_F32)
+      rc = transpose_to_bf16<float>((const float*)io.dy, c_out, T_out, io.k, io.idx, nullptr, nullptr, sel, p.ldt, 0,
+                                    p.ldt, st);
+    else
+      rc = transpose_to_bf16<bf16_t>((const bf16_t*)io.dy, c_out, T_out, io.k, io.idx, nullptr, nullptr, sel, p.ldt,
+                                     0, p.ldt, st);
+    if (rc) return rc;
+    Aw = sel; ldaw = p.ldt; a_rows = nullptr;
+  }
+  const int64_t Kw = p.need_sel ? p.ldt : T_out;
+  rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.split_k, part_dw, nullptr, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.split_k, io.k, p.Nw, io.s_x,
+                     io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+static int check_common(const BwdIo& io, int64_t c_out, const void* ws) {
+  if (io.dy_dtype != EFQAT_F32 && io.dy_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
+  if (io.x_dtype != EFQAT_F32 && io.x_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
+  if (io.dx_dtype != EFQAT_F32 && io.dx_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
+  if (io.dy_layout != EFQAT_DY_TOKEN_MAJOR && io.dy_layout != EFQAT_DY_CHANNEL_MAJOR) return EFQAT_ERR_BAD_LAYOUT;
+  if (io.k < 0 || io.k > c_out) return EFQAT_ERR_BAD_K;
+  if (io.scatter != 0 && io.scatter != 1) return EFQAT_ERR_BAD_LAYOUT;
+  if (!io.dy || !io.x_codes || !io.x_clip || !io.x || !io.s_x || !io.z_x || !io.w_codes || !io.s_w || !io.dx ||
+      !io.ds_x || !io.dz_x || !ws)
+    return EFQAT_ERR_NULL_PTR;
+  if (io.k > 0 && (!io.idx || !io.dw || !io.ds_w || !io.w_clip || !io.w)) return EFQAT_ERR_NULL_PTR;
+  if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  const size_t dysz = io.dy_dtype == EFQAT_F32 ? 4 : 2;
+  // the dY tile loads are 16-byte vectors when dY is used in place
+  if (((uintptr_t)io.dy % 16) != 0 || ((uintptr_t)io.dy % dysz) != 0) return EFQAT_ERR_ALIGNMENT;
+  if (((uintptr_t)io.x % (io.x_dtype == EFQAT_F32 ? 4 : 2)) != 0) return EFQAT_ERR_ALIGNMENT;
+  if (((uintptr_t)io.dx % (io.dx_dtype == EFQAT_F32 ? 4 : 2)) != 0) return EFQAT_ERR_ALIGNMENT;
+  return EFQAT_OK;
+}
+
+}  // namespace efqat
+
+using namespace efqat;
+
+extern "C" size_t efqat_linear_bwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out, int64_t k, int dy_dtype,
+                                                   int dy_layout) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || k < 0 || k > c_out) return 0;
+  return make_plan(T, T, c_in, c_out, 1, k, dy_dtype, dy_layout, false).total;
+}
+
+extern "C" int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in, int64_t c_out,
+                                const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                                const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                                const float* w, const float* s_w, const int32_t* idx, int64_t k, void* dx,
+                                int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
+    return EFQAT_ERR_BAD_SHAPE;
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  int rc = check_common(io, c_out, ws);
+  if (rc) return rc;
+  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
+  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
+}
+
+static int conv_geom(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out, int64_t KH, int64_t KW,
+                     int64_t stride, int64_t pad, ConvGeom* g) {
+  if (N <= 0 || H <= 0 || W <= 0 || c_in <= 0 || c_out <= 0 || KH <= 0 || KW <= 0 || stride <= 0 || pad < 0)
+    return EFQAT_ERR_BAD_SHAPE;
+  if (N > (1 << 24) || H > (1 << 15) || W > (1 << 15) || c_in > (1 << 20) || c_out > (1 << 20) || KH > 64 || KW > 64 ||
+      stride > 64 || pad > 64)
+    return EFQAT_ERR_BAD_SHAPE;
+  if (H + 2 * pad < KH || W + 2 * pad < KW) return EFQAT_ERR_BAD_SHAPE;
+  g->N = (int)N; g->H = (int)H; g->W = (int)W; g->c_in = (int)c_in; g->c_out = (int)c_out;
+  g->KH = (int)KH; g->KW = (int)KW; g->stride = (int)stride; g->pad = (int)pad;
+  g->Ho = (int)((H + 2 * pad - KH) / stride + 1);
+  g->Wo = (int)((W + 2 * pad - KW) / stride + 1);
+  if ((int64_t)N * H * W > (1 << 30) || (int64_t)N * g->Ho * g->Wo > (1 << 30)) return EFQAT_ERR_BAD_SHAPE;
+  return EFQAT_OK;
+}
+
+extern "C" size_t efqat_conv_bwd_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
+                                                 int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t k,
+                                                 int dy_dtype, int dy_layout) {
+  ConvGeom g;
+  if (conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g) || k < 0 || k > c_out) return 0;
+  const bool im2col = !(g.KH * g.KW == 1 && g.stride == 1 && g.pad == 0);
+  return make_plan((int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, g.KH * g.KW, k, dy_dtype, dy_layout,
+                   im2col).total;
+}
+
+extern "C" int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                              int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                              const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                              const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                              const float* w, const float* s_w, const int32_t* idx, int64_t k, void* dx,
+                              int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x, void* ws,
+                              size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  int rc = conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g);
+  if (rc) return rc;
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  rc = check_common(io, c_out, ws);
+  if (rc) return rc;
+  if (ws_bytes < efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout))
+    return EFQAT_ERR_WORKSPACE;
+  return run_bwd(io, (int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, &g, ws, (hipStream_t)stream);
+}

@@ -1,0 +1,103 @@
+// Shared device/host helpers for the EfQAT gfx950 kernels (wave64, CDNA4).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/efqat.h"
+
+namespace efqat {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
+
+constexpr int kWave = 64;
+
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (finite inputs)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+// exact when the value is representable in bf16 (small integers): plain truncation
+__device__ __forceinline__ uint32_t pack_bf16x2_exact(float lo, float hi) {
+  return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const T* p, int64_t i);
+template <>
+__device__ __forceinline__ float load_as_f32<float>(const float* p, int64_t i) { return p[i]; }
+template <>
+__device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+
+// ---- wave-level reductions in a fixed butterfly order (deterministic)
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// workspace carving: every sub-buffer starts on a 256-byte boundary
+struct WsCarver {
+  char* base;
+  size_t off;
+  __host__ explicit WsCarver(void* p) : base((char*)p), off(0) {}
+  __host__ void* take(size_t bytes) {
+    void* r = base ? (void*)(base + off) : nullptr;
+    off += (size_t)round_up((int64_t)bytes, 256);
+    return r;
+  }
+};
+
+#define EFQAT_LAUNCH_CHECK()                              \
+  do {                                                    \
+    if (hipGetLastError() != hipSuccess) return EFQAT_ERR_HIP; \
+  } while (0)
+
+// ---- internal entry points shared between translation units (host side)
+struct GemmEpilogueDx {   // fused STE + activation-qparam partial sums (Eq. 5 left, then Eq. 1's STE)
+  const uint8_t* x_codes; // [M][N]
+  const uint32_t* x_clip; // [M][ceil(N/32)]
+  const void* x;          // [M][N] original activations
+  int x_dtype;
+  const float* s_x;
+  const float* z_x;
+  void* dx;               // [M][N]
+  int dx_dtype;
+  float* partial;         // [grid][2] block partial sums of (dS_x, dZ_x)
+};
+
+// C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
+//   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.
+//   split_k > 1: K is cut in split_k contiguous slices, slice s goes to out_partial + s*M*N (raw fp32).
+//   epi != nullptr (split_k must be 1): fused dX epilogue instead of the raw store.
+int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb,
+                   int64_t M, int64_t N, int64_t K, int split_k, float* out_partial,
+                   const GemmEpilogueDx* epi, hipStream_t stream);
+// number of thread blocks launch_gemm_nt uses for (M, N) (for sizing GemmEpilogueDx::partial)
+int64_t gemm_nt_grid_mn(int64_t M, int64_t N);
+int gemm_pick_split_k(int64_t M, int64_t N, int64_t K);
+
+}  // namespace efqat

@@ -1,0 +1,260 @@
+// Fake-quant forward (Eq. 1-4): quantizer statistics, integer codes, straight-through clip masks.
+// All kernels are HBM-bound streaming passes built on 64-wide wavefront reductions.
+#include "common.hpp"
+
+namespace efqat {
+
+// ----------------------------------------------------------------------------------------------
+// 8 consecutive elements as fp32 (vector path: one 16-byte load for bf16, two for fp32)
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p);
+  float4 b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&v)[8]) {
+  uint4 a = *reinterpret_cast<const uint4*>(p);
+  uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Eq. 2 range: alpha = min x, beta = max x over the whole tensor (MinMax observer).
+template <typename T>
+__global__ __launch_bounds__(256) void k_minmax_partial(const T* __restrict__ x, int64_t n, int vec,
+                                                        float* __restrict__ part) {
+  float lo = INFINITY, hi = -INFINITY;
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
+  if (vec) {
+    const int64_t n8 = n >> 3;
+    for (int64_t i = tid; i < n8; i += nthreads) {
+      float v[8];
+      load8<T>(x + i * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { lo = fminf(lo, v[j]); hi = fmaxf(hi, v[j]); }
+    }
+    for (int64_t i = (n8 << 3) + tid; i < n; i += nthreads) {
+      float v = load_as_f32<T>(x, i);
+      lo = fminf(lo, v); hi = fmaxf(hi, v);
+    }
+  } else {
+    for (int64_t i = tid; i < n; i += nthreads) {
+      float v = load_as_f32<T>(x, i);
+      lo = fminf(lo, v); hi = fmaxf(hi, v);
+    }
+  }
+  lo = wave_min(lo); hi = wave_max(hi);
+  __shared__ float s_lo[4], s_hi[4];
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_lo[w] = lo; s_hi[w] = hi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    part[2 * blockIdx.x] = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
+    part[2 * blockIdx.x + 1] = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+  }
+}
+
+// Eq. 2: S_x = (beta - alpha) / (2^b - 1), Z_x = -round(alpha / S_x), each a single-precision op.
+__global__ __launch_bounds__(256) void k_act_qparams(const float* __restrict__ part, int nparts, int bits,
+                                                     float* __restrict__ scale, float* __restrict__ zp) {
+  float lo = INFINITY, hi = -INFINITY;
+  for (int i = threadIdx.x; i < nparts; i += blockDim.x) {
+    lo = fminf(lo, part[2 * i]); hi = fmaxf(hi, part[2 * i + 1]);
+  }
+  lo = wave_min(lo); hi = wave_max(hi);
+  __shared__ float s_lo[4], s_hi[4];
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { s_lo[w] = lo; s_hi[w] = hi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float alpha = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
+    const float beta = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+    const float qmax = (float)((1 << bits) - 1);
+    float s = __fdiv_rn(__fsub_rn(beta, alpha), qmax);
+    if (!(s > 0.0f)) s = 1.0f;                       // zero range
+    scale[0] = s;
+    zp[0] = 0.0f - rintf(__fdiv_rn(alpha, s));
+  }
+}
+
+// Eq. 4 per row: S_w[c] = max_j |w[c][j]| / (2^(b-1) - 1).  One wavefront per row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_row_absmax_scale(const T* __restrict__ x, int64_t rows, int64_t cols,
+                                                          int vec, int bits, float* __restrict__ scale) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* p = x + row * cols;
+  float m = 0.0f;
+  if (vec) {
+    const int64_t n8 = cols >> 3;
+    for (int64_t i = lane; i < n8; i += 64) {
+      float v[8];
+      load8<T>(p + i * 8, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[j]));
+    }
+  } else {
+    for (int64_t i = lane; i < cols; i += 64) m = fmaxf(m, fabsf(load_as_f32<T>(p, i)));
+  }
+  m = wave_max(m);
+  if (lane == 0) {
+    float s = __fdiv_rn(m, (float)((1 << (bits - 1)) - 1));
+    if (!(s > 0.0f)) s = 1.0f;                       // all-zero row
+    scale[row] = s;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Eq. 1 / Eq. 3: codes + clip-mask bits (+ optional de-quantised bf16 values).
+// One wavefront handles one 512-element segment of one row per iteration; a lane owns 8
+// consecutive elements, four neighbouring lanes assemble one 32-bit mask word.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64_t rows, int64_t cols, int vec,
+                                                  int bits, const float* __restrict__ scale,
+                                                  const float* __restrict__ zp, uint8_t* __restrict__ codes,
+                                                  uint32_t* __restrict__ clip, bf16_t* __restrict__ xq) {
+  const int lane = threadIdx.x & 63;
+  const int64_t segs = ceil_div(cols, 512);
+  const int64_t total = rows * segs;
+  const int64_t wpr = ceil_div(cols, 32);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  float lo, hi, z = 0.0f, s_act = 1.0f;
+  if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
+    lo = 0.0f; hi = (float)((1 << bits) - 1);
+    s_act = scale[0];
+    z = rintf(zp[0]);
+  } else {
+    hi = (float)((1 << (bits - 1)) - 1); lo = -hi;
+  }
+  for (int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); item < total; item += nwaves) {
+    const int64_t row = item / segs;
+    const int64_t seg = item - row * segs;
+    const int64_t col0 = seg * 512 + (int64_t)lane * 8;
+    const float s = (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) ? s_act : scale[row];
+    const int64_t base = row * cols + col0;
+    float v[8];
+    const bool full = col0 + 8 <= cols;
+    if (vec && full) {
+      load8<T>(x + base, v);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = (col0 + j < cols) ? load_as_f32<T>(x, base + j) : 0.0f;
+    }
+    uint32_t bits8 = 0;
+    uint32_t cw[2] = {0u, 0u};
+    float dq[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float q = __fdiv_rn(v[j], s);          // correctly rounded quotient decides the code
+      const float c = rintf(q) + z;                // un-clamped code
+      const bool inr = (c >= lo) && (c <= hi);
+      const float cc = fminf(fmaxf(c, lo), hi);
+      const int ci = (int)cc;
+      if (inr && (col0 + j < cols)) bits8 |= (1u << j);
+      cw[j >> 2] |= ((uint32_t)(ci & 0xFF)) << (8 * (j & 3));
+      dq[j] = s * (cc - z);
+    }
+    if (vec && full) {
+      *reinterpret_cast<uint2*>(codes + base) = make_uint2(cw[0], cw[1]);
+      if (xq) {
+        uint4 o = make_uint4(pack_bf16x2(dq[0], dq[1]), pack_bf16x2(dq[2], dq[3]),
+                             pack_bf16x2(dq[4], dq[5]), pack_bf16x2(dq[6], dq[7]));
+        *reinterpret_cast<uint4*>(xq + base) = o;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (col0 + j < cols) {
+          codes[base + j] = (uint8_t)((cw[j >> 2] >> (8 * (j & 3))) & 0xFF);
+          if (xq) xq[base + j] = f32_to_bf16(dq[j]);
+        }
+      }
+    }
+    uint32_t word = bits8 << (8 * (lane & 3));
+    word |= __shfl_xor(word, 1, kWave);
+    word |= __shfl_xor(word, 2, kWave);
+    const int64_t widx = col0 >> 5;
+    if ((lane & 3) == 0 && widx < wpr) clip[row * wpr + widx] = word;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+static inline bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <typename T>
+static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int bits, int init_minmax,
+                         float* scale, float* zp, void* codes, uint32_t* clip, bf16_t* xq, void* ws,
+                         hipStream_t st) {
+  const int64_t n = rows * cols;
+  const int vec_flat = aligned_to(x, 16) ? 1 : 0;
+  const int vec_row = (vec_flat && cols % 8 == 0 && aligned_to(codes, 8) && (!xq || aligned_to(xq, 16))) ? 1 : 0;
+  if (init_minmax) {
+    if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
+      int nparts = (int)(ceil_div(n, 256 * 32) < 1024 ? ceil_div(n, 256 * 32) : 1024);
+      float* part = (float*)ws;
+      hipLaunchKernelGGL((k_minmax_partial<T>), dim3(nparts), dim3(256), 0, st, x, n, vec_flat, part);
+      EFQAT_LAUNCH_CHECK();
+      hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(256), 0, st, part, nparts, bits, scale, zp);
+      EFQAT_LAUNCH_CHECK();
+    } else {
+      const int vr = (vec_flat && cols % 8 == 0) ? 1 : 0;
+      hipLaunchKernelGGL((k_row_absmax_scale<T>), dim3((unsigned)ceil_div(rows, 4)), dim3(256), 0, st, x, rows,
+                         cols, vr, bits, scale);
+      EFQAT_LAUNCH_CHECK();
+    }
+  }
+  const int64_t items = rows * ceil_div(cols, 512);
+  int64_t blocks = ceil_div(items, 4);
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
+    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
+  else
+    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM>), dim3((unsigned)blocks), dim3(256), 0, st, x,
+                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+}  // namespace efqat
+
+using namespace efqat;
+
+extern "C" size_t efqat_fakequant_fwd_workspace_bytes(int64_t rows, int64_t cols, int mode) {
+  (void)rows; (void)cols;
+  return mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM ? (size_t)(1024 * 2 * sizeof(float)) : (size_t)256;
+}
+
+extern "C" int efqat_fakequant_fwd(const void* x, int dtype, int64_t rows, int64_t cols, int mode, int bits,
+                                   int init_minmax, float* scale, float* zero_point, void* codes,
+                                   uint32_t* clip_bits, void* xq, void* ws, size_t ws_bytes, void* stream) {
+  if (mode != EFQAT_QUANT_ACT_PER_TENSOR_ASYM && mode != EFQAT_QUANT_W_PER_ROW_SYM) return EFQAT_ERR_BAD_LAYOUT;
+  if (dtype != EFQAT_F32 && dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
+  if (rows <= 0 || cols <= 0 || rows > (INT64_MAX / cols)) return EFQAT_ERR_BAD_SHAPE;
+  if (bits < 2 || bits > 8) return EFQAT_ERR_BAD_BITS;
+  if (!x || !scale || !codes || !clip_bits) return EFQAT_ERR_NULL_PTR;
+  if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM && !zero_point) return EFQAT_ERR_NULL_PTR;
+  if (init_minmax && mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
+    if (!ws) return EFQAT_ERR_NULL_PTR;
+    if (ws_bytes < efqat_fakequant_fwd_workspace_bytes(rows, cols, mode)) return EFQAT_ERR_WORKSPACE;
+    if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  }
+  const size_t esz = dtype == EFQAT_F32 ? 4 : 2;
+  if (((uintptr_t)x % esz) != 0 || ((uintptr_t)clip_bits % 4) != 0 || (xq && ((uintptr_t)xq % 2) != 0))
+    return EFQAT_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == EFQAT_F32)
+    return run_fakequant<float>((const float*)x, rows, cols, mode, bits, init_minmax, scale, zero_point, codes,
+                                clip_bits, (bf16_t*)xq, ws, st);
+  return run_fakequant<bf16_t>((const bf16_t*)x, rows, cols, mode, bits, init_minmax, scale, zero_point, codes,
+                               clip_bits, (bf16_t*)xq, ws, st);
+}

@@ -1,0 +1,313 @@
+// bf16 MFMA GEMM core for gfx950:  C[M][N] = sum_k A[row(m)][k] * B[n][k]   (both operands K-contiguous).
+//
+// It serves both contractions of Eq. 5:
+//   dX_q = dY . W_q        A = dY [T][C_out],               B = W_q^T [C_in][C_out]
+//   dW_q[id] = dY[:,id]^T X_q   A = rows id of dY^T [C_out][T] (gather fused into the A-tile loads),
+//                               B = (codes - Z_x)^T [C_in][T]
+// 256 threads = 4 wavefronts in a 2x2 grid, v_mfma_f32_32x32x16_bf16, fp32 accumulation, tiles staged
+// through LDS with an XOR swizzle of the 16-byte chunks, global->register prefetch one K-step ahead,
+// two LDS buffers.  Split-K writes raw fp32 partial tiles (deterministic second-pass reduction).
+#include "common.hpp"
+
+namespace efqat {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;  // K elements per LDS stage (4 MFMA k-steps of 16)
+
+struct GemmArgs {
+  const bf16_t* A; int64_t lda; const int32_t* a_rows;
+  const bf16_t* B; int64_t ldb;
+  int M, N, K;
+  int k_per_split;        // multiple of BK
+  int tiles_m, tiles_n;
+  float* out;             // raw fp32 [split][M][N]
+  // fused dX epilogue
+  const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype;
+  const float* s_x; const float* z_x; void* dx; int dx_dtype; float* partial;
+};
+
+template <int BM, int BN>
+struct TileCfg {
+  static constexpr int WM = BM / 2, WN = BN / 2;      // per-wave tile
+  static constexpr int TM = WM / 32, TN = WN / 32;    // MFMA tiles per wave
+  static constexpr int A_CH = BM / 32, B_CH = BN / 32;  // 16-byte chunks a thread stages per operand
+  static constexpr int LDS_A = BM * BK * 2, LDS_B = BN * BK * 2;
+  static constexpr int LDS_STAGE = LDS_A + LDS_B;
+  static constexpr int LDS_BYTES = 2 * LDS_STAGE;
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * (BK * 2) + ((chunk ^ (row & 7)) << 4); }
+
+template <int BM, int BN, bool DX_EPI>
+__global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
+  using C = TileCfg<BM, BN>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- block -> tile: spread contiguous tile ranges over the 8 XCDs (one L2 each), then walk the
+  // range in groups of 8 row-tiles so that concurrently resident blocks share operand panels.
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int GM = 8;
+  const int per_group = GM * g.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GM;
+  const int gsize = (g.tiles_m - first_m) < GM ? (g.tiles_m - first_m) : GM;
+  const int tm = first_m + (pid % per_group) % gsize;
+  const int tn = (pid % per_group) / gsize;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int k_begin = blockIdx.y * g.k_per_split;
+  const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+
+  // ---- staging: thread owns chunk column c of rows r0 + 32*j
+  const int c = tid & 7, r0 = tid >> 3;
+  const bf16_t* a_ptr[C::A_CH];
+  const bf16_t* b_ptr[C::B_CH];
+#pragma unroll
+  for (int j = 0; j < C::A_CH; ++j) {
+    int gm = m0 + r0 + 32 * j;
+    gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
+    const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
+    a_ptr[j] = g.A + src * g.lda + c * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < C::B_CH; ++j) {
+    int gn = n0 + r0 + 32 * j;
+    gn = gn < g.N ? gn : g.N - 1;
+    b_ptr[j] = g.B + (int64_t)gn * g.ldb + c * 8;
+  }
+  uint4 a_st[C::A_CH], b_st[C::B_CH];
+  auto load_stage = [&](int k0) {
+    const bool ok = (k0 + c * 8) < k_end;              // K is a multiple of 8: a chunk is all in or all out
+#pragma unroll
+    for (int j = 0; j < C::A_CH; ++j)
+      a_st[j] = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < C::B_CH; ++j)
+      b_st[j] = ok ? *reinterpret_cast<const uint4*>(b_ptr[j] + k0) : make_uint4(0, 0, 0, 0);
+  };
+  auto store_stage = [&](int buf) {
+    char* sa = smem + buf * C::LDS_STAGE;
+    char* sb = sa + C::LDS_A;
+#pragma unroll
+    for (int j = 0; j < C::A_CH; ++j) *reinterpret_cast<uint4*>(sa + swz(r0 + 32 * j, c)) = a_st[j];
+#pragma unroll
+    for (int j = 0; j < C::B_CH; ++j) *reinterpret_cast<uint4*>(sb + swz(r0 + 32 * j, c)) = b_st[j];
+  };
+
+  floatx16_t acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int fr = lane & 31, fh = lane >> 5;
+
+  if (nk > 0) {
+    load_stage(k_begin);
+    store_stage(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) load_stage(k_begin + (kt + 1) * BK);
+    const char* sa = smem + cur * C::LDS_STAGE;
+    const char* sb = sa + C::LDS_A;
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+      bf16x8_t af[C::TM], bfr[C::TN];
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(wm * C::WM + i * 32 + fr, 2 * s + fh));
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(wn * C::WN + j * 32 + fr, 2 * s + fh));
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_stage(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue.  MFMA 32x32 accumulator layout: lane holds column (lane & 31) and rows
+  // 8*(r/4) + 4*(lane >> 5) + (r % 4), r = 0..15.
+  if (!DX_EPI) {
+    float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j) {
+        const int col = n0 + wn * C::WN + j * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * C::WM + i * 32 + 8 * (r >> 2) + 4 * fh + (r & 3);
+          if (row < g.M && col < g.N) out[(int64_t)row * g.N + col] = acc[i][j][r];
+        }
+      }
+  } else {
+    // dX = dX_q where the activation was not clipped (straight-through), 0 elsewhere; block partial sums
+    // of dS_x = sum dX_q * (in range ? (code - Z) - x/S : code - Z) and dZ_x = sum dX_q * (in range ? 0 : -S).
+    const float s = g.s_x[0];
+    const float z = rintf(g.z_x[0]);
+    const float inv_s = 1.0f / s;
+    const int64_t wpr = (g.N + 31) >> 5;
+    float ps = 0.0f, pz = 0.0f;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j) {
+        const int col = n0 + wn * C::WN + j * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * C::WM + i * 32 + 8 * (r >> 2) + 4 * fh + (r & 3);
+          if (row < g.M && col < g.N) {
+            const int64_t e = (int64_t)row * g.N + col;
+            const float a = acc[i][j][r];
+            const bool inr = (g.x_clip[(int64_t)row * wpr + (col >> 5)] >> (col & 31)) & 1u;
+            const float q = (float)g.x_codes[e] - z;
+            const float xv = g.x_dtype == EFQAT_F32 ? ((const float*)g.x)[e] : bf16_to_f32(((const bf16_t*)g.x)[e]);
+            const float gs = inr ? (q - xv * inv_s) : q;
+            ps += a * gs;
+            pz += inr ? 0.0f : a;
+            const float o = inr ? a : 0.0f;
+            if (g.dx_dtype == EFQAT_F32) ((float*)g.dx)[e] = o;
+            else ((bf16_t*)g.dx)[e] = f32_to_bf16(o);
+          }
+        }
+      }
+    ps = wave_sum(ps);
+    pz = wave_sum(pz);
+    __syncthreads();                                   // LDS tiles are dead: reuse for the block sum
+    float* red = reinterpret_cast<float*>(smem);
+    if (lane == 0) { red[2 * wave] = ps; red[2 * wave + 1] = pz; }
+    __syncthreads();
+    if (tid == 0) {
+      g.partial[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
+      g.partial[2 * blockIdx.x + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------- host
+static inline bool use_big_tile(int64_t M, int64_t N) {
+  // 256x256 tiles when they still give every CU at least ~2 tiles; else 128x128
+  return ceil_div(M, 256) * ceil_div(N, 256) >= 512;
+}
+
+int64_t gemm_nt_grid_mn(int64_t M, int64_t N) {
+  if (use_big_tile(M, N)) return ceil_div(M, 256) * ceil_div(N, 256);
+  return ceil_div(M, 128) * ceil_div(N, 128);
+}
+
+int gemm_pick_split_k(int64_t M, int64_t N, int64_t K) {
+  const int64_t tiles = gemm_nt_grid_mn(M, N);
+  const int64_t ksteps = ceil_div(K, BK);
+  int64_t s = ceil_div(1024, tiles);                 // aim at >= 4 blocks per CU
+  int64_t max_s = ksteps / 8;                        // but keep >= 8 K-steps (512 elements) per slice
+  if (max_s < 1) max_s = 1;
+  if (s > max_s) s = max_s;
+  if (s < 1) s = 1;
+  if (s > 64) s = 64;
+  return (int)s;
+}
+
+// ---- optional event timing of the contraction kernels (benchmarks only; off by default)
+static const int kMaxProf = 4096;
+static bool g_prof_on = false;
+static hipEvent_t g_prof_ev[2][kMaxProf][2];
+static int g_prof_made[2] = {0, 0};
+static int g_prof_used[2] = {0, 0};
+
+static bool prof_begin(int which, hipStream_t st, int* slot) {
+  if (!g_prof_on || g_prof_used[which] >= kMaxProf) return false;
+  const int i = g_prof_used[which];
+  if (i >= g_prof_made[which]) {
+    if (hipEventCreate(&g_prof_ev[which][i][0]) != hipSuccess) return false;
+    if (hipEventCreate(&g_prof_ev[which][i][1]) != hipSuccess) return false;
+    g_prof_made[which] = i + 1;
+  }
+  if (hipEventRecord(g_prof_ev[which][i][0], st) != hipSuccess) return false;
+  *slot = i;
+  return true;
+}
+static void prof_end(int which, hipStream_t st, int slot) {
+  if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
+}
+
+template <int BM, int BN, bool DX>
+static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
+  using C = TileCfg<BM, BN>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, DX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            C::LDS_BYTES) != hipSuccess)
+      return EFQAT_ERR_HIP;
+    attr_done = true;
+  }
+  dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
+  int slot = 0;
+  const bool timed = prof_begin(DX ? 0 : 1, st, &slot);
+  hipLaunchKernelGGL((k_gemm_nt<BM, BN, DX>), grid, dim3(256), C::LDS_BYTES, st, a);
+  if (timed) prof_end(DX ? 0 : 1, st, slot);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb, int64_t M,
+                   int64_t N, int64_t K, int split_k, float* out_partial, const GemmEpilogueDx* epi,
+                   hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 8) || (lda % 8) || (ldb % 8)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return EFQAT_ERR_BAD_SHAPE;
+  if (epi && split_k != 1) return EFQAT_ERR_BAD_SHAPE;
+  GemmArgs a{};
+  a.A = A; a.lda = lda; a.a_rows = a_rows; a.B = B; a.ldb = ldb;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)(ceil_div(ceil_div(K, BK), split_k) * BK);
+  a.out = out_partial;
+  if (epi) {
+    a.x_codes = epi->x_codes; a.x_clip = epi->x_clip; a.x = epi->x; a.x_dtype = epi->x_dtype;
+    a.s_x = epi->s_x; a.z_x = epi->z_x; a.dx = epi->dx; a.dx_dtype = epi->dx_dtype; a.partial = epi->partial;
+  }
+  const bool big = use_big_tile(M, N);
+  const int bm = big ? 256 : 128;
+  a.tiles_m = (int)ceil_div(M, bm);
+  a.tiles_n = (int)ceil_div(N, bm);
+  if (big) return epi ? launch_cfg<256, 256, true>(a, 1, stream) : launch_cfg<256, 256, false>(a, split_k, stream);
+  return epi ? launch_cfg<128, 128, true>(a, 1, stream) : launch_cfg<128, 128, false>(a, split_k, stream);
+}
+
+}  // namespace efqat
+
+extern "C" int efqat_profile_enable(int on) {
+  efqat::g_prof_on = on != 0;
+  efqat::g_prof_used[0] = efqat::g_prof_used[1] = 0;
+  return EFQAT_OK;
+}
+
+extern "C" int efqat_profile_read(int which, double* total_ms, int64_t* launches) {
+  if (which < 0 || which > 1) return EFQAT_ERR_BAD_LAYOUT;
+  if (!total_ms || !launches) return EFQAT_ERR_NULL_PTR;
+  double sum = 0.0;
+  const int n = efqat::g_prof_used[which];
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(efqat::g_prof_ev[which][i][1]) != hipSuccess) return EFQAT_ERR_HIP;
+    if (hipEventElapsedTime(&ms, efqat::g_prof_ev[which][i][0], efqat::g_prof_ev[which][i][1]) != hipSuccess)
+      return EFQAT_ERR_HIP;
+    sum += (double)ms;
+  }
+  *total_ms = sum;
+  *launches = n;
+  return EFQAT_OK;
+}

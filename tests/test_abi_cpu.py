@@ -1,0 +1,122 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on
+the host before any launch (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2411_11038_amd as ef
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _ensure_built():
+    if not os.path.exists(ef.lib_path()):
+        from paper_2411_11038_amd import build
+        build.build()
+
+
+def test_library_exports_every_declared_symbol():
+    _ensure_built()
+    hdr = open(os.path.join(ROOT, "include", "efqat.h")).read()
+    declared = sorted(set(re.findall(r"\b(efqat_[a-z0-9_]+)\s*\(", hdr)))
+    assert declared, "no declarations found"
+    L = C.CDLL(ef.lib_path())
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in efqat.h but not exported"
+    assert sorted(ef.EXPORTS) == declared
+
+
+def test_version_strerror_k_from_ratio():
+    _ensure_built()
+    L = ef.lib()
+    assert L.efqat_version() == 100
+    assert L.efqat_strerror(0) == b"ok"
+    for code in range(-9, 0):
+        assert L.efqat_strerror(code) not in (b"", b"unknown error code")
+    assert L.efqat_strerror(-99) == b"unknown error code"
+    assert ef.k_from_ratio(3072, 1, 20) == 153 and ef.k_from_ratio(768, 1, 20) == 38
+    assert ef.k_from_ratio(11008, 1, 100) == 110 and ef.k_from_ratio(4096, 1, 50) == 81
+    assert ef.k_from_ratio(256, 0, 1) == 0 and ef.k_from_ratio(256, 1, 1) == 256
+    assert ef.k_from_ratio(256, 2, 1) == -1 and ef.k_from_ratio(-1, 1, 2) == -1 and ef.k_from_ratio(8, 1, 0) == -1
+
+
+def test_argument_validation_needs_no_device():
+    _ensure_built()
+    L = ef.lib()
+    fake = 0x1000          # non-NULL, 256-aligned; never dereferenced because validation fails first
+    # fakequant
+    assert L.efqat_fakequant_fwd(None, 0, 4, 4, 0, 8, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -1
+    assert L.efqat_fakequant_fwd(fake, 0, 0, 4, 0, 8, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -2
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 0, 9, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -3
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 0, 1, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -3
+    assert L.efqat_fakequant_fwd(fake, 7, 4, 4, 0, 8, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -8
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 5, 8, 1, fake, fake, fake, fake, None, fake, 1 << 20, None) == -5
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 0, 8, 1, fake, fake, fake, fake, None, fake, 16, None) == -6
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 0, 8, 1, fake, fake, fake, fake, None, fake + 8, 1 << 20, None) == -9
+    assert L.efqat_fakequant_fwd(fake, 0, 4, 4, 0, 8, 1, fake, None, fake, fake, None, fake, 1 << 20, None) == -1
+    # select
+    assert L.efqat_channel_select(fake, 8, 4, 9, None, fake, fake, 1 << 20, None) == -4
+    assert L.efqat_channel_select(fake, 8, 4, -1, None, fake, fake, 1 << 20, None) == -4
+    assert L.efqat_channel_select(fake, 0, 4, 0, None, fake, fake, 1 << 20, None) == -2
+    assert L.efqat_channel_select(None, 8, 4, 2, None, fake, fake, 1 << 20, None) == -1
+    assert L.efqat_channel_select(fake, 8, 4, 2, None, None, fake, 1 << 20, None) == -1
+    assert L.efqat_channel_select(fake, 8, 4, 2, None, fake, fake, 8, None) == -6
+    assert L.efqat_network_select(fake, fake, 2, 8, 9, fake, fake, fake, 1 << 20, None) == -4
+    assert L.efqat_network_select(fake, None, 2, 8, 3, fake, fake, fake, 1 << 20, None) == -1
+
+    # linear backward
+    def lin(dy=fake, T=8, c_in=8, c_out=8, k=2, idx=fake, dw=fake, ws=fake, wsb=1 << 30, dyd=1, lay=0, sc=0):
+        return L.efqat_linear_bwd(dy, dyd, lay, T, c_in, c_out, fake, fake, fake, 1, fake, fake, fake, fake, fake,
+                                  fake, idx, k, fake, 1, dw, sc, fake, fake, fake, ws, wsb, None)
+    assert lin(dy=None) == -1
+    assert lin(T=0) == -2
+    assert lin(k=9) == -4 and lin(k=-1) == -4
+    assert lin(idx=None) == -1 and lin(dw=None) == -1
+    assert lin(wsb=64) == -6
+    assert lin(dyd=3) == -8
+    assert lin(lay=2) == -5 and lin(sc=2) == -5
+    assert lin(ws=fake + 16) == -9
+    assert lin(dy=fake + 2) == -9
+
+    # conv backward
+    def conv(N=1, H=4, W=4, c_in=8, c_out=8, KH=3, KW=3, stride=1, pad=1, k=2, wsb=1 << 30):
+        return L.efqat_conv_bwd(fake, 1, 0, N, H, W, c_in, c_out, KH, KW, stride, pad, fake, fake, fake, 1, fake,
+                                fake, fake, fake, fake, fake, fake, k, fake, 1, fake, 0, fake, fake, fake, fake,
+                                wsb, None)
+    assert conv(stride=0) == -2 and conv(pad=-1) == -2 and conv(H=1, pad=0) == -2
+    assert conv(k=9) == -4
+    assert conv(wsb=64) == -6
+
+
+def test_workspace_queries_are_host_only_and_monotone():
+    _ensure_built()
+    L = ef.lib()
+    a = L.efqat_linear_bwd_workspace_bytes(12288, 768, 3072, 0, 1, 0)
+    b = L.efqat_linear_bwd_workspace_bytes(12288, 768, 3072, 153, 1, 0)
+    c = L.efqat_linear_bwd_workspace_bytes(12288, 768, 3072, 3072, 1, 0)
+    assert 0 < a < b < c
+    assert L.efqat_linear_bwd_workspace_bytes(0, 768, 3072, 0, 1, 0) == 0
+    assert L.efqat_conv_bwd_workspace_bytes(64, 14, 14, 256, 256, 3, 3, 1, 1, 64, 1, 0) > 0
+    assert L.efqat_channel_select_workspace_bytes(11008) >= 11008 * 12
+    assert L.efqat_fakequant_fwd_workspace_bytes(12288, 768, 0) >= 8192
+
+
+def test_product_path_has_no_oracle_or_cpu_fallback():
+    pkg = os.path.join(ROOT, "paper_2411_11038_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("no oracle", ""), f"{f} mentions the oracle"
+    # missing library must raise, not fall back
+    import paper_2411_11038_amd.binding as b
+    saved, b._LIB = b._LIB, None
+    real = b.lib_path
+    b.lib_path = lambda: "/nonexistent/libefqat.so"
+    try:
+        with pytest.raises(FileNotFoundError):
+            b.lib()
+    finally:
+        b.lib_path, b._LIB = real, saved

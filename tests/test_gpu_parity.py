@@ -1,0 +1,294 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
+element on the same seeded inputs.  Integer results (codes, clip masks, indices) must be
+bit-exact; bf16-MFMA gradients within max|err| <= 2e-2 * max|ref|; fp32 reductions within
+1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_11038_amd as ef
+from oracle import efqat_oracle as orc
+from workloads import synth
+
+from gpu_util import (act_tensor, assert_max_err, assert_rms_err, clip_words, dev, host, pack_mask)
+
+pytestmark = pytest.mark.gpu
+
+GEMM_TOL = 2e-2      # bf16 operands, fp32 accumulation (stated bound)
+GEMM_RMS = 5e-3      # derived: one bf16 rounding (2^-9 relative) per W_q / fp32-dY element
+EXACT_TOL = 2e-4     # bf16 dY and integer codes are exact in bf16: only fp32 accumulation error
+
+
+# ---------------------------------------------------------------- fake-quant forward
+@pytest.mark.parametrize("rows,cols", [(1, 1), (5, 7), (37, 100), (256, 256), (300, 768), (64, 4104), (3, 1031)])
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_fakequant_act_minmax(rows, cols, kind, bits):
+    X = synth.normal(100 + rows, 0, (rows, cols))
+    X = synth.as_bf16_values(X) if kind == "bf16" else X.astype(np.float32)
+    s, z = orc.act_qparams_minmax(X, bits)
+    codes, mask, xq = orc.fakequant_act(X, s, z, bits)
+    out = ef.fakequant_fwd(act_tensor(X, kind), ef.ACT_PER_TENSOR_ASYM, bits, init_minmax=True, want_xq=True)
+    torch.cuda.synchronize()
+    assert out["scale"].item() == float(s) and out["zero_point"].item() == float(z)
+    assert np.array_equal(out["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(out["clip_bits"]), pack_mask(mask))
+    assert_max_err(host(out["xq"]), xq, 2.0 ** -8, "xq")
+
+
+@pytest.mark.parametrize("rows,cols", [(5, 7), (129, 200), (256, 256)])
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_fakequant_act_given_params_clipping_and_ties(rows, cols, kind):
+    X = synth.normal(7, 0, (rows, cols))
+    X = synth.as_bf16_values(X) if kind == "bf16" else X.astype(np.float32)
+    # exact ties and on-bound values: multiples of S/2 with S a power of two
+    S, Z = np.float32(0.03125), np.float32(100.3)       # non-integer zero point: forward uses round(Z)
+    X.flat[: min(40, X.size)] = (np.arange(min(40, X.size)) - 20.5) * 0.5 * S
+    X.flat[-1] = S * (255 - 100); X.flat[-2] = S * (0 - 100); X.flat[-3] = S * (256 - 100)
+    codes, mask, _ = orc.fakequant_act(X, S, Z, 8)
+    assert (~mask).any() and mask.any()
+    out = ef.fakequant_fwd(act_tensor(X, kind), ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=False,
+                           scale=dev(np.array([S])), zero_point=dev(np.array([Z])))
+    torch.cuda.synchronize()
+    assert np.array_equal(out["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(out["clip_bits"]), pack_mask(mask))
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (6, 5), (40, 100), (256, 256), (136, 200), (33, 1032)])
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("shrink", [1.0, 0.7])
+def test_fakequant_weight(rows, cols, bits, shrink):
+    W = synth.normal(9 + cols, 1, (rows, cols), std=0.02).astype(np.float32)
+    if rows > 3:
+        W[2] = 0.0                                            # degenerate row
+    sw = orc.weight_scale_minmax(W, bits)
+    if shrink == 1.0:
+        out = ef.fakequant_fwd(dev(W), ef.W_PER_ROW_SYM, bits, init_minmax=True, want_xq=True)
+    else:
+        sw = (sw * np.float32(shrink)).astype(np.float32)
+        out = ef.fakequant_fwd(dev(W), ef.W_PER_ROW_SYM, bits, init_minmax=False, scale=dev(sw), want_xq=True)
+    codes, mask, wq = orc.fakequant_weight(W, sw, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["scale"].cpu().numpy(), sw)
+    assert np.array_equal(out["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(out["clip_bits"]), pack_mask(mask))
+    assert_max_err(host(out["xq"]), wq, 2.0 ** -8, "wq")
+    if shrink < 1.0 and rows * cols > 100:
+        assert (~mask).any()
+
+
+def test_fakequant_conv_weight_ohwi():
+    W = synth.normal(3, 1, (24, 3, 3, 16), std=0.05).astype(np.float32)
+    sw = orc.weight_scale_minmax(W, 4)
+    codes, mask, _ = orc.fakequant_weight(W, sw, 4)
+    out = ef.fakequant_fwd(dev(W), ef.W_PER_ROW_SYM, 4, init_minmax=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["scale"].cpu().numpy(), sw)
+    assert np.array_equal(out["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(out["clip_bits"]), pack_mask(mask.reshape(24, -1)))
+
+
+# ---------------------------------------------------------------- importance + Top-K
+@pytest.mark.parametrize("c_out,block", [(1, 1), (7, 5), (256, 256), (300, 77), (1030, 64), (3072, 768)])
+def test_channel_select_matches_oracle(c_out, block):
+    W = synth.normal(40 + c_out, 1, (c_out, block), std=0.02).astype(np.float32)
+    if c_out >= 7:
+        W[5] = W[1]; W[6] = -W[1]                              # exact ties: lower index must win
+    imp = orc.channel_importance(W)
+    Wd = dev(W)
+    for k in sorted({0, 1, c_out // 20, c_out // 4, c_out - 1, c_out}):
+        if k < 0:
+            continue
+        idx, scores = ef.channel_select(Wd, k)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(scores.cpu().numpy(), imp, rtol=1e-12, atol=0)
+        assert idx.cpu().numpy().tolist() == orc.top_k_channels(imp, k).tolist(), (c_out, k)
+
+
+def test_channel_select_all_equal_scores_picks_lowest_indices():
+    W = np.full((200, 16), 0.5, np.float32)
+    W[:, ::2] *= -1
+    idx, _ = ef.channel_select(dev(W), 37)
+    assert idx.cpu().numpy().tolist() == list(range(37))
+
+
+def test_network_select_cwpn():
+    shapes = [(64, 32), (48, 100), (200, 8), (16, 16)]
+    scores, offs = [], [0]
+    for i, (c, b) in enumerate(shapes):
+        W = synth.normal(60 + i, 1, (c, b), std=0.02 * (1 + 0.3 * i)).astype(np.float32)
+        scores.append(orc.channel_importance(W)); offs.append(offs[-1] + c)
+    scores[2][:] = scores[2][0]                                 # one layer of all-equal scores
+    flat = dev(np.concatenate(scores)); off_d = dev(np.array(offs, dtype=np.int64))
+    for k_total in (0, 1, 40, 163, offs[-1]):
+        idx, kpl = ef.network_select(flat, off_d, k_total)
+        torch.cuda.synchronize()
+        ref = orc.network_top_k(scores, k_total)
+        assert kpl.cpu().numpy().tolist() == [len(r) for r in ref]
+        assert idx.cpu().numpy().tolist() == np.concatenate(ref).astype(np.int64).tolist() if k_total else True
+
+
+# ---------------------------------------------------------------- linear backward
+def _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter, dx_dtype=None):
+    T, c_in = X.shape; c_out = W.shape[0]
+    xd, wd = act_tensor(X, kind), dev(W)
+    fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, a_bits, init_minmax=True)
+    fw = ef.fakequant_fwd(wd, ef.W_PER_ROW_SYM, w_bits, init_minmax=True)
+    sx, zx = orc.act_qparams_minmax(X, a_bits)
+    sw = orc.weight_scale_minmax(W, w_bits)
+    if shrink != 1.0:
+        sx = np.float32(sx * np.float32(shrink)); sw = (sw * np.float32(shrink)).astype(np.float32)
+        fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, a_bits, init_minmax=False, scale=dev(np.array([sx])),
+                              zero_point=dev(np.array([zx])))
+        fw = ef.fakequant_fwd(wd, ef.W_PER_ROW_SYM, w_bits, init_minmax=False, scale=dev(sw))
+    k = ef.k_from_ratio(c_out, num, den)
+    assert k == orc.k_from_ratio(c_out, num, den)
+    idx, _ = ef.channel_select(wd, k)
+    idx_ref = orc.top_k_channels(orc.channel_importance(W), k)
+    dy_host = dY if layout == ef.DY_TOKEN_MAJOR else np.ascontiguousarray(dY.T)
+    out = ef.linear_bwd(act_tensor(dy_host, kind), fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"],
+                        fw["codes"], fw["clip_bits"], wd, fw["scale"], idx if k else None, dy_layout=layout,
+                        scatter=scatter, dx_dtype=dx_dtype)
+    torch.cuda.synchronize()
+    ref = orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx_ref)
+    return out, ref, idx, idx_ref, fx, fw, (sx, zx, sw)
+
+
+def _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, dx_is_bf16, shape_w):
+    sx, zx, sw = qp
+    k = len(idx_ref)
+    assert idx.cpu().numpy().tolist() == idx_ref.tolist()
+    # ---- dX: masked entries are exactly zero, the rest within the bf16-MFMA bound
+    dx = host(out["dx"]).reshape(ref["dX"].shape)
+    assert not dx[~ref["x_mask"]].any()
+    assert_max_err(dx, ref["dX"], GEMM_TOL, "dX")
+    assert_rms_err(dx, ref["dX"], GEMM_RMS + (4e-3 if dx_is_bf16 else 0.0), "dX rms")
+    # ---- dS_x, dZ_x: sums of dXq * g; tolerance relative to the l2 size of the summands
+    z = np.rint(float(zx)); q = ref["x_codes"] - z
+    g = np.where(ref["x_mask"], q - X.astype(np.float64) / float(sx), q)
+    l2 = np.sqrt(np.sum((ref["dXq"] * g) ** 2))
+    assert abs(out["ds_x"].item() - ref["dS_x"]) <= GEMM_TOL * l2 + 1e-30, (out["ds_x"].item(), ref["dS_x"], l2)
+    l2z = float(sx) * np.sqrt(np.sum((ref["dXq"][~ref["x_mask"]]) ** 2))
+    assert abs(out["dz_x"].item() - ref["dZ_x"]) <= GEMM_TOL * l2z + 1e-30, (out["dz_x"].item(), ref["dZ_x"])
+    if ref["x_mask"].all():
+        assert out["dz_x"].item() == 0.0
+    if k == 0:
+        return
+    # ---- dW rows idx (+ frozen rows untouched in scatter mode)
+    tol = EXACT_TOL if kind == "bf16" else GEMM_TOL
+    dw = host(out["dw"]).astype(np.float64)
+    dsw = host(out["ds_w"]).astype(np.float64)
+    dw_ref = ref["dW"].reshape(ref["dW"].shape[0], -1)
+    if scatter:
+        dw = dw.reshape(dw_ref.shape)
+        frozen = np.setdiff1d(np.arange(dw_ref.shape[0]), idx_ref)
+        assert not dw[frozen].any() and not dsw[frozen].any()
+        dw = dw[idx_ref]; dsw = dsw[idx_ref]
+    else:
+        dw = dw.reshape(k, -1)
+    wm = ref["w_mask"].reshape(dw_ref.shape)[idx_ref]
+    assert not dw[~wm].any()
+    assert_max_err(dw, dw_ref[idx_ref], tol, "dW")
+    # dS_w per row: tolerance relative to the l2 size of that row's summands
+    wc = ref["w_codes"].reshape(dw_ref.shape)[idx_ref].astype(np.float64)
+    W2 = W.reshape(dw_ref.shape)[idx_ref].astype(np.float64)
+    gw = np.where(wm, wc - W2 / sw[idx_ref, None].astype(np.float64), wc)
+    # un-masked dW_q of the oracle for the l2 scale: where masked, use |dW| bound from the row max
+    row_l2 = np.sqrt(np.sum((np.abs(dw_ref[idx_ref]).max(axis=1, keepdims=True) * gw) ** 2, axis=1))
+    err = np.abs(dsw - ref["dS_w"][idx_ref])
+    assert np.all(err <= tol * row_l2 + 1e-30), (err.max(), row_l2.min())
+
+
+LIN_CASES = [
+    # T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter
+    (256, 256, 256, "f32", 8, 8, 1.0, (1, 4), 0, False),          # config 1, seed 0
+    (256, 256, 256, "f32", 8, 8, 0.7, (1, 4), 0, True),
+    (256, 256, 256, "f32", 8, 8, 1.0, (1, 4), 1, False),
+    (300, 200, 136, "bf16", 8, 4, 0.7, (1, 4), 0, False),         # ragged tiles, several per dimension
+    (300, 200, 136, "bf16", 8, 4, 0.7, (1, 4), 1, True),
+    (517, 392, 264, "bf16", 8, 8, 0.8, (1, 2), 0, True),
+    (129, 72, 40, "bf16", 8, 8, 1.0, (1, 1), 0, False),           # r = 100 %: full QAT backward
+    (129, 72, 40, "bf16", 8, 8, 0.7, (0, 1), 0, False),           # r = 0: no weight gradient
+    (130, 70, 43, "f32", 8, 4, 0.7, (1, 3), 0, False),            # nothing a multiple of 8
+    (130, 70, 43, "bf16", 8, 4, 0.7, (1, 3), 1, False),
+    (131, 70, 43, "f32", 4, 4, 0.6, (1, 3), 1, True),
+    (1, 8, 8, "bf16", 8, 8, 1.0, (1, 1), 0, False),               # single token
+    (1024, 768, 768, "bf16", 8, 8, 0.8, (1, 20), 0, False),       # BERT-width, split-K path
+    (1024, 768, 768, "bf16", 8, 8, 0.8, (1, 20), 1, False),
+]
+
+
+@pytest.mark.parametrize("case", LIN_CASES, ids=lambda c: "T%d_%dx%d_%s_w%d_s%s_r%d-%d_L%d_sc%d" % (
+    c[0], c[1], c[2], c[3], c[5], c[6], c[7][0], c[7][1], c[8], int(c[9])))
+def test_linear_bwd_matches_oracle(case):
+    T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter = case
+    seed = 0 if (T, c_in, c_out) == (256, 256, 256) else 1000 + T + c_in
+    X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=kind)
+    out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout,
+                                                     scatter)
+    assert np.array_equal(fx["codes"].cpu().numpy().astype(np.int64), ref["x_codes"])
+    assert np.array_equal(fw["codes"].cpu().numpy().astype(np.int64), ref["w_codes"])
+    assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"]))
+    assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"]))
+    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+
+
+def test_linear_bwd_dx_independent_of_fraction_and_fp32_dx():
+    X, W, dY = synth.linear_layer(77, 260, 136, 200, act_dtype="bf16")
+    outs = []
+    for num, den in [(0, 1), (1, 20), (1, 1)]:
+        out, ref, *_ = _run_linear(X, W, dY, "bf16", 8, 8, 0.8, num, den, 0, False, dx_dtype=torch.float32)
+        outs.append(out)
+        assert_max_err(host(out["dx"]), ref["dX"], GEMM_TOL, "dX fp32")
+    for o in outs[1:]:
+        assert torch.equal(o["dx"], outs[0]["dx"])                   # bitwise: dX does not depend on r
+        assert o["ds_x"].item() == outs[0]["ds_x"].item() and o["dz_x"].item() == outs[0]["dz_x"].item()
+
+
+def test_linear_bwd_is_deterministic():
+    X, W, dY = synth.linear_layer(78, 512, 256, 264, act_dtype="bf16")
+    a, *_ = _run_linear(X, W, dY, "bf16", 8, 8, 0.8, 1, 4, 0, False)
+    b, *_ = _run_linear(X, W, dY, "bf16", 8, 8, 0.8, 1, 4, 0, False)
+    for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
+        assert torch.equal(a[key], b[key]), key
+
+
+# ---------------------------------------------------------------- conv backward
+CONV_CASES = [
+    # N, H, W, c_in, c_out, kh, kw, stride, pad, kind, w_bits, shrink, (num, den), layout, scatter
+    (2, 7, 6, 16, 24, 3, 3, 1, 1, "bf16", 4, 0.7, (1, 4), 0, False),
+    (2, 7, 6, 16, 24, 3, 3, 1, 1, "bf16", 4, 0.7, (1, 4), 1, True),
+    (3, 9, 8, 12, 20, 3, 3, 2, 1, "f32", 4, 0.8, (1, 2), 0, False),
+    (2, 8, 8, 24, 16, 1, 1, 1, 0, "bf16", 8, 0.7, (1, 4), 0, False),
+    (2, 8, 8, 24, 16, 1, 1, 2, 0, "bf16", 8, 1.0, (1, 1), 0, False),
+    (2, 6, 7, 10, 9, 2, 3, 2, 0, "f32", 4, 0.7, (1, 3), 1, False),
+    (4, 14, 14, 64, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (1, 20), 0, False),   # ResNet-like, several tiles
+    (4, 14, 14, 64, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (0, 1), 0, False),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "N%d_%dx%d_%d-%d_k%dx%d_s%dp%d_%s_L%d" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8], c[9], c[13]))
+def test_conv_bwd_matches_oracle(case):
+    N, H, Wd, c_in, c_out, kh, kw, stride, pad, kind, w_bits, shrink, (num, den), layout, scatter = case
+    X, W, dY = synth.conv_layer(4000 + H + c_in, N, H, Wd, c_in, c_out, kh, kw, stride, pad, act_dtype=kind)
+    xd, wd = act_tensor(X, kind), dev(W)
+    sx, zx = orc.act_qparams_minmax(X, 8)
+    sw = orc.weight_scale_minmax(W, w_bits)
+    sx = np.float32(sx * np.float32(shrink)); sw = (sw * np.float32(shrink)).astype(np.float32)
+    fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=False, scale=dev(np.array([sx])),
+                          zero_point=dev(np.array([zx])))
+    fw = ef.fakequant_fwd(wd, ef.W_PER_ROW_SYM, w_bits, init_minmax=False, scale=dev(sw))
+    k = ef.k_from_ratio(c_out, num, den)
+    idx, _ = ef.channel_select(wd, k)
+    idx_ref = orc.top_k_channels(orc.channel_importance(W), k)
+    dy_host = dY if layout == 0 else np.ascontiguousarray(np.moveaxis(dY, -1, 0))
+    out = ef.conv_bwd(act_tensor(dy_host, kind), fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"],
+                      fw["codes"], fw["clip_bits"], wd, fw["scale"], idx if k else None, stride=stride, pad=pad,
+                      dy_layout=layout, scatter=scatter)
+    torch.cuda.synchronize()
+    ref = orc.conv_bwd(dY, X, sx, zx, 8, W, sw, w_bits, idx_ref, stride, pad)
+    assert np.array_equal(fx["codes"].cpu().numpy().astype(np.int64), ref["x_codes"])
+    assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"].reshape(-1, c_in)))
+    assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"].reshape(c_out, -1)))
+    _check_bwd(out, ref, idx, idx_ref, X, W, (sx, zx, sw), kind, scatter, kind == "bf16", W.shape)
