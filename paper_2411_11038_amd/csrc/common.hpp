@@ -22,8 +22,13 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
+// two fp32 -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  f32x2_hw_t v = {lo, hi};
+  bf16x2_hw_t b = __builtin_convertvector(v, bf16x2_hw_t);
+  return *reinterpret_cast<uint32_t*>(&b);
 }
 // exact when the value is representable in bf16 (small integers): plain truncation
 __device__ __forceinline__ uint32_t pack_bf16x2_exact(float lo, float hi) {
@@ -88,6 +93,8 @@ struct GemmEpilogueDx {   // fused STE + activation-qparam partial sums (Eq. 5 l
   int dx_dtype;
   float* partial;         // [grid][2] block partial sums of (dS_x, dZ_x)
 };
+// true when the fused epilogue may use 8-element vector accesses on x_codes / x / dx
+bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N);
 
 // C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
 //   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.

@@ -26,6 +26,7 @@ struct GemmArgs {
   // fused dX epilogue
   const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype;
   const float* s_x; const float* z_x; void* dx; int dx_dtype; float* partial;
+  int epi_vec;            // 8-wide vector accesses allowed in the fused epilogue
 };
 
 template <int BM, int BN>
@@ -158,37 +159,98 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   } else {
     // dX = dX_q where the activation was not clipped (straight-through), 0 elsewhere; block partial sums
     // of dS_x = sum dX_q * (in range ? (code - Z) - x/S : code - Z) and dZ_x = sum dX_q * (in range ? 0 : -S).
+    // The accumulators go through LDS (32 rows of the wave's tile at a time) so that every lane then owns
+    // 8 consecutive columns of one row: 8-byte code loads, 16-byte x loads and 16-byte dX stores.
+    constexpr int PITCH = C::WN + 8;                   // floats; 4*PITCH = 32 (mod 64) banks
+    constexpr int CPR = C::WN / 8;                     // 8-column chunks per row
+    constexpr int RPP = 64 / CPR;                      // rows per pass of the wavefront
+    float* stage = reinterpret_cast<float*>(smem) + wave * 32 * PITCH;
     const float s = g.s_x[0];
     const float z = rintf(g.z_x[0]);
-    const float inv_s = 1.0f / s;
+    const float ninv_s = -1.0f / s;
     const int64_t wpr = (g.N + 31) >> 5;
+    const int row_l0 = lane / CPR, ch = lane % CPR;
+    const int gcol = n0 + wn * C::WN + ch * 8;
     float ps = 0.0f, pz = 0.0f;
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i)
+    for (int i = 0; i < C::TM; ++i) {
+      if (i > 0) __syncthreads();
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j) {
-        const int col = n0 + wn * C::WN + j * 32 + fr;
+      for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * C::WM + i * 32 + 8 * (r >> 2) + 4 * fh + (r & 3);
-          if (row < g.M && col < g.N) {
-            const int64_t e = (int64_t)row * g.N + col;
-            const float a = acc[i][j][r];
-            const bool inr = (g.x_clip[(int64_t)row * wpr + (col >> 5)] >> (col & 31)) & 1u;
-            const float q = (float)g.x_codes[e] - z;
-            const float xv = g.x_dtype == EFQAT_F32 ? ((const float*)g.x)[e] : bf16_to_f32(((const bf16_t*)g.x)[e]);
-            const float gs = inr ? (q - xv * inv_s) : q;
-            ps += a * gs;
-            pz += inr ? 0.0f : a;
-            const float o = inr ? a : 0.0f;
-            if (g.dx_dtype == EFQAT_F32) ((float*)g.dx)[e] = o;
-            else ((bf16_t*)g.dx)[e] = f32_to_bf16(o);
+        for (int r = 0; r < 16; ++r)
+          stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < 32 / RPP; ++p) {
+        const int row_l = p * RPP + row_l0;
+        const int grow = m0 + wm * C::WM + i * 32 + row_l;
+        if (grow < g.M && gcol < g.N) {
+          const float4 a0 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8);
+          const float4 a1 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8 + 4);
+          const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+          const int64_t e = (int64_t)grow * g.N + gcol;
+          const uint32_t mbits = g.x_clip[(int64_t)grow * wpr + (gcol >> 5)] >> (gcol & 31);
+          float o[8];
+          if (g.epi_vec && gcol + 8 <= g.N) {
+            const uint2 cw = *reinterpret_cast<const uint2*>(g.x_codes + e);
+            float xv[8];
+            if (g.x_dtype == EFQAT_F32) {
+              const float4 x0 = *reinterpret_cast<const float4*>((const float*)g.x + e);
+              const float4 x1 = *reinterpret_cast<const float4*>((const float*)g.x + e + 4);
+              xv[0] = x0.x; xv[1] = x0.y; xv[2] = x0.z; xv[3] = x0.w;
+              xv[4] = x1.x; xv[5] = x1.y; xv[6] = x1.z; xv[7] = x1.w;
+            } else {
+              const uint4 xr = *reinterpret_cast<const uint4*>((const bf16_t*)g.x + e);
+              const uint32_t xw[4] = {xr.x, xr.y, xr.z, xr.w};
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                xv[2 * t] = __uint_as_float(xw[t] << 16);
+                xv[2 * t + 1] = __uint_as_float(xw[t] & 0xFFFF0000u);
+              }
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+              const uint32_t byte = ((t < 4 ? cw.x : cw.y) >> (8 * (t & 3))) & 0xFFu;
+              const float q = (float)byte - z;
+              const bool inr = (mbits >> t) & 1u;
+              const float gs = inr ? fmaf(xv[t], ninv_s, q) : q;
+              ps = fmaf(a[t], gs, ps);
+              o[t] = inr ? a[t] : 0.0f;
+              pz += a[t] - o[t];
+            }
+            if (g.dx_dtype == EFQAT_F32) {
+              *reinterpret_cast<float4*>((float*)g.dx + e) = make_float4(o[0], o[1], o[2], o[3]);
+              *reinterpret_cast<float4*>((float*)g.dx + e + 4) = make_float4(o[4], o[5], o[6], o[7]);
+            } else {
+              *reinterpret_cast<uint4*>((bf16_t*)g.dx + e) =
+                  make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                             pack_bf16x2(o[6], o[7]));
+            }
+          } else {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+              if (gcol + t < g.N) {
+                const float q = (float)g.x_codes[e + t] - z;
+                const float xv = g.x_dtype == EFQAT_F32 ? ((const float*)g.x)[e + t]
+                                                        : bf16_to_f32(((const bf16_t*)g.x)[e + t]);
+                // the mask word may end inside this chunk: re-read per element
+                const bool inr = (g.x_clip[(int64_t)grow * wpr + ((gcol + t) >> 5)] >> ((gcol + t) & 31)) & 1u;
+                const float gs = inr ? fmaf(xv, ninv_s, q) : q;
+                ps = fmaf(a[t], gs, ps);
+                const float ov = inr ? a[t] : 0.0f;
+                pz += a[t] - ov;
+                if (g.dx_dtype == EFQAT_F32) ((float*)g.dx)[e + t] = ov;
+                else ((bf16_t*)g.dx)[e + t] = f32_to_bf16(ov);
+              }
+            }
           }
         }
       }
+    }
     ps = wave_sum(ps);
     pz = wave_sum(pz);
-    __syncthreads();                                   // LDS tiles are dead: reuse for the block sum
+    __syncthreads();                                   // staging area is dead: reuse for the block sum
     float* red = reinterpret_cast<float*>(smem);
     if (lane == 0) { red[2 * wave] = ps; red[2 * wave + 1] = pz; }
     __syncthreads();
@@ -203,6 +265,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 static inline bool use_big_tile(int64_t M, int64_t N) {
   // 256x256 tiles when they still give every CU at least ~2 tiles; else 128x128
   return ceil_div(M, 256) * ceil_div(N, 256) >= 512;
+}
+
+bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N) {
+  return (N % 8) == 0 && ((uintptr_t)e.x_codes % 8) == 0 && ((uintptr_t)e.x % 16) == 0 && ((uintptr_t)e.dx % 16) == 0;
 }
 
 int64_t gemm_nt_grid_mn(int64_t M, int64_t N) {
@@ -278,6 +344,7 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
   if (epi) {
     a.x_codes = epi->x_codes; a.x_clip = epi->x_clip; a.x = epi->x; a.x_dtype = epi->x_dtype;
     a.s_x = epi->s_x; a.z_x = epi->z_x; a.dx = epi->dx; a.dx_dtype = epi->dx_dtype; a.partial = epi->partial;
+    a.epi_vec = gemm_epilogue_vec_ok(*epi, N) ? 1 : 0;
   }
   const bool big = use_big_tile(M, N);
   const int bm = big ? 256 : 128;
