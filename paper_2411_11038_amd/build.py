@@ -44,7 +44,7 @@ def build(verbose: bool = False) -> str:
             print(f"--- {src}\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB_PATH] + objs
     subprocess.run(cmd, check=True)
     for o in objs:
         os.remove(o)

@@ -13,6 +13,7 @@ namespace efqat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int BK = 64;  // K elements per LDS stage (4 MFMA k-steps of 16)
 
@@ -43,6 +44,7 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * (BK * 2) +
 
 template <int BM, int BN, bool DX_EPI>
 __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins; the host pass needs only the launch stub
   using C = TileCfg<BM, BN>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -64,42 +66,58 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 
   const int k_begin = blockIdx.y * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
-  const int nk = (k_end - k_begin + BK - 1) / BK;
 
-  // ---- staging: thread owns chunk column c of rows r0 + 32*j
-  const int c = tid & 7, r0 = tid >> 3;
+  // ---- operand staging.  One stage of an operand is R rows x 128 bytes (64 bf16); the 16-byte chunk c of
+  // row r lives at r*128 + ((c ^ (r & 7)) << 4) so that the MFMA fragment reads below are bank-conflict
+  // free.  A wavefront stages groups of 8 rows: lane l covers row 8*grp + (l >> 3) and LDS slot (l & 7),
+  // i.e. the logical chunk (l & 7) ^ (l >> 3); one wave instruction thus fills 1 KiB of contiguous LDS,
+  // which is the shape the direct global->LDS load (global_load_lds_dwordx4) writes.
+  const int lrow = lane >> 3, lch = (lane & 7) ^ lrow;
   const bf16_t* a_ptr[C::A_CH];
   const bf16_t* b_ptr[C::B_CH];
 #pragma unroll
   for (int j = 0; j < C::A_CH; ++j) {
-    int gm = m0 + r0 + 32 * j;
+    int gm = m0 + (wave + 4 * j) * 8 + lrow;
     gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
     const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
-    a_ptr[j] = g.A + src * g.lda + c * 8;
+    a_ptr[j] = g.A + src * g.lda + lch * 8 + k_begin;
   }
 #pragma unroll
   for (int j = 0; j < C::B_CH; ++j) {
-    int gn = n0 + r0 + 32 * j;
+    int gn = n0 + (wave + 4 * j) * 8 + lrow;
     gn = gn < g.N ? gn : g.N - 1;
-    b_ptr[j] = g.B + (int64_t)gn * g.ldb + c * 8;
+    b_ptr[j] = g.B + (int64_t)gn * g.ldb + lch * 8 + k_begin;
   }
-  uint4 a_st[C::A_CH], b_st[C::B_CH];
-  auto load_stage = [&](int k0) {
-    const bool ok = (k0 + c * 8) < k_end;              // K is a multiple of 8: a chunk is all in or all out
-#pragma unroll
-    for (int j = 0; j < C::A_CH; ++j)
-      a_st[j] = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + k0) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int j = 0; j < C::B_CH; ++j)
-      b_st[j] = ok ? *reinterpret_cast<const uint4*>(b_ptr[j] + k0) : make_uint4(0, 0, 0, 0);
-  };
-  auto store_stage = [&](int buf) {
+  const int span = k_end - k_begin;
+  const int nfull = span > 0 ? span / BK : 0;          // K-steps that need no predicate
+  const int nk = span > 0 ? (span + BK - 1) / BK : 0;
+
+  // stage K-step kt into LDS buffer buf
+  auto issue = [&](int kt, int buf) {
     char* sa = smem + buf * C::LDS_STAGE;
     char* sb = sa + C::LDS_A;
+    const int koff = kt * BK;
+    if (kt < nfull) {
 #pragma unroll
-    for (int j = 0; j < C::A_CH; ++j) *reinterpret_cast<uint4*>(sa + swz(r0 + 32 * j, c)) = a_st[j];
+      for (int j = 0; j < C::A_CH; ++j)
+        __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
 #pragma unroll
-    for (int j = 0; j < C::B_CH; ++j) *reinterpret_cast<uint4*>(sb + swz(r0 + 32 * j, c)) = b_st[j];
+      for (int j = 0; j < C::B_CH; ++j)
+        __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
+    } else {
+      // ragged last step: K is a multiple of 8, so a 16-byte chunk is all in or all out; missing chunks are 0
+      const bool ok = (koff + lch * 8) < span;
+#pragma unroll
+      for (int j = 0; j < C::A_CH; ++j) {
+        const uint4 v = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(sa + (wave + 4 * j) * 1024 + lane * 16) = v;
+      }
+#pragma unroll
+      for (int j = 0; j < C::B_CH; ++j) {
+        const uint4 v = ok ? *reinterpret_cast<const uint4*>(b_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(sb + (wave + 4 * j) * 1024 + lane * 16) = v;
+      }
+    }
   };
 
   floatx16_t acc[C::TM][C::TN];
@@ -111,33 +129,40 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int fr = lane & 31, fh = lane >> 5;
+  // byte offsets of this lane's fragment rows inside a stage (swizzle folded in per K-sub-step below)
+  const int a_row0 = wm * C::WM + fr, b_row0 = wn * C::WN + fr;
 
-  if (nk > 0) {
-    load_stage(k_begin);
-    store_stage(0);
-  }
+  if (nk > 0) issue(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) load_stage(k_begin + (kt + 1) * BK);
+    if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
     const char* sa = smem + cur * C::LDS_STAGE;
     const char* sb = sa + C::LDS_A;
+    bf16x8_t af[2][C::TM], bfr[2][C::TN];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, fh));
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, fh));
 #pragma unroll
     for (int s = 0; s < BK / 16; ++s) {
-      bf16x8_t af[C::TM], bfr[C::TN];
+      const int cb = s & 1, nb = cb ^ 1;
+      if (s + 1 < BK / 16) {                           // fragments of the next sub-step, ahead of the MFMAs
 #pragma unroll
-      for (int i = 0; i < C::TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(wm * C::WM + i * 32 + fr, 2 * s + fh));
+        for (int i = 0; i < C::TM; ++i)
+          af[nb][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, 2 * (s + 1) + fh));
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(wn * C::WN + j * 32 + fr, 2 * s + fh));
+        for (int j = 0; j < C::TN; ++j)
+          bfr[nb][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, 2 * (s + 1) + fh));
+      }
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
 #pragma unroll
         for (int j = 0; j < C::TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_stage(cur ^ 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct global->LDS loads of the next stage landed
     __syncthreads();
   }
 
@@ -259,6 +284,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       g.partial[2 * blockIdx.x + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
     }
   }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------- host
