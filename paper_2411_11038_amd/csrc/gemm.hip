@@ -47,7 +47,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins; the host pass needs only the launch stub
   using C = TileCfg<BM, BN>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay scalar
   const int wm = wave >> 1, wn = wave & 1;
 
   // ---- block -> tile: spread contiguous tile ranges over the 8 XCDs (one L2 each), then walk the
@@ -132,39 +133,92 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   // byte offsets of this lane's fragment rows inside a stage (swizzle folded in per K-sub-step below)
   const int a_row0 = wm * C::WM + fr, b_row0 = wn * C::WN + fr;
 
+  // ---- main loop.  Software pipeline per stage (4 sub-steps of K = 16):
+  //   sub-steps 0..2: read the fragments of the next sub-step from LDS while the MFMAs of this one run;
+  //   before sub-step 3: wait for this wave's in-flight LDS reads and its global->LDS loads of stage kt+1,
+  //     then barrier (now stage kt+1 is complete and nobody reads stage kt's buffer any more);
+  //   sub-step 3: issue the global->LDS loads of stage kt+2 into the freed buffer and read the first
+  //     fragments of stage kt+1, all under the MFMAs of sub-step 3.
+  bf16x8_t af[2][C::TM], bfr[2][C::TN];
+  auto load_frags = [&](int buf, int s, int rb) {
+    const char* sa = smem + buf * C::LDS_STAGE;
+    const char* sb = sa + C::LDS_A;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+      af[rb][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, 2 * s + fh));
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+      bfr[rb][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, 2 * s + fh));
+  };
+  auto mfma_all = [&](int rb) {
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb][i], bfr[rb][j], acc[i][j], 0, 0, 0);
+  };
+
+  // direct loads of a full (unpredicated) stage, no control flow: usable inside a scheduling region
+  auto issue_direct = [&](int kt, int buf) {
+    char* sa = smem + buf * C::LDS_STAGE;
+    char* sb = sa + C::LDS_A;
+    const int koff = kt * BK;
+#pragma unroll
+    for (int j = 0; j < C::A_CH; ++j)
+      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < C::B_CH; ++j)
+      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
+  };
+
   if (nk > 0) issue(0, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
-    const char* sa = smem + cur * C::LDS_STAGE;
-    const char* sb = sa + C::LDS_A;
-    bf16x8_t af[2][C::TM], bfr[2][C::TN];
+  if (nk > 1) issue(1, 1);
+  if (nk > 0) load_frags(0, 0, 0);
+  constexpr int MF = C::TM * C::TN, NR = C::TM + C::TN;   // MFMAs and fragment reads per sub-step
+  auto substeps012 = [&](int cur) {
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i) af[0][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, fh));
+    for (int s = 0; s < 3; ++s) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(cur, s + 1, (s + 1) & 1);
+      mfma_all(s & 1);
 #pragma unroll
-    for (int j = 0; j < C::TN; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, fh));
-#pragma unroll
-    for (int s = 0; s < BK / 16; ++s) {
-      const int cb = s & 1, nb = cb ^ 1;
-      if (s + 1 < BK / 16) {                           // fragments of the next sub-step, ahead of the MFMAs
-#pragma unroll
-        for (int i = 0; i < C::TM; ++i)
-          af[nb][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, 2 * (s + 1) + fh));
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-          bfr[nb][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, 2 * (s + 1) + fh));
+      for (int q = 0; q < NR; ++q) {                   // a share of the MFMAs, then one LDS read
+        __builtin_amdgcn_sched_group_barrier(0x008, MF / NR, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-#pragma unroll
-      for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cb][i], bfr[cb][j], acc[i][j], 0, 0, 0);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct global->LDS loads of the next stage landed
-    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int kt = 0;
+  // steady state: stage kt+2 exists and is a full stage -> branch-free body, one scheduling region per sub-step
+  for (; kt + 2 < nfull; ++kt) {
+    const int cur = kt & 1;
+    substeps012(cur);
+    issue_direct(kt + 2, cur);
+    load_frags(cur ^ 1, 0, 0);
+    mfma_all(1);
+#pragma unroll
+    for (int q = 0; q < MF; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (q < C::A_CH + C::B_CH) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+  // drain: the last (up to three) stages, including a ragged one
+  for (; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    substeps012(cur);
+    if (kt + 2 < nk) issue(kt + 2, cur);
+    if (kt + 1 < nk) load_frags(cur ^ 1, 0, 0);
+    mfma_all(1);
+  }
+  __syncthreads();
 
   // ---- epilogue.  MFMA 32x32 accumulator layout: lane holds column (lane & 31) and rows
   // 8*(r/4) + 4*(lane >> 5) + (r % 4), r = 0..15.
