@@ -4,9 +4,11 @@
 //   dX_q = dY . W_q        A = dY [T][C_out],               B = W_q^T [C_in][C_out]
 //   dW_q[id] = dY[:,id]^T X_q   A = rows id of dY^T [C_out][T] (gather fused into the A-tile loads),
 //                               B = (codes - Z_x)^T [C_in][T]
-// 256 threads = 4 wavefronts in a 2x2 grid, v_mfma_f32_32x32x16_bf16, fp32 accumulation, tiles staged
-// through LDS with an XOR swizzle of the 16-byte chunks, global->register prefetch one K-step ahead,
-// two LDS buffers.  Split-K writes raw fp32 partial tiles (deterministic second-pass reduction).
+// 256 threads = 4 wavefronts in a 2x2 grid, v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  Operand tiles
+// go global -> LDS directly (global_load_lds_dwordx4, 128-byte row segments = whole cache lines per request)
+// into two LDS stages of K = 64 with an XOR swizzle that makes the ds_read_b128 fragment reads conflict free;
+// fragments are double-buffered in registers and the loads of the stage after next are spread over three of the
+// four MFMA sub-steps.  Split-K writes raw fp32 partial tiles (deterministic second-pass reduction).
 #include "common.hpp"
 
 namespace efqat {
@@ -15,13 +17,13 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-constexpr int BK = 64;  // K elements per LDS stage (4 MFMA k-steps of 16)
+constexpr int KALIGN = 64;  // split-K slices start on multiples of this many K elements
 
 struct GemmArgs {
   const bf16_t* A; int64_t lda; const int32_t* a_rows;
   const bf16_t* B; int64_t ldb;
   int M, N, K;
-  int k_per_split;        // multiple of BK
+  int k_per_split;        // multiple of KALIGN
   int tiles_m, tiles_n;
   float* out;             // raw fp32 [split][M][N]
   // fused dX epilogue
@@ -30,22 +32,41 @@ struct GemmArgs {
   int epi_vec;            // 8-wide vector accesses allowed in the fused epilogue
 };
 
-template <int BM, int BN>
+// BM x BN output tile per 256-thread block, BKT K-elements per LDS stage, S stages in the LDS ring.
+template <int BM, int BN, int BKT, int S>
 struct TileCfg {
-  static constexpr int WM = BM / 2, WN = BN / 2;      // per-wave tile
-  static constexpr int TM = WM / 32, TN = WN / 32;    // MFMA tiles per wave
-  static constexpr int A_CH = BM / 32, B_CH = BN / 32;  // 16-byte chunks a thread stages per operand
-  static constexpr int LDS_A = BM * BK * 2, LDS_B = BN * BK * 2;
+  static constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 wavefronts)
+  static constexpr int TM = WM / 32, TN = WN / 32;      // MFMA tiles per wave
+  static constexpr int PITCH_B = BKT * 2;               // bytes per tile row in LDS
+  static constexpr int CPRW = BKT / 8;                  // 16-byte chunks per row
+  static constexpr int RPI = 1024 / PITCH_B;            // rows covered by one 1-KiB wave load
+  static constexpr int R256 = 256 / PITCH_B;            // rows per 256 bytes (LDS bank period for b128)
+  static constexpr int A_G = BM / RPI / 4, B_G = BN / RPI / 4;  // 1-KiB row groups per wave and stage
+  static constexpr int NS = BKT / 16;                   // MFMA sub-steps per stage
+  static constexpr int LDS_A = BM * PITCH_B, LDS_B = BN * PITCH_B;
   static constexpr int LDS_STAGE = LDS_A + LDS_B;
-  static constexpr int LDS_BYTES = 2 * LDS_STAGE;
+  static constexpr int LDS_LOOP = S * LDS_STAGE;
+  static constexpr int LDS_EPI = 4 * 32 * (WN + 8) * 4;  // staging of the fused dX epilogue
+  static constexpr int LDS_BYTES = LDS_LOOP > LDS_EPI ? LDS_LOOP : LDS_EPI;
+  // XOR swizzle: 16 consecutive rows read the same logical chunk in one ds_read_b128 quarter-wave; with
+  // f(row) = (row / R256) mod CPRW the 16 physical chunks are distinct modulo 256 bytes (64 banks).
+  __device__ static __forceinline__ int swz(int row, int chunk) {
+    return row * PITCH_B + ((chunk ^ ((row / R256) & (CPRW - 1))) << 4);
+  }
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * (BK * 2) + ((chunk ^ (row & 7)) << 4); }
+struct True { static constexpr bool value = true; };
+struct False { static constexpr bool value = false; };
 
-template <int BM, int BN, bool DX_EPI>
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int BKT, int S, bool DX_EPI>
 __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins; the host pass needs only the launch stub
-  using C = TileCfg<BM, BN>;
+  using C = TileCfg<BM, BN, BKT, S>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay scalar
@@ -68,53 +89,59 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const int k_begin = blockIdx.y * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
 
-  // ---- operand staging.  One stage of an operand is R rows x 128 bytes (64 bf16); the 16-byte chunk c of
-  // row r lives at r*128 + ((c ^ (r & 7)) << 4) so that the MFMA fragment reads below are bank-conflict
-  // free.  A wavefront stages groups of 8 rows: lane l covers row 8*grp + (l >> 3) and LDS slot (l & 7),
-  // i.e. the logical chunk (l & 7) ^ (l >> 3); one wave instruction thus fills 1 KiB of contiguous LDS,
-  // which is the shape the direct global->LDS load (global_load_lds_dwordx4) writes.
-  const int lrow = lane >> 3, lch = (lane & 7) ^ lrow;
-  const bf16_t* a_ptr[C::A_CH];
-  const bf16_t* b_ptr[C::B_CH];
+  // ---- operand staging.  One wave instruction of the direct global->LDS load (global_load_lds_dwordx4)
+  // fills 1 KiB of contiguous LDS = RPI tile rows: lane l lands in row RPI*grp + l / CPRW, slot l % CPRW, so
+  // it must fetch the logical chunk slot ^ f(row) of that row (f is the same for every group of a wave).
+  const int lrow = lane / C::CPRW, slot = lane % C::CPRW;
+  const int lch = slot ^ (((wave * C::RPI + lrow) / C::R256) & (C::CPRW - 1));
+  const bf16_t* a_ptr[C::A_G];
+  const bf16_t* b_ptr[C::B_G];
 #pragma unroll
-  for (int j = 0; j < C::A_CH; ++j) {
-    int gm = m0 + (wave + 4 * j) * 8 + lrow;
+  for (int j = 0; j < C::A_G; ++j) {
+    int gm = m0 + (wave + 4 * j) * C::RPI + lrow;
     gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
     const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
     a_ptr[j] = g.A + src * g.lda + lch * 8 + k_begin;
   }
 #pragma unroll
-  for (int j = 0; j < C::B_CH; ++j) {
-    int gn = n0 + (wave + 4 * j) * 8 + lrow;
+  for (int j = 0; j < C::B_G; ++j) {
+    int gn = n0 + (wave + 4 * j) * C::RPI + lrow;
     gn = gn < g.N ? gn : g.N - 1;
     b_ptr[j] = g.B + (int64_t)gn * g.ldb + lch * 8 + k_begin;
   }
   const int span = k_end - k_begin;
-  const int nfull = span > 0 ? span / BK : 0;          // K-steps that need no predicate
-  const int nk = span > 0 ? (span + BK - 1) / BK : 0;
+  const int nfull = span > 0 ? span / BKT : 0;         // stages that need no predicate
+  const int nk = span > 0 ? (span + BKT - 1) / BKT : 0;
 
-  // stage K-step kt into LDS buffer buf
-  auto issue = [&](int kt, int buf) {
+  constexpr int LPS = C::A_G + C::B_G;                 // wave-level 1-KiB loads per stage
+  auto issue_direct = [&](int kt, int buf) {           // a full, unpredicated stage
     char* sa = smem + buf * C::LDS_STAGE;
     char* sb = sa + C::LDS_A;
-    const int koff = kt * BK;
+    const int koff = kt * BKT;
+#pragma unroll
+    for (int j = 0; j < C::A_G; ++j)
+      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < C::B_G; ++j)
+      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
+  };
+  // any stage: a ragged last stage goes through registers.  K is a multiple of 8, so a 16-byte chunk is
+  // all in or all out; missing chunks are written as zeros.
+  auto issue = [&](int kt, int buf) {
     if (kt < nfull) {
-#pragma unroll
-      for (int j = 0; j < C::A_CH; ++j)
-        __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
-#pragma unroll
-      for (int j = 0; j < C::B_CH; ++j)
-        __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
+      issue_direct(kt, buf);
     } else {
-      // ragged last step: K is a multiple of 8, so a 16-byte chunk is all in or all out; missing chunks are 0
+      char* sa = smem + buf * C::LDS_STAGE;
+      char* sb = sa + C::LDS_A;
+      const int koff = kt * BKT;
       const bool ok = (koff + lch * 8) < span;
 #pragma unroll
-      for (int j = 0; j < C::A_CH; ++j) {
+      for (int j = 0; j < C::A_G; ++j) {
         const uint4 v = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
         *reinterpret_cast<uint4*>(sa + (wave + 4 * j) * 1024 + lane * 16) = v;
       }
 #pragma unroll
-      for (int j = 0; j < C::B_CH; ++j) {
+      for (int j = 0; j < C::B_G; ++j) {
         const uint4 v = ok ? *reinterpret_cast<const uint4*>(b_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
         *reinterpret_cast<uint4*>(sb + (wave + 4 * j) * 1024 + lane * 16) = v;
       }
@@ -130,25 +157,17 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int fr = lane & 31, fh = lane >> 5;
-  // byte offsets of this lane's fragment rows inside a stage (swizzle folded in per K-sub-step below)
   const int a_row0 = wm * C::WM + fr, b_row0 = wn * C::WN + fr;
-
-  // ---- main loop.  Software pipeline per stage (4 sub-steps of K = 16):
-  //   sub-steps 0..2: read the fragments of the next sub-step from LDS while the MFMAs of this one run;
-  //   before sub-step 3: wait for this wave's in-flight LDS reads and its global->LDS loads of stage kt+1,
-  //     then barrier (now stage kt+1 is complete and nobody reads stage kt's buffer any more);
-  //   sub-step 3: issue the global->LDS loads of stage kt+2 into the freed buffer and read the first
-  //     fragments of stage kt+1, all under the MFMAs of sub-step 3.
   bf16x8_t af[2][C::TM], bfr[2][C::TN];
   auto load_frags = [&](int buf, int s, int rb) {
     const char* sa = smem + buf * C::LDS_STAGE;
     const char* sb = sa + C::LDS_A;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
-      af[rb][i] = *reinterpret_cast<const bf16x8_t*>(sa + swz(a_row0 + i * 32, 2 * s + fh));
+      af[rb][i] = *reinterpret_cast<const bf16x8_t*>(sa + C::swz(a_row0 + i * 32, 2 * s + fh));
 #pragma unroll
     for (int j = 0; j < C::TN; ++j)
-      bfr[rb][j] = *reinterpret_cast<const bf16x8_t*>(sb + swz(b_row0 + j * 32, 2 * s + fh));
+      bfr[rb][j] = *reinterpret_cast<const bf16x8_t*>(sb + C::swz(b_row0 + j * 32, 2 * s + fh));
   };
   auto mfma_all = [&](int rb) {
 #pragma unroll
@@ -158,63 +177,100 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb][i], bfr[rb][j], acc[i][j], 0, 0, 0);
   };
 
-  // direct loads of a full (unpredicated) stage, no control flow: usable inside a scheduling region
-  auto issue_direct = [&](int kt, int buf) {
+  // ---- main loop, two LDS stages.  Stage kt computes from buffer kt & 1 in NS = 4 sub-steps of K = 16:
+  //   sub-step s < 3: read the fragments of sub-step s+1 while the MFMAs of sub-step s run; sub-steps 0 and 1
+  //     also issue the 2nd and 3rd thirds of the loads of stage kt+1 into the other buffer;
+  //   then wait for this wave's LDS reads and global->LDS loads, and barrier: stage kt+1 is complete for
+  //     everybody and nobody reads this stage's buffer any more;
+  //   sub-step 3: read the first fragments of stage kt+1 and issue the 1st third of the loads of stage kt+2
+  //     into this stage's (now free) buffer, under the MFMAs of sub-step 3.
+  // Every load thus has at least one full sub-step (16 MFMAs per wave) to land, and the texture addresser never
+  // sees more than a third of a stage at once.
+  static_assert(S == 2 && C::NS == 4, "two-stage schedule");
+  constexpr int MF = C::TM * C::TN, NR = C::TM + C::TN;
+  constexpr int P0 = (LPS + 2) / 3, P1 = (LPS - P0 + 1) / 2, P2 = LPS - P0 - P1;   // loads per third
+  auto issue_range = [&](int kt, int buf, int t0, int t1) {
     char* sa = smem + buf * C::LDS_STAGE;
     char* sb = sa + C::LDS_A;
-    const int koff = kt * BK;
+    const int koff = kt * BKT;
 #pragma unroll
-    for (int j = 0; j < C::A_CH; ++j)
-      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int j = 0; j < C::B_CH; ++j)
-      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
-  };
-
-  if (nk > 0) issue(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (nk > 1) issue(1, 1);
-  if (nk > 0) load_frags(0, 0, 0);
-  constexpr int MF = C::TM * C::TN, NR = C::TM + C::TN;   // MFMAs and fragment reads per sub-step
-  auto substeps012 = [&](int cur) {
-#pragma unroll
-    for (int s = 0; s < 3; ++s) {
-      __builtin_amdgcn_sched_barrier(0);
-      load_frags(cur, s + 1, (s + 1) & 1);
-      mfma_all(s & 1);
-#pragma unroll
-      for (int q = 0; q < NR; ++q) {                   // a share of the MFMAs, then one LDS read
-        __builtin_amdgcn_sched_group_barrier(0x008, MF / NR, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
+    for (int t = t0; t < t1; ++t) {
+      if (t < C::A_G)
+        __builtin_amdgcn_global_load_lds(a_ptr[t] + koff, (lds_ptr_t)(sa + (wave + 4 * t) * 1024), 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds(b_ptr[t - C::A_G] + koff,
+                                         (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, 0);
     }
+  };
+  auto sched_pattern = [&](int nloads) {
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {                      // a share of the MFMAs, one LDS read, now and then a load
+      __builtin_amdgcn_sched_group_barrier(0x008, MF / NR, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (q < nloads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+  };
+  auto stage_sync = [&]() {
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
+
+  if (nk > 0) issue(0, 0);
+  wait_vmcnt<0>();
+  __syncthreads();
+  if (1 < nfull) issue_range(1, 1, 0, P0);
+  if (nk > 0) load_frags(0, 0, 0);
   int kt = 0;
-  // steady state: stage kt+2 exists and is a full stage -> branch-free body, one scheduling region per sub-step
+  // steady state: stages kt+1 and kt+2 are full stages -> branch-free body, one scheduling region per sub-step
   for (; kt + 2 < nfull; ++kt) {
     const int cur = kt & 1;
-    substeps012(cur);
-    issue_direct(kt + 2, cur);
-    load_frags(cur ^ 1, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 1, 1);
+#ifndef EFQAT_GEMM_DEBUG_NOLOAD
+    issue_range(kt + 1, cur ^ 1, P0, P0 + P1);
+#endif
+    mfma_all(0);
+    sched_pattern(P1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 2, 0);
+#ifndef EFQAT_GEMM_DEBUG_NOLOAD
+    issue_range(kt + 1, cur ^ 1, P0 + P1, LPS);
+#endif
     mfma_all(1);
-#pragma unroll
-    for (int q = 0; q < MF; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (q < C::A_CH + C::B_CH) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
+    sched_pattern(P2);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 3, 1);
+    mfma_all(0);
+    sched_pattern(0);
+    stage_sync();
+    load_frags(cur ^ 1, 0, 0);
+#ifndef EFQAT_GEMM_DEBUG_NOLOAD
+    issue_range(kt + 2, cur, 0, P0);
+#endif
+    mfma_all(1);
+    sched_pattern(P0);
     __builtin_amdgcn_sched_barrier(0);
   }
-  // drain: the last (up to three) stages, including a ragged one
+  // drain: the last stages, including a ragged one
   for (; kt < nk; ++kt) {
     const int cur = kt & 1;
-    substeps012(cur);
-    if (kt + 2 < nk) issue(kt + 2, cur);
+    if (kt + 1 < nfull) issue_range(kt + 1, cur ^ 1, P0, LPS);   // its first third is already in flight
+    else if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 1, 1);
+    mfma_all(0);
+    sched_pattern(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 2, 0);
+    mfma_all(1);
+    sched_pattern(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(cur, 3, 1);
+    mfma_all(0);
+    sched_pattern(0);
+    stage_sync();
     if (kt + 1 < nk) load_frags(cur ^ 1, 0, 0);
     mfma_all(1);
   }
@@ -342,6 +398,16 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------- host
+#ifndef EFQAT_BIG_BK
+#define EFQAT_BIG_BK 64
+#define EFQAT_BIG_S 2
+#endif
+#ifndef EFQAT_SMALL_BK
+#define EFQAT_SMALL_BK 64
+#define EFQAT_SMALL_S 2
+#endif
+constexpr int BIG_BK = EFQAT_BIG_BK, BIG_S = EFQAT_BIG_S, SMALL_BK = EFQAT_SMALL_BK, SMALL_S = EFQAT_SMALL_S;
+
 static inline bool use_big_tile(int64_t M, int64_t N) {
   // 256x256 tiles when they still give every CU at least ~2 tiles; else 128x128
   return ceil_div(M, 256) * ceil_div(N, 256) >= 512;
@@ -358,7 +424,7 @@ int64_t gemm_nt_grid_mn(int64_t M, int64_t N) {
 
 int gemm_pick_split_k(int64_t M, int64_t N, int64_t K) {
   const int64_t tiles = gemm_nt_grid_mn(M, N);
-  const int64_t ksteps = ceil_div(K, BK);
+  const int64_t ksteps = ceil_div(K, KALIGN);
   int64_t s = ceil_div(1024, tiles);                 // aim at >= 4 blocks per CU
   int64_t max_s = ksteps / 8;                        // but keep >= 8 K-steps (512 elements) per slice
   if (max_s < 1) max_s = 1;
@@ -391,12 +457,12 @@ static void prof_end(int which, hipStream_t st, int slot) {
   if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
 }
 
-template <int BM, int BN, bool DX>
+template <int BM, int BN, int BKT, int S, bool DX>
 static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
-  using C = TileCfg<BM, BN>;
+  using C = TileCfg<BM, BN, BKT, S>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, DX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, BKT, S, DX>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             C::LDS_BYTES) != hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
@@ -404,7 +470,7 @@ static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
   int slot = 0;
   const bool timed = prof_begin(DX ? 0 : 1, st, &slot);
-  hipLaunchKernelGGL((k_gemm_nt<BM, BN, DX>), grid, dim3(256), C::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((k_gemm_nt<BM, BN, BKT, S, DX>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) prof_end(DX ? 0 : 1, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
@@ -419,7 +485,7 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
   GemmArgs a{};
   a.A = A; a.lda = lda; a.a_rows = a_rows; a.B = B; a.ldb = ldb;
   a.M = (int)M; a.N = (int)N; a.K = (int)K;
-  a.k_per_split = (int)(ceil_div(ceil_div(K, BK), split_k) * BK);
+  a.k_per_split = (int)(ceil_div(ceil_div(K, KALIGN), split_k) * KALIGN);
   a.out = out_partial;
   if (epi) {
     a.x_codes = epi->x_codes; a.x_clip = epi->x_clip; a.x = epi->x; a.x_dtype = epi->x_dtype;
@@ -430,8 +496,11 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
   const int bm = big ? 256 : 128;
   a.tiles_m = (int)ceil_div(M, bm);
   a.tiles_n = (int)ceil_div(N, bm);
-  if (big) return epi ? launch_cfg<256, 256, true>(a, 1, stream) : launch_cfg<256, 256, false>(a, split_k, stream);
-  return epi ? launch_cfg<128, 128, true>(a, 1, stream) : launch_cfg<128, 128, false>(a, split_k, stream);
+  if (big)
+    return epi ? launch_cfg<256, 256, BIG_BK, BIG_S, true>(a, 1, stream)
+               : launch_cfg<256, 256, BIG_BK, BIG_S, false>(a, split_k, stream);
+  return epi ? launch_cfg<128, 128, SMALL_BK, SMALL_S, true>(a, 1, stream)
+             : launch_cfg<128, 128, SMALL_BK, SMALL_S, false>(a, split_k, stream);
 }
 
 }  // namespace efqat
