@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
 // of the weight quantizer and the per-row scale gradient
 //   dW[c][j] = in range ? dW_q : 0,  dS_w[c] = sum_j dW_q * (in range ? code - w/S_w : code),  c = idx[m].
 __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ part, int S, int64_t k, int64_t ncols,
-                                                   const float* __restrict__ s_x, const int8_t* __restrict__ w_codes,
+                                                   int vec, const float* __restrict__ s_x,
+                                                   const int8_t* __restrict__ w_codes,
                                                    const uint32_t* __restrict__ w_clip, const float* __restrict__ w,
                                                    const float* __restrict__ s_w, const int32_t* __restrict__ idx,
                                                    float* __restrict__ dw, int scatter, float* __restrict__ ds_w) {
@@ -163,16 +164,43 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
   const float sx = s_x[0];
   const float sw = s_w[c];
   const int64_t orow = scatter ? c : m;
+  const int64_t slice = k * ncols;
   float acc = 0.0f;
-  for (int64_t j = threadIdx.x; j < ncols; j += 256) {
-    float a = 0.0f;
-    for (int s = 0; s < S; ++s) a += part[((int64_t)s * k + m) * ncols + j];
-    const float dwq = sx * a;
-    const bool inr = (w_clip[c * wpr + (j >> 5)] >> (j & 31)) & 1u;
-    const float code = (float)w_codes[c * ncols + j];
-    const float gs = inr ? (code - w[c * ncols + j] / sw) : code;
-    acc += dwq * gs;
-    dw[orow * ncols + j] = inr ? dwq : 0.0f;
+  if (vec) {                                          // ncols % 4 == 0 and 16-byte aligned rows
+    for (int64_t j = (int64_t)threadIdx.x * 4; j < ncols; j += 1024) {
+      const float* p = part + m * ncols + j;
+      float4 a = *reinterpret_cast<const float4*>(p);
+      for (int s = 1; s < S; ++s) {
+        const float4 b = *reinterpret_cast<const float4*>(p + (int64_t)s * slice);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+      }
+      const float dwq[4] = {sx * a.x, sx * a.y, sx * a.z, sx * a.w};
+      const uint32_t bits = w_clip[c * wpr + (j >> 5)] >> (j & 31);
+      const uint32_t cw = *reinterpret_cast<const uint32_t*>(w_codes + c * ncols + j);
+      const float4 wv = *reinterpret_cast<const float4*>(w + c * ncols + j);
+      const float wf[4] = {wv.x, wv.y, wv.z, wv.w};
+      float o[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const bool inr = (bits >> t) & 1u;
+        const float code = (float)(int8_t)((cw >> (8 * t)) & 0xFFu);
+        const float gs = inr ? (code - wf[t] / sw) : code;
+        acc += dwq[t] * gs;
+        o[t] = inr ? dwq[t] : 0.0f;
+      }
+      *reinterpret_cast<float4*>(dw + orow * ncols + j) = make_float4(o[0], o[1], o[2], o[3]);
+    }
+  } else {
+    for (int64_t j = threadIdx.x; j < ncols; j += 256) {
+      float a = 0.0f;
+      for (int s = 0; s < S; ++s) a += part[(int64_t)s * slice + m * ncols + j];
+      const float dwq = sx * a;
+      const bool inr = (w_clip[c * wpr + (j >> 5)] >> (j & 31)) & 1u;
+      const float code = (float)w_codes[c * ncols + j];
+      const float gs = inr ? (code - w[c * ncols + j] / sw) : code;
+      acc += dwq * gs;
+      dw[orow * ncols + j] = inr ? dwq : 0.0f;
+    }
   }
   acc = wave_sum(acc);
   __shared__ float red[4];
@@ -348,8 +376,10 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   const int64_t Kw = p.need_sel ? p.ldt : T_out;
   rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.split_k, part_dw, nullptr, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.split_k, io.k, p.Nw, io.s_x,
-                     io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w);
+  const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
+                    ((uintptr_t)io.w_codes % 4) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.split_k, io.k, p.Nw, fvec,
+                     io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }

@@ -140,6 +140,7 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
     const int64_t seg = item - row * segs;
     const int64_t col0 = seg * 512 + (int64_t)lane * 8;
     const float s = (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) ? s_act : scale[row];
+    const float inv_s = __fdiv_rn(1.0f, s);
     const int64_t base = row * cols + col0;
     float v[8];
     const bool full = col0 + 8 <= cols;
@@ -154,8 +155,15 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
     float dq[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float q = __fdiv_rn(v[j], s);          // correctly rounded quotient decides the code
-      const float c = rintf(q) + z;                // un-clamped code
+      // The code is defined on the correctly rounded quotient x/s.  x * (1/s) is within 1.5 ulp of it, so the
+      // two round to the same integer unless x/s sits that close to a half-way point; only then is the exact
+      // (slow) division needed (always for huge quotients, where the tolerance exceeds one half, and for a
+      // scale so small that its reciprocal overflows).
+      const float qf = v[j] * inv_s;
+      float r = rintf(qf);
+      const float tol = 2.5e-7f * fabsf(qf);
+      if (!(0.5f - fabsf(qf - r) > tol) || !(inv_s < 3.0e38f)) r = rintf(__fdiv_rn(v[j], s));
+      const float c = r + z;                       // un-clamped code
       const bool inr = (c >= lo) && (c <= hi);
       const float cc = fminf(fmaxf(c, lo), hi);
       const int ci = (int)cc;

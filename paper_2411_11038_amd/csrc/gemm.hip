@@ -17,6 +17,9 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
+#ifndef EFQAT_GEMM_AUX
+#define EFQAT_GEMM_AUX 0   // cache-policy bits of the global->LDS tile loads (sc0 = 1, nt = 2, sc1 = 16)
+#endif
 constexpr int KALIGN = 64;  // split-K slices start on multiples of this many K elements
 
 struct GemmArgs {
@@ -85,6 +88,11 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const int tm = first_m + (pid % per_group) % gsize;
   const int tn = (pid % per_group) / gsize;
   const int m0 = tm * BM, n0 = tn * BN;
+#ifdef EFQAT_GEMM_DEBUG_SAMETILE
+  const int lm0 = 0, ln0 = 0;
+#else
+  const int lm0 = m0, ln0 = n0;
+#endif
 
   const int k_begin = blockIdx.y * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
@@ -98,14 +106,14 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const bf16_t* b_ptr[C::B_G];
 #pragma unroll
   for (int j = 0; j < C::A_G; ++j) {
-    int gm = m0 + (wave + 4 * j) * C::RPI + lrow;
+    int gm = lm0 + (wave + 4 * j) * C::RPI + lrow;
     gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
     const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
     a_ptr[j] = g.A + src * g.lda + lch * 8 + k_begin;
   }
 #pragma unroll
   for (int j = 0; j < C::B_G; ++j) {
-    int gn = n0 + (wave + 4 * j) * C::RPI + lrow;
+    int gn = ln0 + (wave + 4 * j) * C::RPI + lrow;
     gn = gn < g.N ? gn : g.N - 1;
     b_ptr[j] = g.B + (int64_t)gn * g.ldb + lch * 8 + k_begin;
   }
@@ -120,10 +128,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     const int koff = kt * BKT;
 #pragma unroll
     for (int j = 0; j < C::A_G; ++j)
-      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, EFQAT_GEMM_AUX);
 #pragma unroll
     for (int j = 0; j < C::B_G; ++j)
-      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, EFQAT_GEMM_AUX);
   };
   // any stage: a ragged last stage goes through registers.  K is a multiple of 8, so a 16-byte chunk is
   // all in or all out; missing chunks are written as zeros.
@@ -196,10 +204,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #pragma unroll
     for (int t = t0; t < t1; ++t) {
       if (t < C::A_G)
-        __builtin_amdgcn_global_load_lds(a_ptr[t] + koff, (lds_ptr_t)(sa + (wave + 4 * t) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(a_ptr[t] + koff, (lds_ptr_t)(sa + (wave + 4 * t) * 1024), 16, 0, EFQAT_GEMM_AUX);
       else
         __builtin_amdgcn_global_load_lds(b_ptr[t - C::A_G] + koff,
-                                         (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, 0);
+                                         (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, EFQAT_GEMM_AUX);
     }
   };
   auto sched_pattern = [&](int nloads) {
@@ -423,14 +431,16 @@ int64_t gemm_nt_grid_mn(int64_t M, int64_t N) {
 }
 
 int gemm_pick_split_k(int64_t M, int64_t N, int64_t K) {
+  // Enough slices that every CU gets about two blocks, but each slice keeps >= 8 K-steps of 64 and the
+  // fp32 partial tiles (written once, read once by the second pass) stay a small part of the traffic.
   const int64_t tiles = gemm_nt_grid_mn(M, N);
   const int64_t ksteps = ceil_div(K, KALIGN);
-  int64_t s = ceil_div(1024, tiles);                 // aim at >= 4 blocks per CU
-  int64_t max_s = ksteps / 8;                        // but keep >= 8 K-steps (512 elements) per slice
+  int64_t s = ceil_div(512, tiles);
+  int64_t max_s = ksteps / 8;
   if (max_s < 1) max_s = 1;
   if (s > max_s) s = max_s;
   if (s < 1) s = 1;
-  if (s > 64) s = 64;
+  if (s > 32) s = 32;
   return (int)s;
 }
 

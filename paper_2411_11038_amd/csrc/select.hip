@@ -1,5 +1,5 @@
-// Channel importance (Eq. 6) and deterministic Top-K (Sec. 3.2): scores in fp64, selection by exact
-// rank under the key (score descending, index ascending), output compacted in ascending index order.
+// Channel importance (Eq. 6) and deterministic Top-K (Sec. 3.2): scores in fp64, exact selection under the
+// key (score descending, index ascending) by radix select, output compacted in ascending index order.
 #include "common.hpp"
 
 namespace efqat {
@@ -25,54 +25,80 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
   if (lane == 0) scores[row] = acc / (double)n;
 }
 
-// flag[c] = 1 iff fewer than k channels precede c in the order (score desc, index asc).
-__global__ __launch_bounds__(256) void k_rank_flags(const double* __restrict__ scores, int64_t n, int64_t k,
-                                                    int32_t* __restrict__ flags) {
-  __shared__ double tile[1024];
-  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const double mine = c < n ? scores[c] : 0.0;
-  int64_t rank = 0;
-  for (int64_t j0 = 0; j0 < n; j0 += 1024) {
-    const int64_t cnt = (n - j0) < 1024 ? (n - j0) : 1024;
+// Exact Top-K by radix select, one 1024-thread block.  Scores are non-negative doubles, so their bit
+// patterns order like the values.  Eight passes over the bytes of the 64-bit key (most significant first)
+// find the key T of the k-th largest score and `need`, the number of scores equal to T that still belong to
+// the selection; then one ordered sweep writes every index whose score is > T, plus the first `need` indices
+// (ascending) whose score equals T: ties go to the lower index, output is ascending.  Integer counting only,
+// so the result does not depend on thread scheduling.
+__global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
+                                                     int32_t* __restrict__ idx) {
+  __shared__ unsigned int hist[256];
+  __shared__ unsigned long long s_prefix;
+  __shared__ long long s_need;
+  __shared__ int wsum_gt[16], wsum_eq[16];
+  __shared__ long long s_base_gt, s_base_eq;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid == 0) { s_prefix = 0ull; s_need = k; }
+  for (int pass = 7; pass >= 0; --pass) {
+    if (tid < 256) hist[tid] = 0u;
     __syncthreads();
-    for (int64_t t = threadIdx.x; t < cnt; t += blockDim.x) tile[t] = scores[j0 + t];
+    const unsigned long long prefix = s_prefix;
+    for (int64_t i = tid; i < n; i += 1024) {
+      const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
+      const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
+      if (match) atomicAdd(&hist[(key >> (8 * pass)) & 255ull], 1u);
+    }
     __syncthreads();
-    if (c < n) {
-      for (int64_t t = 0; t < cnt; ++t) {
-        const double o = tile[t];
-        rank += (o > mine) || (o == mine && (j0 + t) < c);
+    if (wv == 0) {
+      // digit search by the first wavefront: lane l owns bins 4l..4l+3; suffix sums (bins above) by shuffles
+      const long long need = s_need;
+      const long long h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+      const long long tot = h0 + h1 + h2 + h3;
+      long long inc = tot;                              // inclusive suffix sum over lanes >= l
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const long long t = __shfl_down(inc, o, kWave);
+        if (lane + o < 64) inc += t;
+      }
+      long long a = inc - tot;                          // keys in bins above this lane's four
+      if (a < need && need <= a + tot) {                // exactly one lane holds the crossing
+        int d;
+        if (a + h3 >= need) d = 3;
+        else { a += h3; if (a + h2 >= need) d = 2; else { a += h2; if (a + h1 >= need) d = 1; else { a += h1; d = 0; } } }
+        s_need = need - a;                              // still to take among keys whose byte equals d
+        s_prefix = (prefix << 8) | (unsigned long long)(4 * lane + d);
       }
     }
+    __syncthreads();
   }
-  if (c < n) flags[c] = rank < k ? 1 : 0;
-}
-
-// Ordered compaction of the flagged indices (single block, chunks of 1024 in ascending order).
-__global__ __launch_bounds__(1024) void k_compact(const int32_t* __restrict__ flags, int64_t n, int64_t k,
-                                                  int32_t* __restrict__ idx) {
-  __shared__ int32_t wsum[16];
-  __shared__ int32_t s_base;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  if (threadIdx.x == 0) s_base = 0;
+  const unsigned long long T = s_prefix;
+  const long long need = s_need;
+  if (tid == 0) { s_base_gt = 0; s_base_eq = 0; }
   __syncthreads();
   for (int64_t c0 = 0; c0 < n; c0 += 1024) {
-    const int64_t c = c0 + threadIdx.x;
-    const int f = (c < n) ? flags[c] : 0;
-    const unsigned long long b = __ballot(f);
-    const int before = __popcll(b & ((1ull << lane) - 1ull));
-    if (lane == 0) wsum[wv] = __popcll(b);
+    const int64_t c = c0 + tid;
+    unsigned long long key = 0ull;
+    if (c < n) key = (unsigned long long)__double_as_longlong(scores[c]);
+    const bool gt = (c < n) && key > T;
+    const bool eq = (c < n) && key == T;
+    const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (lane == 0) { wsum_gt[wv] = __popcll(bg); wsum_eq[wv] = __popcll(be); }
     __syncthreads();
-    int off = s_base;
-    for (int i = 0; i < wv; ++i) off += wsum[i];
-    if (f) {
-      const int64_t pos = (int64_t)off + before;
+    long long gt_before = s_base_gt + __popcll(bg & below);
+    long long eq_before = s_base_eq + __popcll(be & below);
+    for (int i = 0; i < wv; ++i) { gt_before += wsum_gt[i]; eq_before += wsum_eq[i]; }
+    const bool take = gt || (eq && eq_before < need);
+    if (take) {
+      const long long pos = gt_before + (eq_before < need ? eq_before : need);
       if (pos < k) idx[pos] = (int32_t)c;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int i = 0; i < 16; ++i) t += wsum[i];
-      s_base += t;
+    if (tid == 0) {
+      long long a = 0, e = 0;
+      for (int i = 0; i < 16; ++i) { a += wsum_gt[i]; e += wsum_eq[i]; }
+      s_base_gt += a; s_base_eq += e;
     }
     __syncthreads();
   }
@@ -80,16 +106,20 @@ __global__ __launch_bounds__(1024) void k_compact(const int32_t* __restrict__ fl
 
 // CWPN helpers: per-layer counts of selected channels, and global -> per-layer local indices.
 __global__ void k_layer_counts(const int64_t* __restrict__ layer_off, int64_t n_layers,
-                               const int32_t* __restrict__ flags, int32_t* __restrict__ k_per_layer) {
-  // one wavefront per layer, deterministic integer count
-  const int lane = threadIdx.x & 63;
-  const int64_t l = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+                               const int32_t* __restrict__ idx, int64_t k_total,
+                               int32_t* __restrict__ k_per_layer) {
+  // idx holds ascending global indices: the count of a layer is a difference of two lower bounds
+  const int64_t l = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (l >= n_layers) return;
-  int cnt = 0;
-  for (int64_t c = layer_off[l] + lane; c < layer_off[l + 1]; c += 64) cnt += flags[c];
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, kWave);
-  if (lane == 0) k_per_layer[l] = cnt;
+  auto lower_bound = [&](int64_t v) {
+    int64_t lo = 0, hi = k_total;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)idx[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+  };
+  k_per_layer[l] = (int32_t)(lower_bound(layer_off[l + 1]) - lower_bound(layer_off[l]));
 }
 __global__ void k_localize(const int64_t* __restrict__ layer_off, int64_t n_layers, int64_t k_total,
                             int32_t* __restrict__ idx) {
@@ -115,7 +145,7 @@ extern "C" int64_t efqat_k_from_ratio(int64_t c_out, int64_t num, int64_t den) {
 
 extern "C" size_t efqat_channel_select_workspace_bytes(int64_t c_out) {
   if (c_out <= 0) return 0;
-  return (size_t)(round_up(c_out * (int64_t)sizeof(double), 256) + round_up(c_out * (int64_t)sizeof(int32_t), 256));
+  return (size_t)round_up(c_out * (int64_t)sizeof(double), 256);
 }
 
 extern "C" int efqat_channel_select(const float* w, int64_t c_out, int64_t block, int64_t k, double* scores,
@@ -128,23 +158,20 @@ extern "C" int efqat_channel_select(const float* w, int64_t c_out, int64_t block
   hipStream_t st = (hipStream_t)stream;
   WsCarver carve(ws);
   double* sc = (double*)carve.take((size_t)c_out * sizeof(double));
-  int32_t* flags = (int32_t*)carve.take((size_t)c_out * sizeof(int32_t));
   double* sc_out = scores ? scores : sc;
   const int vec = (((uintptr_t)w % 16) == 0 && block % 4 == 0) ? 1 : 0;
   hipLaunchKernelGGL(k_row_importance, dim3((unsigned)ceil_div(c_out, 4)), dim3(256), 0, st, w, c_out, block, vec,
                      sc_out);
   EFQAT_LAUNCH_CHECK();
   if (k == 0) return EFQAT_OK;
-  hipLaunchKernelGGL(k_rank_flags, dim3((unsigned)ceil_div(c_out, 256)), dim3(256), 0, st, sc_out, c_out, k, flags);
-  EFQAT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, flags, c_out, k, idx);
+  hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, sc_out, c_out, k, idx);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
 
 extern "C" size_t efqat_network_select_workspace_bytes(int64_t total) {
-  if (total <= 0) return 0;
-  return (size_t)round_up(total * (int64_t)sizeof(int32_t), 256);
+  (void)total;
+  return 256;   // no scratch needed; kept so callers can treat every entry point alike
 }
 
 extern "C" int efqat_network_select(const double* scores, const int64_t* layer_off, int64_t n_layers,
@@ -156,16 +183,15 @@ extern "C" int efqat_network_select(const double* scores, const int64_t* layer_o
   if (ws_bytes < efqat_network_select_workspace_bytes(total)) return EFQAT_ERR_WORKSPACE;
   if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
   hipStream_t st = (hipStream_t)stream;
-  int32_t* flags = (int32_t*)ws;
-  hipLaunchKernelGGL(k_rank_flags, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st, scores, total, k_total,
-                     flags);
-  EFQAT_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_layer_counts, dim3((unsigned)ceil_div(n_layers, 4)), dim3(256), 0, st, layer_off, n_layers,
-                     flags, k_per_layer);
+  // k_per_layer is derived from idx; with k_total == 0 every count is 0 and idx is never read
+  if (k_total > 0) {
+    hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, scores, total, k_total, idx);
+    EFQAT_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_layer_counts, dim3((unsigned)ceil_div(n_layers, 256)), dim3(256), 0, st, layer_off, n_layers,
+                     idx, k_total, k_per_layer);
   EFQAT_LAUNCH_CHECK();
   if (k_total > 0) {
-    hipLaunchKernelGGL(k_compact, dim3(1), dim3(1024), 0, st, flags, total, k_total, idx);
-    EFQAT_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_localize, dim3((unsigned)ceil_div(k_total, 256)), dim3(256), 0, st, layer_off, n_layers,
                        k_total, idx);
     EFQAT_LAUNCH_CHECK();
