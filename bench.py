@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain device copy of 256 MiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -218,6 +220,13 @@ def main():
                    k=ks, step="fakequant(X,W) + select + restricted backward, every layer"),
                roofline=roofline, sweep=sweep,
                paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        a.fill_(1)
+        for _ in range(5):
+            b.copy_(a)                                  # reads 256 MiB, writes 256 MiB per launch
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, num, den, cfg["a_bits"], w_bits)
     print(json.dumps(out))
