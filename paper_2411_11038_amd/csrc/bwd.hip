@@ -239,7 +239,7 @@ struct BwdPlan {
   int64_t ldt;     // Tw rounded up to 8
   bool need_dyn;   // token-major bf16 copy of dY needed
   bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
-  int split_k;
+  GemmPlan plan_dx, plan_dw;
   size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, total;
 };
 
@@ -253,15 +253,16 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.need_dyn = !direct_tok;
   const bool direct_rows = dy_layout == EFQAT_DY_CHANNEL_MAJOR && dy_dtype == EFQAT_BF16 && (T_out % 8) == 0;
   p.need_sel = k > 0 && !direct_rows;
-  p.split_k = k > 0 ? gemm_pick_split_k(k, p.Nw, p.ldt) : 1;
+  p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false);
+  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
   p.b_colA = im2col ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
-  p.b_part_dx = (size_t)gemm_nt_grid_mn(p.Mx, c_in) * 2 * sizeof(float); cv.take(p.b_part_dx);
+  p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
   p.b_xcT = k > 0 ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (size_t)k * p.ldt * 2 : 0; cv.take(p.b_sel);
-  p.b_part_dw = k > 0 ? (size_t)p.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
+  p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
 }
@@ -331,10 +332,10 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     A = colA; lda = p.Kx;
   }
   GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
-  rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, 1, nullptr, &epi, st);
+  rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx, gemm_nt_grid_mn(p.Mx, c_in), io.ds_x,
-                     io.dz_x);
+  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx,
+                     (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n, io.ds_x, io.dz_x);
   EFQAT_LAUNCH_CHECK();
 
   if (io.k == 0) return EFQAT_OK;
@@ -374,11 +375,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     Aw = sel; ldaw = p.ldt; a_rows = nullptr;
   }
   const int64_t Kw = p.need_sel ? p.ldt : T_out;
-  rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.split_k, part_dw, nullptr, st);
+  rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.plan_dw, part_dw, nullptr, st);
   if (rc) return rc;
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0) ? 1 : 0;
-  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.split_k, io.k, p.Nw, fvec,
+  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw, fvec,
                      io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;

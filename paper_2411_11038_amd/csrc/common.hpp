@@ -96,15 +96,23 @@ struct GemmEpilogueDx {   // fused STE + activation-qparam partial sums (Eq. 5 l
 // true when the fused epilogue may use 8-element vector accesses on x_codes / x / dx
 bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N);
 
+// Launch shape of one product: square block tile (256, 192 or 128), split-K factor, tile grid.
+struct GemmPlan {
+  int tile;
+  int split_k;
+  int tiles_m, tiles_n;
+};
+// Pure host function of the problem size (so the workspace query and the call agree).  allow_split = false
+// for the product with the fused dX epilogue.
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split);
+
 // C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
 //   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.
-//   split_k > 1: K is cut in split_k contiguous slices, slice s goes to out_partial + s*M*N (raw fp32).
-//   epi != nullptr (split_k must be 1): fused dX epilogue instead of the raw store.
+//   plan.split_k > 1: K is cut in contiguous slices, slice s goes to out_partial + s*M*N (raw fp32).
+//   epi != nullptr (split_k must be 1): fused dX epilogue instead of the raw store; it writes one
+//   (dS_x, dZ_x) partial pair per block, plan.tiles_m * plan.tiles_n pairs in all.
 int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb,
-                   int64_t M, int64_t N, int64_t K, int split_k, float* out_partial,
+                   int64_t M, int64_t N, int64_t K, const GemmPlan& plan, float* out_partial,
                    const GemmEpilogueDx* epi, hipStream_t stream);
-// number of thread blocks launch_gemm_nt uses for (M, N) (for sizing GemmEpilogueDx::partial)
-int64_t gemm_nt_grid_mn(int64_t M, int64_t N);
-int gemm_pick_split_k(int64_t M, int64_t N, int64_t K);
 
 }  // namespace efqat

@@ -61,6 +61,20 @@ struct TileCfg {
 struct True { static constexpr bool value = true; };
 struct False { static constexpr bool value = false; };
 
+// Scheduling hint for one MFMA sub-step: NR groups of (a share of the MF MFMAs, one LDS fragment read), the
+// first NL groups followed by one global->LDS load.  The group sizes must be compile-time constants.
+template <int MF, int NR, int NL, int Q>
+struct SchedPattern {
+  static __device__ __forceinline__ void run() {
+    if constexpr (Q < NR) {
+      __builtin_amdgcn_sched_group_barrier(0x008, ((Q + 1) * MF) / NR - (Q * MF) / NR, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if constexpr (Q < NL) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      SchedPattern<MF, NR, NL, Q + 1>::run();
+    }
+  }
+};
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -210,14 +224,6 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
                                          (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, EFQAT_GEMM_AUX);
     }
   };
-  auto sched_pattern = [&](int nloads) {
-#pragma unroll
-    for (int q = 0; q < NR; ++q) {                      // a share of the MFMAs, one LDS read, now and then a load
-      __builtin_amdgcn_sched_group_barrier(0x008, MF / NR, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      if (q < nloads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-  };
   auto stage_sync = [&]() {
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -240,25 +246,25 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     issue_range(kt + 1, cur ^ 1, P0, P0 + P1);
 #endif
     mfma_all(0);
-    sched_pattern(P1);
+    SchedPattern<MF, NR, P1, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 2, 0);
 #ifndef EFQAT_GEMM_DEBUG_NOLOAD
     issue_range(kt + 1, cur ^ 1, P0 + P1, LPS);
 #endif
     mfma_all(1);
-    sched_pattern(P2);
+    SchedPattern<MF, NR, P2, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 3, 1);
     mfma_all(0);
-    sched_pattern(0);
+    SchedPattern<MF, NR, 0, 0>::run();
     stage_sync();
     load_frags(cur ^ 1, 0, 0);
 #ifndef EFQAT_GEMM_DEBUG_NOLOAD
     issue_range(kt + 2, cur, 0, P0);
 #endif
     mfma_all(1);
-    sched_pattern(P0);
+    SchedPattern<MF, NR, P0, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
   }
   // drain: the last stages, including a ragged one
@@ -269,15 +275,15 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 1, 1);
     mfma_all(0);
-    sched_pattern(0);
+    SchedPattern<MF, NR, 0, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 2, 0);
     mfma_all(1);
-    sched_pattern(0);
+    SchedPattern<MF, NR, 0, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 3, 1);
     mfma_all(0);
-    sched_pattern(0);
+    SchedPattern<MF, NR, 0, 0>::run();
     stage_sync();
     if (kt + 1 < nk) load_frags(cur ^ 1, 0, 0);
     mfma_all(1);
@@ -306,7 +312,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     // 8 consecutive columns of one row: 8-byte code loads, 16-byte x loads and 16-byte dX stores.
     constexpr int PITCH = C::WN + 8;                   // floats; 4*PITCH = 32 (mod 64) banks
     constexpr int CPR = C::WN / 8;                     // 8-column chunks per row
-    constexpr int RPP = 64 / CPR;                      // rows per pass of the wavefront
+    constexpr int RPP = 64 / CPR;                      // rows per pass of the wavefront (lanes beyond RPP*CPR idle)
+    constexpr int NPASS = (32 + RPP - 1) / RPP;
     float* stage = reinterpret_cast<float*>(smem) + wave * 32 * PITCH;
     const float s = g.s_x[0];
     const float z = rintf(g.z_x[0]);
@@ -315,48 +322,73 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     const int row_l0 = lane / CPR, ch = lane % CPR;
     const int gcol = n0 + wn * C::WN + ch * 8;
     float ps = 0.0f, pz = 0.0f;
+    const bool lane_on = row_l0 < RPP && gcol < g.N;
+    if (g.epi_vec) {
+      // Vector path (N % 8 == 0, aligned pointers): a lane's 8-column chunk is entirely inside the matrix.
+      // The global inputs of 32-row slab i+1 are fetched while slab i is computed, so their latency is hidden
+      // even with a single resident block per CU.
+      struct Inputs { uint2 cw; uint4 xa, xb; uint32_t mb; };
+      Inputs in[2][NPASS];
+      auto fetch = [&](int i, int b) {
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i) {
-      if (i > 0) __syncthreads();
+        for (int p = 0; p < NPASS; ++p) {
+          const int row_l = p * RPP + row_l0;
+          const int grow = m0 + wm * C::WM + i * 32 + row_l;
+          if (lane_on && row_l < 32 && grow < g.M) {
+            const int64_t e = (int64_t)grow * g.N + gcol;
+            in[b][p].mb = g.x_clip[(int64_t)grow * wpr + (gcol >> 5)] >> (gcol & 31);
+            in[b][p].cw = *reinterpret_cast<const uint2*>(g.x_codes + e);
+            if (g.x_dtype == EFQAT_F32) {
+              in[b][p].xa = *reinterpret_cast<const uint4*>((const float*)g.x + e);
+              in[b][p].xb = *reinterpret_cast<const uint4*>((const float*)g.x + e + 4);
+            } else {
+              in[b][p].xa = *reinterpret_cast<const uint4*>((const bf16_t*)g.x + e);
+            }
+          }
+        }
+      };
+      fetch(0, 0);
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j)
+      for (int i = 0; i < C::TM; ++i) {
+        const int b = i & 1;
+        if (i > 0) __syncthreads();
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
-      __syncthreads();
+        for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-      for (int p = 0; p < 32 / RPP; ++p) {
-        const int row_l = p * RPP + row_l0;
-        const int grow = m0 + wm * C::WM + i * 32 + row_l;
-        if (grow < g.M && gcol < g.N) {
-          const float4 a0 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8);
-          const float4 a1 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8 + 4);
-          const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-          const int64_t e = (int64_t)grow * g.N + gcol;
-          const uint32_t mbits = g.x_clip[(int64_t)grow * wpr + (gcol >> 5)] >> (gcol & 31);
-          float o[8];
-          if (g.epi_vec && gcol + 8 <= g.N) {
-            const uint2 cw = *reinterpret_cast<const uint2*>(g.x_codes + e);
+          for (int r = 0; r < 16; ++r)
+            stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
+        __syncthreads();
+        if (i + 1 < C::TM) fetch(i + 1, b ^ 1);
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+          const int row_l = p * RPP + row_l0;
+          const int grow = m0 + wm * C::WM + i * 32 + row_l;
+          if (lane_on && row_l < 32 && grow < g.M) {
+            const float4 a0 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8);
+            const float4 a1 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8 + 4);
+            const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const int64_t e = (int64_t)grow * g.N + gcol;
+            const Inputs& q8 = in[b][p];
             float xv[8];
             if (g.x_dtype == EFQAT_F32) {
-              const float4 x0 = *reinterpret_cast<const float4*>((const float*)g.x + e);
-              const float4 x1 = *reinterpret_cast<const float4*>((const float*)g.x + e + 4);
-              xv[0] = x0.x; xv[1] = x0.y; xv[2] = x0.z; xv[3] = x0.w;
-              xv[4] = x1.x; xv[5] = x1.y; xv[6] = x1.z; xv[7] = x1.w;
+              xv[0] = __uint_as_float(q8.xa.x); xv[1] = __uint_as_float(q8.xa.y);
+              xv[2] = __uint_as_float(q8.xa.z); xv[3] = __uint_as_float(q8.xa.w);
+              xv[4] = __uint_as_float(q8.xb.x); xv[5] = __uint_as_float(q8.xb.y);
+              xv[6] = __uint_as_float(q8.xb.z); xv[7] = __uint_as_float(q8.xb.w);
             } else {
-              const uint4 xr = *reinterpret_cast<const uint4*>((const bf16_t*)g.x + e);
-              const uint32_t xw[4] = {xr.x, xr.y, xr.z, xr.w};
+              const uint32_t xw[4] = {q8.xa.x, q8.xa.y, q8.xa.z, q8.xa.w};
 #pragma unroll
               for (int t = 0; t < 4; ++t) {
                 xv[2 * t] = __uint_as_float(xw[t] << 16);
                 xv[2 * t + 1] = __uint_as_float(xw[t] & 0xFFFF0000u);
               }
             }
+            float o[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-              const uint32_t byte = ((t < 4 ? cw.x : cw.y) >> (8 * (t & 3))) & 0xFFu;
+              const uint32_t byte = ((t < 4 ? q8.cw.x : q8.cw.y) >> (8 * (t & 3))) & 0xFFu;
               const float q = (float)byte - z;
-              const bool inr = (mbits >> t) & 1u;
+              const bool inr = (q8.mb >> t) & 1u;
               const float gs = inr ? fmaf(xv[t], ninv_s, q) : q;
               ps = fmaf(a[t], gs, ps);
               o[t] = inr ? a[t] : 0.0f;
@@ -370,19 +402,38 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
                   make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
                              pack_bf16x2(o[6], o[7]));
             }
-          } else {
+          }
+        }
+      }
+    } else {
+      // Element-wise path for ragged widths / unaligned pointers.
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i) {
+        if (i > 0) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+          const int row_l = p * RPP + row_l0;
+          const int grow = m0 + wm * C::WM + i * 32 + row_l;
+          if (lane_on && row_l < 32 && grow < g.M) {
+            const int64_t e = (int64_t)grow * g.N + gcol;
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
               if (gcol + t < g.N) {
+                const float av = stage[row_l * PITCH + ch * 8 + t];
                 const float q = (float)g.x_codes[e + t] - z;
                 const float xv = g.x_dtype == EFQAT_F32 ? ((const float*)g.x)[e + t]
                                                         : bf16_to_f32(((const bf16_t*)g.x)[e + t]);
-                // the mask word may end inside this chunk: re-read per element
                 const bool inr = (g.x_clip[(int64_t)grow * wpr + ((gcol + t) >> 5)] >> ((gcol + t) & 31)) & 1u;
                 const float gs = inr ? fmaf(xv, ninv_s, q) : q;
-                ps = fmaf(a[t], gs, ps);
-                const float ov = inr ? a[t] : 0.0f;
-                pz += a[t] - ov;
+                ps = fmaf(av, gs, ps);
+                const float ov = inr ? av : 0.0f;
+                pz += av - ov;
                 if (g.dx_dtype == EFQAT_F32) ((float*)g.dx)[e + t] = ov;
                 else ((bf16_t*)g.dx)[e + t] = f32_to_bf16(ov);
               }
@@ -406,42 +457,46 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------- host
-#ifndef EFQAT_BIG_BK
-#define EFQAT_BIG_BK 64
-#define EFQAT_BIG_S 2
-#endif
-#ifndef EFQAT_SMALL_BK
-#define EFQAT_SMALL_BK 64
-#define EFQAT_SMALL_S 2
-#endif
-constexpr int BIG_BK = EFQAT_BIG_BK, BIG_S = EFQAT_BIG_S, SMALL_BK = EFQAT_SMALL_BK, SMALL_S = EFQAT_SMALL_S;
+// Tile / split-K choice: a small cost model in CU clock cycles, evaluated on the host and calibrated on
+// measured runs of this kernel (rates in flop per clock per block):
+//   - a T x T block runs its K loop at `rate`: 256 -> 2500, 192 -> 2100, 128 -> 1000 with two blocks resident
+//     per CU.  The big tiles are bounded by what one CU's vector L1 pulls from L2 (about 19 B/clk) times their
+//     flop per byte, the small one additionally by its doubled L2 traffic;
+//   - per block: launch/prologue 4000 cycles plus the epilogue, 0.75 cycles per output element for the fused
+//     dX epilogue (it streams x, codes, mask and dX through HBM), 0.6 when a second resident block overlaps it,
+//     0.3 for the raw fp32 store;
+//   - blocks run in rounds of 256 CUs x blocks-per-CU;  split-K adds its fp32 partial tiles, written and read once.
+struct TileModel { int t; int bpc; double rate; double epi_dx; };
+static const TileModel kTiles[3] = {{256, 1, 2500.0, 0.75}, {192, 1, 2100.0, 0.75}, {128, 2, 1000.0, 0.6}};
 
-static inline bool use_big_tile(int64_t M, int64_t N) {
-  // 256x256 tiles when they still give every CU at least ~2 tiles; else 128x128
-  return ceil_div(M, 256) * ceil_div(N, 256) >= 512;
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split) {
+  GemmPlan best{};
+  double best_t = 1e300;
+  const int64_t ksteps = ceil_div(K, KALIGN);
+  for (const TileModel& tm : kTiles) {
+    const int64_t tiles = ceil_div(M, tm.t) * ceil_div(N, tm.t);
+    int64_t max_s = allow_split ? ksteps / 8 : 1;
+    if (max_s < 1) max_s = 1;
+    if (max_s > 32) max_s = 32;
+    for (int64_t s = 1; s <= max_s; ++s) {
+      const int64_t kslice = ceil_div(ksteps, s) * KALIGN;
+      const double per_elem = allow_split ? 0.3 : tm.epi_dx;
+      const double block = 2.0 * tm.t * tm.t * (double)kslice / tm.rate + 4000.0 + per_elem * tm.t * tm.t;
+      const double rounds = (double)ceil_div(tiles * s, 256 * tm.bpc);
+      double t = rounds * block;
+      if (allow_split) t += (double)s * (double)M * (double)N * 8.0 / 2400.0;   // partial tiles at ~5 TB/s
+      if (t < best_t) {
+        best_t = t;
+        best.tile = tm.t; best.split_k = (int)s;
+        best.tiles_m = (int)ceil_div(M, tm.t); best.tiles_n = (int)ceil_div(N, tm.t);
+      }
+    }
+  }
+  return best;
 }
 
 bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N) {
   return (N % 8) == 0 && ((uintptr_t)e.x_codes % 8) == 0 && ((uintptr_t)e.x % 16) == 0 && ((uintptr_t)e.dx % 16) == 0;
-}
-
-int64_t gemm_nt_grid_mn(int64_t M, int64_t N) {
-  if (use_big_tile(M, N)) return ceil_div(M, 256) * ceil_div(N, 256);
-  return ceil_div(M, 128) * ceil_div(N, 128);
-}
-
-int gemm_pick_split_k(int64_t M, int64_t N, int64_t K) {
-  // Enough slices that every CU gets about two blocks, but each slice keeps >= 8 K-steps of 64 and the
-  // fp32 partial tiles (written once, read once by the second pass) stay a small part of the traffic.
-  const int64_t tiles = gemm_nt_grid_mn(M, N);
-  const int64_t ksteps = ceil_div(K, KALIGN);
-  int64_t s = ceil_div(512, tiles);
-  int64_t max_s = ksteps / 8;
-  if (max_s < 1) max_s = 1;
-  if (s > max_s) s = max_s;
-  if (s < 1) s = 1;
-  if (s > 32) s = 32;
-  return (int)s;
 }
 
 // ---- optional event timing of the contraction kernels (benchmarks only; off by default)
@@ -487,10 +542,11 @@ static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
 }
 
 int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb, int64_t M,
-                   int64_t N, int64_t K, int split_k, float* out_partial, const GemmEpilogueDx* epi,
+                   int64_t N, int64_t K, const GemmPlan& plan, float* out_partial, const GemmEpilogueDx* epi,
                    hipStream_t stream) {
   if (M <= 0 || N <= 0 || K <= 0 || (K % 8) || (lda % 8) || (ldb % 8)) return EFQAT_ERR_BAD_SHAPE;
   if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return EFQAT_ERR_BAD_SHAPE;
+  const int split_k = plan.split_k;
   if (epi && split_k != 1) return EFQAT_ERR_BAD_SHAPE;
   GemmArgs a{};
   a.A = A; a.lda = lda; a.a_rows = a_rows; a.B = B; a.ldb = ldb;
@@ -502,15 +558,18 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
     a.s_x = epi->s_x; a.z_x = epi->z_x; a.dx = epi->dx; a.dx_dtype = epi->dx_dtype; a.partial = epi->partial;
     a.epi_vec = gemm_epilogue_vec_ok(*epi, N) ? 1 : 0;
   }
-  const bool big = use_big_tile(M, N);
-  const int bm = big ? 256 : 128;
-  a.tiles_m = (int)ceil_div(M, bm);
-  a.tiles_n = (int)ceil_div(N, bm);
-  if (big)
-    return epi ? launch_cfg<256, 256, BIG_BK, BIG_S, true>(a, 1, stream)
-               : launch_cfg<256, 256, BIG_BK, BIG_S, false>(a, split_k, stream);
-  return epi ? launch_cfg<128, 128, SMALL_BK, SMALL_S, true>(a, 1, stream)
-             : launch_cfg<128, 128, SMALL_BK, SMALL_S, false>(a, split_k, stream);
+  a.tiles_m = plan.tiles_m;
+  a.tiles_n = plan.tiles_n;
+  switch (plan.tile) {
+    case 256:
+      return epi ? launch_cfg<256, 256, 64, 2, true>(a, 1, stream) : launch_cfg<256, 256, 64, 2, false>(a, split_k, stream);
+    case 192:
+      return epi ? launch_cfg<192, 192, 64, 2, true>(a, 1, stream) : launch_cfg<192, 192, 64, 2, false>(a, split_k, stream);
+    case 128:
+      return epi ? launch_cfg<128, 128, 64, 2, true>(a, 1, stream) : launch_cfg<128, 128, 64, 2, false>(a, split_k, stream);
+    default:
+      return EFQAT_ERR_BAD_SHAPE;
+  }
 }
 
 }  // namespace efqat
