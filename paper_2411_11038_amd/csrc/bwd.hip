@@ -19,35 +19,78 @@ template <> __device__ __forceinline__ float rd<uint8_t>(const uint8_t* p, int64
 //   rs(i) = rowscale ? rowscale[i] : 1 (per-output-channel weight scale)
 //   sub   = subz ? round(subz[0]) : 0  (activation zero point)
 // `out` row j starts at out + j*ldo + out_off (ldo = pitch in elements).
+template <typename T> struct Vec4 { };
+template <> struct Vec4<float> { typedef float4 type; };
+template <> struct Vec4<bf16_t> { typedef uint2 type; };
+template <> struct Vec4<int8_t> { typedef uint32_t type; };
+template <> struct Vec4<uint8_t> { typedef uint32_t type; };
+__device__ __forceinline__ void unpack4(const float4& v, float (&o)[4]) { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+__device__ __forceinline__ void unpack4(const uint2& v, float (&o)[4]) {
+  o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+}
+template <typename T>
+__device__ __forceinline__ void unpack4b(uint32_t v, float (&o)[4]) {
+#pragma unroll
+  for (int t = 0; t < 4; ++t) o[t] = (float)(T)((v >> (8 * t)) & 0xFFu);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in, int64_t ld_in, int64_t R,
                                                         int64_t Cn, const int32_t* __restrict__ colmap,
                                                         const float* __restrict__ rowscale,
                                                         const float* __restrict__ subz, bf16_t* __restrict__ out,
-                                                        int64_t ldo, int64_t out_off, int64_t i_pad) {
-  __shared__ bf16_t tile[64][66];
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+                                                        int64_t ldo, int64_t out_off, int64_t i_pad, int vec) {
+  __shared__ bf16_t tile[64][66];                     // tile[i][j]
   const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
   const float sub = subz ? rintf(subz[0]) : 0.0f;
-  const int64_t j = j0 + tx;
-  const int64_t jc = (j < Cn) ? (colmap ? (int64_t)colmap[j] : j) : 0;
-#pragma unroll 4
-  for (int rr = 0; rr < 16; ++rr) {
-    const int li = ty + 4 * rr;
-    const int64_t i = i0 + li;
-    float v = 0.0f;
-    if (i < R && j < Cn) {
-      v = rd<T>(in, i * ld_in + jc) - sub;
-      if (rowscale) v *= rowscale[i];
+  if (vec && j0 + 64 <= Cn) {
+    // dense source, 4 consecutive columns per lane (one 4..16-byte load)
+    const int jq = (threadIdx.x & 15) * 4, ib = threadIdx.x >> 4;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int li = ib + 16 * rr;
+      const int64_t i = i0 + li;
+      float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (i < R) {
+        const typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(in + i * ld_in + j0 + jq);
+        if constexpr (sizeof(T) == 1) unpack4b<T>(raw, v); else unpack4(raw, v);
+        const float rs = rowscale ? rowscale[i] : 1.0f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = (v[t] - sub) * rs;
+      }
+      *reinterpret_cast<uint32_t*>(&tile[li][jq]) = pack_bf16x2(v[0], v[1]);
+      *reinterpret_cast<uint32_t*>(&tile[li][jq + 2]) = pack_bf16x2(v[2], v[3]);
     }
-    tile[li][tx] = f32_to_bf16(v);
+  } else {
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t j = j0 + tx;
+    const int64_t jc = (j < Cn) ? (colmap ? (int64_t)colmap[j] : j) : 0;
+#pragma unroll 4
+    for (int rr = 0; rr < 16; ++rr) {
+      const int li = ty + 4 * rr;
+      const int64_t i = i0 + li;
+      float v = 0.0f;
+      if (i < R && j < Cn) {
+        v = rd<T>(in, i * ld_in + jc) - sub;
+        if (rowscale) v *= rowscale[i];
+      }
+      tile[li][tx] = f32_to_bf16(v);
+    }
   }
   __syncthreads();
-#pragma unroll 4
-  for (int rr = 0; rr < 16; ++rr) {
-    const int lj = ty + 4 * rr;
-    const int64_t jo = j0 + lj, io = i0 + tx;
-    if (jo < Cn && io < i_pad) out[jo * ldo + out_off + io] = tile[tx][lj];
+  // out[j][i0 + 8a .. 8a+7]: one 16-byte store per lane, 8 lanes cover the 128 bytes of one output row
+  const int a8 = (threadIdx.x & 7) * 8, jb = threadIdx.x >> 3;
+#pragma unroll
+  for (int ww = 0; ww < 2; ++ww) {
+    const int lj = jb + 32 * ww;
+    const int64_t jo = j0 + lj, io = i0 + a8;
+    if (jo < Cn && io < i_pad) {
+      uint32_t w[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) w[t] = (uint32_t)tile[a8 + 2 * t][lj] | ((uint32_t)tile[a8 + 2 * t + 1][lj] << 16);
+      *reinterpret_cast<uint4*>(out + jo * ldo + out_off + io) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
   }
 }
 
@@ -223,8 +266,11 @@ static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, 
                              int64_t i_pad, hipStream_t st) {
   dim3 grid((unsigned)ceil_div(i_pad, 64), (unsigned)ceil_div(Cn, 64));
   if (grid.y > 65535) return EFQAT_ERR_BAD_SHAPE;
+  // 16-byte stores need an 8-element aligned destination; 4-wide loads a dense, 4-element aligned source
+  if ((ldo % 8) || (out_off % 8) || (i_pad % 8) || ((uintptr_t)out % 16)) return EFQAT_ERR_ALIGNMENT;
+  const int vec = (!colmap && (ld_in % 4) == 0 && ((uintptr_t)in % (4 * sizeof(T))) == 0) ? 1 : 0;
   hipLaunchKernelGGL((k_transpose_bf16<T>), grid, dim3(256), 0, st, in, ld_in, R, Cn, colmap, rowscale, subz, out,
-                     ldo, out_off, i_pad);
+                     ldo, out_off, i_pad, vec);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
