@@ -85,41 +85,15 @@ __global__ __launch_bounds__(256) void k_act_qparams(const float* __restrict__ p
   }
 }
 
-// Eq. 4 per row: S_w[c] = max_j |w[c][j]| / (2^(b-1) - 1).  One wavefront per row.
-template <typename T>
-__global__ __launch_bounds__(256) void k_row_absmax_scale(const T* __restrict__ x, int64_t rows, int64_t cols,
-                                                          int vec, int bits, float* __restrict__ scale) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const T* p = x + row * cols;
-  float m = 0.0f;
-  if (vec) {
-    const int64_t n8 = cols >> 3;
-    for (int64_t i = lane; i < n8; i += 64) {
-      float v[8];
-      load8<T>(p + i * 8, v);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[j]));
-    }
-  } else {
-    for (int64_t i = lane; i < cols; i += 64) m = fmaxf(m, fabsf(load_as_f32<T>(p, i)));
-  }
-  m = wave_max(m);
-  if (lane == 0) {
-    float s = __fdiv_rn(m, (float)((1 << (bits - 1)) - 1));
-    if (!(s > 0.0f)) s = 1.0f;                       // all-zero row
-    scale[row] = s;
-  }
-}
-
 // ----------------------------------------------------------------------------------------------
 // Eq. 1 / Eq. 3: codes + clip-mask bits (+ optional de-quantised bf16 values).
 // One wavefront handles one 512-element segment of one row per iteration; a lane owns 8
 // consecutive elements, four neighbouring lanes assemble one 32-bit mask word.
-template <typename T, int MODE>
+// INIT (weights only): the wavefront first takes the row's abs-max and writes its Eq. 4 scale
+// S_w[c] = max_j |w[c][j]| / (2^(b-1) - 1), then quantizes the row it has just pulled through the caches.
+template <typename T, int MODE, bool INIT>
 __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64_t rows, int64_t cols, int vec,
-                                                  int bits, const float* __restrict__ scale,
+                                                  int bits, float* __restrict__ scale,
                                                   const float* __restrict__ zp, uint8_t* __restrict__ codes,
                                                   uint32_t* __restrict__ clip, bf16_t* __restrict__ xq) {
   const int lane = threadIdx.x & 63;
@@ -139,7 +113,31 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
     const int64_t row = item / segs;
     const int64_t seg = item - row * segs;
     const int64_t col0 = seg * 512 + (int64_t)lane * 8;
-    const float s = (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) ? s_act : scale[row];
+    float s;
+    if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
+      s = s_act;
+    } else if (INIT) {
+      // every segment's wavefront scans the whole row (it is small and cache resident): identical result
+      const T* p = x + row * cols;
+      float m = 0.0f;
+      if (vec) {
+        const int64_t n8 = cols >> 3;
+        for (int64_t i = lane; i < n8; i += 64) {
+          float t8[8];
+          load8<T>(p + i * 8, t8);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(t8[j]));
+        }
+      } else {
+        for (int64_t i = lane; i < cols; i += 64) m = fmaxf(m, fabsf(load_as_f32<T>(p, i)));
+      }
+      m = wave_max(m);
+      s = __fdiv_rn(m, hi);
+      if (!(s > 0.0f)) s = 1.0f;                     // all-zero row
+      if (seg == 0 && lane == 0) scale[row] = s;
+    } else {
+      s = scale[row];
+    }
     const float inv_s = __fdiv_rn(1.0f, s);
     const int64_t base = row * cols + col0;
     float v[8];
@@ -164,11 +162,13 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
       const float tol = 2.5e-7f * fabsf(qf);
       if (!(0.5f - fabsf(qf - r) > tol) || !(inv_s < 3.0e38f)) r = rintf(__fdiv_rn(v[j], s));
       const float c = r + z;                       // un-clamped code
-      const bool inr = (c >= lo) && (c <= hi);
-      const float cc = fminf(fmaxf(c, lo), hi);
-      const int ci = (int)cc;
+      const float cc = __builtin_amdgcn_fmed3f(c, lo, hi);
+      const bool inr = (c == cc);                  // closed interval: a code on the bound is not clipped
       if (inr && (col0 + j < cols)) bits8 |= (1u << j);
-      cw[j >> 2] |= ((uint32_t)(ci & 0xFF)) << (8 * (j & 3));
+      if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
+        cw[j >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(cc, j & 3, cw[j >> 2]);   // cc is an integer in [0, 255]
+      else
+        cw[j >> 2] |= ((uint32_t)((int)cc & 0xFF)) << (8 * (j & 3));
       dq[j] = s * (cc - z);
     }
     if (vec && full) {
@@ -205,29 +205,26 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
   const int64_t n = rows * cols;
   const int vec_flat = aligned_to(x, 16) ? 1 : 0;
   const int vec_row = (vec_flat && cols % 8 == 0 && aligned_to(codes, 8) && (!xq || aligned_to(xq, 16))) ? 1 : 0;
-  if (init_minmax) {
-    if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
-      int nparts = (int)(ceil_div(n, 256 * 32) < 1024 ? ceil_div(n, 256 * 32) : 1024);
-      float* part = (float*)ws;
-      hipLaunchKernelGGL((k_minmax_partial<T>), dim3(nparts), dim3(256), 0, st, x, n, vec_flat, part);
-      EFQAT_LAUNCH_CHECK();
-      hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(256), 0, st, part, nparts, bits, scale, zp);
-      EFQAT_LAUNCH_CHECK();
-    } else {
-      const int vr = (vec_flat && cols % 8 == 0) ? 1 : 0;
-      hipLaunchKernelGGL((k_row_absmax_scale<T>), dim3((unsigned)ceil_div(rows, 4)), dim3(256), 0, st, x, rows,
-                         cols, vr, bits, scale);
-      EFQAT_LAUNCH_CHECK();
-    }
+  if (init_minmax && mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
+    int64_t np64 = ceil_div(n, 256 * 16);
+    const int nparts = (int)(np64 < 1024 ? np64 : 1024);
+    float* part = (float*)ws;
+    hipLaunchKernelGGL((k_minmax_partial<T>), dim3(nparts), dim3(256), 0, st, x, n, vec_flat, part);
+    EFQAT_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(256), 0, st, part, nparts, bits, scale, zp);
+    EFQAT_LAUNCH_CHECK();
   }
   const int64_t items = rows * ceil_div(cols, 512);
   int64_t blocks = ceil_div(items, 4);
   if (blocks > 256 * 32) blocks = 256 * 32;
   if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
-    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
+    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM, false>), dim3((unsigned)blocks), dim3(256), 0,
+                       st, x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
+  else if (init_minmax)
+    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, true>), dim3((unsigned)blocks), dim3(256), 0, st, x,
+                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   else
-    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM>), dim3((unsigned)blocks), dim3(256), 0, st, x,
+    hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, false>), dim3((unsigned)blocks), dim3(256), 0, st, x,
                        rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;

@@ -33,35 +33,90 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
 // so the result does not depend on thread scheduling.
 __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
                                                      int32_t* __restrict__ idx) {
-  __shared__ unsigned int hist[256];
-  __shared__ unsigned long long s_prefix;
+  __shared__ unsigned int hist[16][256];              // one histogram per wavefront: 16x less atomic contention
+  __shared__ unsigned int total[256];
+  __shared__ unsigned long long s_prefix, s_or[16], s_and[16];
   __shared__ long long s_need;
   __shared__ int wsum_gt[16], wsum_eq[16];
   __shared__ long long s_base_gt, s_base_eq;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (tid == 0) { s_prefix = 0ull; s_need = k; }
-  for (int pass = 7; pass >= 0; --pass) {
-    if (tid < 256) hist[tid] = 0u;
-    __syncthreads();
-    const unsigned long long prefix = s_prefix;
+  // Up to KPT keys per thread stay in registers for all passes (n <= 12288); longer inputs are re-read.
+  constexpr int KPT = 12;
+  unsigned long long keys[KPT];
+  const bool cached = n <= (int64_t)KPT * 1024;
+  // Bytes on which all keys agree need no pass: find them from the OR and AND of all keys.
+  unsigned long long vor = 0ull, vand = ~0ull;
+  if (cached) {
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int64_t i = (int64_t)q * 1024 + tid;
+      keys[q] = 0ull;
+      if (i < n) {
+        keys[q] = (unsigned long long)__double_as_longlong(scores[i]);
+        vor |= keys[q]; vand &= keys[q];
+      }
+    }
+  } else {
     for (int64_t i = tid; i < n; i += 1024) {
       const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
-      const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
-      if (match) atomicAdd(&hist[(key >> (8 * pass)) & 255ull], 1u);
+      vor |= key; vand &= key;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    vor |= __shfl_xor(vor, o, kWave);
+    vand &= __shfl_xor(vand, o, kWave);
+  }
+  if (lane == 0) { s_or[wv] = vor; s_and[wv] = vand; }
+  __syncthreads();
+  vor = 0ull; vand = ~0ull;
+  for (int i = 0; i < 16; ++i) { vor |= s_or[i]; vand &= s_and[i]; }
+  const unsigned long long diff = vor ^ vand;          // bits that differ between some two keys
+  int first_pass = 7;
+  while (first_pass > 0 && (diff >> (8 * first_pass)) == 0ull) --first_pass;
+  if (tid == 0) {
+    s_prefix = first_pass == 7 ? 0ull : (vor >> (8 * (first_pass + 1)));   // the shared high bytes
+    s_need = k;
+  }
+  for (int b = tid; b < 16 * 256; b += 1024) (&hist[0][0])[b] = 0u;
+  __syncthreads();
+  for (int pass = first_pass; pass >= 0; --pass) {
+    const unsigned long long prefix = s_prefix;
+    if (cached) {
+#pragma unroll
+      for (int q = 0; q < KPT; ++q) {
+        const int64_t i = (int64_t)q * 1024 + tid;
+        const unsigned long long key = keys[q];
+        const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
+        if (i < n && match) atomicAdd(&hist[wv][(key >> (8 * pass)) & 255ull], 1u);
+      }
+    } else {
+      for (int64_t i = tid; i < n; i += 1024) {
+        const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
+        const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
+        if (match) atomicAdd(&hist[wv][(key >> (8 * pass)) & 255ull], 1u);
+      }
+    }
+    __syncthreads();
+    if (tid < 256) {                                    // fold the 16 per-wave histograms, clear them for the next pass
+      unsigned int t = 0;
+      for (int w = 0; w < 16; ++w) { t += hist[w][tid]; hist[w][tid] = 0u; }
+      total[tid] = t;
     }
     __syncthreads();
     if (wv == 0) {
       // digit search by the first wavefront: lane l owns bins 4l..4l+3; suffix sums (bins above) by shuffles
-      const long long need = s_need;
-      const long long h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-      const long long tot = h0 + h1 + h2 + h3;
-      long long inc = tot;                              // inclusive suffix sum over lanes >= l
+      const int need = (int)s_need;                     // counts fit 32 bits: n <= INT32_MAX
+      const int h0 = (int)total[4 * lane], h1 = (int)total[4 * lane + 1], h2 = (int)total[4 * lane + 2],
+                h3 = (int)total[4 * lane + 3];
+      const int tot = h0 + h1 + h2 + h3;
+      int inc = tot;                                    // inclusive suffix sum over lanes >= l
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
-        const long long t = __shfl_down(inc, o, kWave);
+        const int t = __shfl_down(inc, o, kWave);
         if (lane + o < 64) inc += t;
       }
-      long long a = inc - tot;                          // keys in bins above this lane's four
+      int a = inc - tot;                                // keys in bins above this lane's four
       if (a < need && need <= a + tot) {                // exactly one lane holds the crossing
         int d;
         if (a + h3 >= need) d = 3;
