@@ -109,35 +109,37 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
   } else {
     hi = (float)((1 << (bits - 1)) - 1); lo = -hi;
   }
-  for (int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); item < total; item += nwaves) {
-    const int64_t row = item / segs;
-    const int64_t seg = item - row * segs;
+  // work item = (row, 512-element segment); with INIT a wavefront keeps the whole row (one abs-max scan, then
+  // all its segments) so the row is read from HBM once
+  const int64_t nitems = INIT ? rows : total;
+  for (int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); item < nitems; item += nwaves) {
+   const int64_t row = INIT ? item : item / segs;
+   float s_row = 1.0f;
+   if (INIT) {
+     const T* p = x + row * cols;
+     float m = 0.0f;
+     if (vec) {
+       const int64_t n8 = cols >> 3;
+       for (int64_t i = lane; i < n8; i += 64) {
+         float t8[8];
+         load8<T>(p + i * 8, t8);
+#pragma unroll
+         for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(t8[j]));
+       }
+     } else {
+       for (int64_t i = lane; i < cols; i += 64) m = fmaxf(m, fabsf(load_as_f32<T>(p, i)));
+     }
+     m = wave_max(m);
+     s_row = __fdiv_rn(m, hi);
+     if (!(s_row > 0.0f)) s_row = 1.0f;             // all-zero row
+     if (lane == 0) scale[row] = s_row;
+   }
+   for (int64_t seg = INIT ? 0 : item - row * segs; seg < (INIT ? segs : item - row * segs + 1); ++seg) {
     const int64_t col0 = seg * 512 + (int64_t)lane * 8;
     float s;
-    if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
-      s = s_act;
-    } else if (INIT) {
-      // every segment's wavefront scans the whole row (it is small and cache resident): identical result
-      const T* p = x + row * cols;
-      float m = 0.0f;
-      if (vec) {
-        const int64_t n8 = cols >> 3;
-        for (int64_t i = lane; i < n8; i += 64) {
-          float t8[8];
-          load8<T>(p + i * 8, t8);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(t8[j]));
-        }
-      } else {
-        for (int64_t i = lane; i < cols; i += 64) m = fmaxf(m, fabsf(load_as_f32<T>(p, i)));
-      }
-      m = wave_max(m);
-      s = __fdiv_rn(m, hi);
-      if (!(s > 0.0f)) s = 1.0f;                     // all-zero row
-      if (seg == 0 && lane == 0) scale[row] = s;
-    } else {
-      s = scale[row];
-    }
+    if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) s = s_act;
+    else if (INIT) s = s_row;
+    else s = scale[row];
     const float inv_s = __fdiv_rn(1.0f, s);
     const int64_t base = row * cols + col0;
     float v[8];
@@ -192,6 +194,7 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
     word |= __shfl_xor(word, 2, kWave);
     const int64_t widx = col0 >> 5;
     if ((lane & 3) == 0 && widx < wpr) clip[row * wpr + widx] = word;
+   }
   }
 }
 
@@ -214,7 +217,8 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
     hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(256), 0, st, part, nparts, bits, scale, zp);
     EFQAT_LAUNCH_CHECK();
   }
-  const int64_t items = rows * ceil_div(cols, 512);
+  const bool row_items = init_minmax && mode == EFQAT_QUANT_W_PER_ROW_SYM;   // one wavefront per row
+  const int64_t items = row_items ? rows : rows * ceil_div(cols, 512);
   int64_t blocks = ceil_div(items, 4);
   if (blocks > 256 * 32) blocks = 256 * 32;
   if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
