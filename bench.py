@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the dX product kernel, mean of the two layers of config 2 with token-major dY: from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_bert_ffn_r25_kernel_stats.md
+# (FFN1 143.3 MB read + 18.9 MB written, FFN2 245.6 MB + 75.6 MB).  Not measurable live; other workloads: null.
+DX_KERNEL_TRAFFIC_BYTES = {("cfg2", 0): 0.5 * (143.3e6 + 18.9e6 + 245.6e6 + 75.6e6)}
 
 
 def parse_args():
@@ -104,29 +108,27 @@ def time_region(torch, fn, steps):
 
 
 def cpu_baseline(layers, num, den, a_bits, w_bits):
-    """The oracle, as it stands, on the host cores: one backward of the first layer on a token sample."""
-    import numpy as np
+    """The oracle, as it stands, on the host cores: one whole step (every layer, all tokens)."""
     from oracle import efqat_oracle as orc
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    lay = layers[0]
-    X, W, dY = lay.host
-    Ts = min(lay.T, 4096)
-    X, dY = X[:Ts], dY[:Ts]
     t0 = time.perf_counter()
-    sx, zx = orc.act_qparams_minmax(X, a_bits)
-    sw = orc.weight_scale_minmax(W, w_bits)
-    k = orc.k_from_ratio(lay.c_out, num, den)
-    idx = orc.top_k_channels(orc.channel_importance(W), k)
-    orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
+    fl = 0.0
+    for lay in layers:
+        X, W, dY = lay.host
+        sx, zx = orc.act_qparams_minmax(X, a_bits)
+        sw = orc.weight_scale_minmax(W, w_bits)
+        k = orc.k_from_ratio(lay.c_out, num, den)
+        idx = orc.top_k_channels(orc.channel_importance(W), k)
+        orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
+        fl += lay.flops(k)
     dt = time.perf_counter() - t0
-    fl = 2.0 * Ts * lay.c_in * (lay.c_out + k)
     return dict(value=fl / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
-                sample="layer %s, first %d of %d tokens, r=%d/%d, whole hot path (quantize, select, backward), "
-                       "fp64 NumPy, %.2f s" % (lay.name, Ts, lay.T, num, den, dt))
+                sample="one whole step of the same workload (%s; all tokens; r=%d/%d; quantize, select, backward), "
+                       "fp64 NumPy, %.1f s" % (", ".join(l.name for l in layers), num, den, dt))
 
 
 def main():
@@ -175,7 +177,9 @@ def main():
     dx_avg_s = dx_ms / max(dx_n, 1) / 1e3
     achieved = dx_flops / dx_avg_s / 1e12 if dx_n else 0.0
     roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None, kernel="k_gemm_nt<dX epilogue>",
+                    frac=achieved / PEAK_BF16_TFLOPS,
+                    traffic=DX_KERNEL_TRAFFIC_BYTES.get((args.workload, args.dy_layout)),
+                    kernel="k_gemm_nt<dX epilogue>", algorithmic_flops_per_launch=dx_flops,
                     avg_kernel_ms=dx_avg_s * 1e3, launches=int(dx_n),
                     dw_kernel_avg_ms=(dw_ms / dw_n) if dw_n else None)
 
