@@ -214,6 +214,30 @@ def main():
         for row, key in zip(sweep, fr):
             row["speedup_vs_full"] = full / times[key]
 
+    # low-precision forward (int8 matrix cores), not part of the step or of `value`: the paper leaves the forward
+    # pass out of its timings
+    fwd = None
+    if not args.no_sweep:
+        ys = [torch.empty((l.T, l.c_out), dtype=l.x.dtype if l.x.dtype == torch.bfloat16 else torch.float32,
+                          device="cuda") for l in layers]
+        fws = [torch.empty(max(ef.lib().efqat_linear_fwd_workspace_bytes(l.T, l.c_in, l.c_out), 256),
+                           dtype=torch.uint8, device="cuda") for l in layers]
+
+        def fwd_all():
+            for l, y, w_ in zip(layers, ys, fws):
+                ef.linear_fwd(l.fx["codes"], l.fx["scale"], l.fx["zero_point"], l.fw["codes"], l.fw["scale"],
+                              ws=w_, out=y)
+        for _ in range(3):
+            fwd_all()
+        ef.profile_enable(True)
+        tf = time_region(torch, fwd_all, max(3, args.steps // 2))
+        kms, kn = ef.profile_read(2)
+        ef.profile_enable(False)
+        ops = sum(2.0 * l.T * l.c_in * l.c_out for l in layers)
+        fwd = dict(ms=tf * 1e3, tops=ops / tf / 1e12, kernel_ms=kms / max(kn, 1) * len(layers),
+                   kernel_tops=ops / (kms / max(kn, 1) * len(layers) / 1e3) / 1e12 if kn else None,
+                   peak_tops=5000.0, note="Y = X_q W_q^T from the 8-bit codes, v_mfma_i32_32x32x32_i8, all layers")
+
     out = dict(metric="QAT backward time + TFLOP/s per layer vs update fraction; speedup over full bwd",
                value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
@@ -222,7 +246,7 @@ def main():
                    args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
                    num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
                    k=ks, step="fakequant(X,W) + select + restricted backward, every layer"),
-               roofline=roofline, sweep=sweep,
+               roofline=roofline, sweep=sweep, forward_int8=fwd,
                paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")

@@ -188,6 +188,21 @@ int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64
                    int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                    float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------ low-precision forward
+ * The forward product of Sec. 3.1, Y = X_q W_q^T, computed from the 8-bit codes on the int8 matrix
+ * cores with exact int32 accumulation:
+ *   y[t][c] = S_x * S_w[c] * sum_i (x_codes[t][i] - round(Z_x)) * w_codes[c][i]
+ * (the paper leaves this pass out of its timings; it is here because it consumes exactly what
+ * efqat_fakequant_fwd emits).
+ *   x_codes  in  uint8 [T][c_in];  w_codes  in  int8 [c_out][c_in];  s_x, z_x float[1];  s_w float[c_out]
+ *   y        out [T][c_out], dtype y_dtype (F32 or BF16)
+ *   c_in <= 131072.  Codes must be 16-byte aligned unless c_in is not a multiple of 16 (then they
+ *   are copied into zero-padded rows in the workspace). */
+size_t efqat_linear_fwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out);
+int efqat_linear_fwd(const uint8_t* x_codes, const float* s_x, const float* z_x, const int8_t* w_codes,
+                     const float* s_w, int64_t T, int64_t c_in, int64_t c_out, void* y, int y_dtype,
+                     void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ kernel timing (benchmarks)
  * The two products of Eq. 5 dominate the backward pass; to report them against the matrix-core
  * roofline a benchmark can have every product kernel bracketed by HIP events on the stream it is
@@ -196,7 +211,7 @@ int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64
  *   efqat_profile_enable(on)  on != 0 starts a new measurement (counters reset), 0 stops it.
  *                             At most 4096 launches per product are recorded.
  *   efqat_profile_read(which, total_ms, launches)  which = 0: input-gradient product (dX),
- *                             1: weight-gradient product (dW).  Waits for the recorded events
+ *                             1: weight-gradient product (dW), 2: forward product.  Waits for the recorded events
  *                             (host pointers out: summed kernel time in ms, number of launches). */
 int efqat_profile_enable(int on);
 int efqat_profile_read(int which, double* total_ms, int64_t* launches);

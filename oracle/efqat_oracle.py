@@ -164,6 +164,16 @@ def grad_weight_scale(dWq_rows, W_rows, codes_rows, mask_rows, S_w_rows):
 
 
 # --------------------------------------------------------------------------
+# Linear forward (Sec. 3.1, "Computational Bottleneck of QAT Schemes")
+# --------------------------------------------------------------------------
+def linear_fwd(X, S_x, Z_x, a_bits, W, S_w, w_bits):
+    """Y = X_q W_q^T with the fake-quantised operands of Eq. 1 / Eq. 3 (PyTorch Linear convention)."""
+    _, _, Xq = fakequant_act(X, S_x, Z_x, a_bits)
+    _, _, Wq = fakequant_weight(W, S_w, w_bits)
+    return Xq @ Wq.T
+
+
+# --------------------------------------------------------------------------
 # Linear backward (Eq. 5, Alg. 1 backward step)
 # --------------------------------------------------------------------------
 def linear_bwd(dY, X, S_x, Z_x, a_bits, W, S_w, w_bits, idx):

@@ -18,6 +18,7 @@ EXPORTS = [
     "efqat_network_select_workspace_bytes", "efqat_network_select",
     "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
     "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd",
+    "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
     "efqat_profile_enable", "efqat_profile_read",
 ]
 
@@ -72,6 +73,10 @@ def lib():
     L.efqat_conv_bwd.restype = ci
     L.efqat_conv_bwd.argtypes = ([vp, ci, ci] + [i64] * 9 + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
                                  + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_linear_fwd_workspace_bytes.restype = sz
+    L.efqat_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64]
+    L.efqat_linear_fwd.restype = ci
+    L.efqat_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
     L.efqat_profile_enable.restype = ci
     L.efqat_profile_enable.argtypes = [ci]
     L.efqat_profile_read.restype = ci
@@ -235,6 +240,20 @@ def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, d
                             ws.numel(), _stream())
     _check(rc, "efqat_linear_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)
+
+
+def linear_fwd(x_codes, s_x, z_x, w_codes, s_w, y_dtype=torch.bfloat16, ws=None, out=None):
+    """Low-precision forward Y = X_q W_q^T from the integer codes (int8 matrix cores).  Returns y [T, c_out]."""
+    L = lib()
+    T, c_in = x_codes.shape
+    c_out = w_codes.shape[0]
+    y = out if out is not None else torch.empty((T, c_out), dtype=y_dtype, device=x_codes.device)
+    if ws is None:
+        ws = _ws(L.efqat_linear_fwd_workspace_bytes(T, c_in, c_out), x_codes)
+    rc = L.efqat_linear_fwd(_p(x_codes), _p(s_x), _p(z_x), _p(w_codes), _p(s_w), T, c_in, c_out, _p(y), _dt(y),
+                            _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_linear_fwd")
+    return y
 
 
 def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, stride=1, pad=0,

@@ -115,4 +115,10 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
                    int64_t M, int64_t N, int64_t K, const GemmPlan& plan, float* out_partial,
                    const GemmEpilogueDx* epi, hipStream_t stream);
 
+// Forward product on int8 matrix cores: y[m][n] = S_x * S_w[n] * sum_k (x_codes[m][k] - round(Z_x)) * w_codes[n][k].
+// K, lda, ldb multiples of 16; wsum[n] = sum_k w_codes[n][k].
+int launch_gemm_fwd_i8(const uint8_t* x_codes, int64_t lda, const int8_t* w_codes, int64_t ldb, int64_t M, int64_t N,
+                       int64_t K, const GemmPlan& plan, const float* s_x, const float* z_x, const float* s_w,
+                       const int32_t* wsum, void* y, int y_dtype, hipStream_t stream);
+
 }  // namespace efqat

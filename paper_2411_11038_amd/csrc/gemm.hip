@@ -11,10 +11,14 @@
 // four MFMA sub-steps.  Split-K writes raw fp32 partial tiles (deterministic second-pass reduction).
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace efqat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef int intx4_t __attribute__((ext_vector_type(4)));
+typedef int intx16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 #ifndef EFQAT_GEMM_AUX
@@ -22,9 +26,11 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 #endif
 constexpr int KALIGN = 64;  // split-K slices start on multiples of this many K elements
 
+enum { EPI_RAW = 0, EPI_DX = 1, EPI_FWD = 2 };
+
 struct GemmArgs {
-  const bf16_t* A; int64_t lda; const int32_t* a_rows;
-  const bf16_t* B; int64_t ldb;
+  const void* A; int64_t lda; const int32_t* a_rows;   // lda / ldb / K in elements (bf16 or int8)
+  const void* B; int64_t ldb;
   int M, N, K;
   int k_per_split;        // multiple of KALIGN
   int tiles_m, tiles_n;
@@ -33,11 +39,15 @@ struct GemmArgs {
   const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype;
   const float* s_x; const float* z_x; void* dx; int dx_dtype; float* partial;
   int epi_vec;            // 8-wide vector accesses allowed in the fused epilogue
+  // forward epilogue (int8 product): y = s_x * s_w[n] * (acc + (128 - round(z_x)) * wsum[n])
+  const float* s_w; const int32_t* wsum; void* y; int y_dtype;
 };
 
-// BM x BN output tile per 256-thread block, BKT K-elements per LDS stage, S stages in the LDS ring.
-template <int BM, int BN, int BKT, int S>
+// BM x BN output tile per 256-thread block; one LDS stage holds 128 bytes of K per tile row (64 bf16 or 128 int8),
+// S stages.
+template <int BM, int BN, int S>
 struct TileCfg {
+  static constexpr int BKT = 64;                        // K in units of 2 bytes
   static constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 wavefronts)
   static constexpr int TM = WM / 32, TN = WN / 32;      // MFMA tiles per wave
   static constexpr int PITCH_B = BKT * 2;               // bytes per tile row in LDS
@@ -80,10 +90,16 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int BKT, int S, bool DX_EPI>
+// EPI: EPI_RAW fp32 partial tiles (split-K), EPI_DX fused dX epilogue, EPI_FWD forward epilogue.
+// I8: operands are int8 codes (A unsigned, re-biased by 128 in registers) on v_mfma_i32_32x32x32_i8; else bf16.
+template <int BM, int BN, int EPI, bool I8>
 __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins; the host pass needs only the launch stub
-  using C = TileCfg<BM, BN, BKT, S>;
+  constexpr int S = 2;
+  constexpr int ESZ = I8 ? 1 : 2;                       // bytes per K element
+  constexpr int BKT = 128 / ESZ;                        // K elements per LDS stage
+  static_assert(I8 == (EPI == EPI_FWD), "the int8 product is the forward pass");
+  using C = TileCfg<BM, BN, S>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases stay scalar
@@ -116,20 +132,20 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   // it must fetch the logical chunk slot ^ f(row) of that row (f is the same for every group of a wave).
   const int lrow = lane / C::CPRW, slot = lane % C::CPRW;
   const int lch = slot ^ (((wave * C::RPI + lrow) / C::R256) & (C::CPRW - 1));
-  const bf16_t* a_ptr[C::A_G];
-  const bf16_t* b_ptr[C::B_G];
+  const char* a_ptr[C::A_G];
+  const char* b_ptr[C::B_G];
 #pragma unroll
   for (int j = 0; j < C::A_G; ++j) {
     int gm = lm0 + (wave + 4 * j) * C::RPI + lrow;
     gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
     const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
-    a_ptr[j] = g.A + src * g.lda + lch * 8 + k_begin;
+    a_ptr[j] = (const char*)g.A + (src * g.lda + k_begin) * ESZ + lch * 16;
   }
 #pragma unroll
   for (int j = 0; j < C::B_G; ++j) {
     int gn = ln0 + (wave + 4 * j) * C::RPI + lrow;
     gn = gn < g.N ? gn : g.N - 1;
-    b_ptr[j] = g.B + (int64_t)gn * g.ldb + lch * 8 + k_begin;
+    b_ptr[j] = (const char*)g.B + ((int64_t)gn * g.ldb + k_begin) * ESZ + lch * 16;
   }
   const int span = k_end - k_begin;
   const int nfull = span > 0 ? span / BKT : 0;         // stages that need no predicate
@@ -139,7 +155,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   auto issue_direct = [&](int kt, int buf) {           // a full, unpredicated stage
     char* sa = smem + buf * C::LDS_STAGE;
     char* sb = sa + C::LDS_A;
-    const int koff = kt * BKT;
+    const int koff = kt * 128;                          // bytes
 #pragma unroll
     for (int j = 0; j < C::A_G; ++j)
       __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, EFQAT_GEMM_AUX);
@@ -155,8 +171,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     } else {
       char* sa = smem + buf * C::LDS_STAGE;
       char* sb = sa + C::LDS_A;
-      const int koff = kt * BKT;
-      const bool ok = (koff + lch * 8) < span;
+      const int koff = kt * 128;                          // bytes
+      const bool ok = (koff + lch * 16) < span * ESZ;
 #pragma unroll
       for (int j = 0; j < C::A_G; ++j) {
         const uint4 v = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
@@ -170,33 +186,45 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     }
   };
 
-  floatx16_t acc[C::TM][C::TN];
+  typename std::conditional<I8, intx16_t, floatx16_t>::type acc[C::TM][C::TN];
 #pragma unroll
   for (int i = 0; i < C::TM; ++i)
 #pragma unroll
     for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
   const int fr = lane & 31, fh = lane >> 5;
   const int a_row0 = wm * C::WM + fr, b_row0 = wn * C::WN + fr;
-  bf16x8_t af[2][C::TM], bfr[2][C::TN];
+  intx4_t af[2][C::TM], bfr[2][C::TN];                  // 16-byte fragments: 8 bf16 or 16 int8 along K
   auto load_frags = [&](int buf, int s, int rb) {
     const char* sa = smem + buf * C::LDS_STAGE;
     const char* sb = sa + C::LDS_A;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
-      af[rb][i] = *reinterpret_cast<const bf16x8_t*>(sa + C::swz(a_row0 + i * 32, 2 * s + fh));
+      af[rb][i] = *reinterpret_cast<const intx4_t*>(sa + C::swz(a_row0 + i * 32, 2 * s + fh));
 #pragma unroll
     for (int j = 0; j < C::TN; ++j)
-      bfr[rb][j] = *reinterpret_cast<const bf16x8_t*>(sb + C::swz(b_row0 + j * 32, 2 * s + fh));
+      bfr[rb][j] = *reinterpret_cast<const intx4_t*>(sb + C::swz(b_row0 + j * 32, 2 * s + fh));
   };
   auto mfma_all = [&](int rb) {
+    if constexpr (I8) {
+      // activation codes are unsigned: x - 128 fits int8 (flip the top bit of every byte); the epilogue adds
+      // 128 * sum_k w back
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i) af[rb][i] ^= (int)0x80808080;
+    }
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[rb][i], bfr[rb][j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < C::TN; ++j) {
+        if constexpr (I8)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[rb][i], bfr[rb][j], acc[i][j], 0, 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[rb][i]),
+                                                              __builtin_bit_cast(bf16x8_t, bfr[rb][j]), acc[i][j],
+                                                              0, 0, 0);
+      }
   };
 
   // ---- main loop, two LDS stages.  Stage kt computes from buffer kt & 1 in NS = 4 sub-steps of K = 16:
@@ -214,7 +242,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   auto issue_range = [&](int kt, int buf, int t0, int t1) {
     char* sa = smem + buf * C::LDS_STAGE;
     char* sb = sa + C::LDS_A;
-    const int koff = kt * BKT;
+    const int koff = kt * 128;                          // bytes
 #pragma unroll
     for (int t = t0; t < t1; ++t) {
       if (t < C::A_G)
@@ -292,7 +320,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 
   // ---- epilogue.  MFMA 32x32 accumulator layout: lane holds column (lane & 31) and rows
   // 8*(r/4) + 4*(lane >> 5) + (r % 4), r = 0..15.
-  if (!DX_EPI) {
+  if constexpr (EPI == EPI_RAW) {
     float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
@@ -305,7 +333,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
           if (row < g.M && col < g.N) out[(int64_t)row * g.N + col] = acc[i][j][r];
         }
       }
-  } else {
+  } else if constexpr (EPI == EPI_DX) {
     // dX = dX_q where the activation was not clipped (straight-through), 0 elsewhere; block partial sums
     // of dS_x = sum dX_q * (in range ? (code - Z) - x/S : code - Z) and dZ_x = sum dX_q * (in range ? 0 : -S).
     // The accumulators go through LDS (32 rows of the wave's tile at a time) so that every lane then owns
@@ -452,6 +480,69 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       g.partial[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
       g.partial[2 * blockIdx.x + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
     }
+  } else {
+    // Forward epilogue: the int32 sums are over (code - 128) * w, so
+    //   y[m][n] = S_x * S_w[n] * (acc + (128 - round(Z_x)) * sum_k w[n][k]).
+    // Accumulators go through LDS so that a lane owns 8 consecutive columns of a row (16/32-byte stores).
+    constexpr int PITCH = C::WN + 8;
+    constexpr int CPR = C::WN / 8;
+    constexpr int RPP = 64 / CPR;
+    constexpr int NPASS = (32 + RPP - 1) / RPP;
+    int* stage = reinterpret_cast<int*>(smem) + wave * 32 * PITCH;
+    const float sx = g.s_x[0];
+    const long long zc = 128 - (long long)rintf(g.z_x[0]);
+    const int row_l0 = lane / CPR, ch = lane % CPR;
+    const int gcol = n0 + wn * C::WN + ch * 8;
+    const bool lane_on = row_l0 < RPP && gcol < g.N;
+    float scl[8];
+    long long corr[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const bool ok = lane_on && gcol + t < g.N;
+      scl[t] = ok ? sx * g.s_w[gcol + t] : 0.0f;
+      corr[t] = ok ? zc * (long long)g.wsum[gcol + t] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      if (i > 0) __syncthreads();
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
+      __syncthreads();
+#pragma unroll
+      for (int p = 0; p < NPASS; ++p) {
+        const int row_l = p * RPP + row_l0;
+        const int grow = m0 + wm * C::WM + i * 32 + row_l;
+        if (lane_on && row_l < 32 && grow < g.M) {
+          const int4 a0 = *reinterpret_cast<const int4*>(stage + row_l * PITCH + ch * 8);
+          const int4 a1 = *reinterpret_cast<const int4*>(stage + row_l * PITCH + ch * 8 + 4);
+          const int a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+          float o[8];
+#pragma unroll
+          for (int t = 0; t < 8; ++t) o[t] = scl[t] * (float)((long long)a[t] + corr[t]);
+          const int64_t e = (int64_t)grow * g.N + gcol;
+          if (g.epi_vec && gcol + 8 <= g.N) {
+            if (g.y_dtype == EFQAT_F32) {
+              *reinterpret_cast<float4*>((float*)g.y + e) = make_float4(o[0], o[1], o[2], o[3]);
+              *reinterpret_cast<float4*>((float*)g.y + e + 4) = make_float4(o[4], o[5], o[6], o[7]);
+            } else {
+              *reinterpret_cast<uint4*>((bf16_t*)g.y + e) =
+                  make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                             pack_bf16x2(o[6], o[7]));
+            }
+          } else {
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+              if (gcol + t < g.N) {
+                if (g.y_dtype == EFQAT_F32) ((float*)g.y)[e + t] = o[t];
+                else ((bf16_t*)g.y)[e + t] = f32_to_bf16(o[t]);
+              }
+          }
+        }
+      }
+    }
   }
 #endif
 }
@@ -502,9 +593,9 @@ bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N) {
 // ---- optional event timing of the contraction kernels (benchmarks only; off by default)
 static const int kMaxProf = 4096;
 static bool g_prof_on = false;
-static hipEvent_t g_prof_ev[2][kMaxProf][2];
-static int g_prof_made[2] = {0, 0};
-static int g_prof_used[2] = {0, 0};
+static hipEvent_t g_prof_ev[3][kMaxProf][2];
+static int g_prof_made[3] = {0, 0, 0};
+static int g_prof_used[3] = {0, 0, 0};
 
 static bool prof_begin(int which, hipStream_t st, int* slot) {
   if (!g_prof_on || g_prof_used[which] >= kMaxProf) return false;
@@ -522,21 +613,22 @@ static void prof_end(int which, hipStream_t st, int slot) {
   if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
 }
 
-template <int BM, int BN, int BKT, int S, bool DX>
+template <int BM, int BN, int EPI, bool I8>
 static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
-  using C = TileCfg<BM, BN, BKT, S>;
+  using C = TileCfg<BM, BN, 2>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, BKT, S, DX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, EPI, I8>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             C::LDS_BYTES) != hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
   }
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
   int slot = 0;
-  const bool timed = prof_begin(DX ? 0 : 1, st, &slot);
-  hipLaunchKernelGGL((k_gemm_nt<BM, BN, BKT, S, DX>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) prof_end(DX ? 0 : 1, st, slot);
+  constexpr int kProf = EPI == EPI_DX ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
+  const bool timed = prof_begin(kProf, st, &slot);
+  hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8>), grid, dim3(256), C::LDS_BYTES, st, a);
+  if (timed) prof_end(kProf, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -562,13 +654,37 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
   a.tiles_n = plan.tiles_n;
   switch (plan.tile) {
     case 256:
-      return epi ? launch_cfg<256, 256, 64, 2, true>(a, 1, stream) : launch_cfg<256, 256, 64, 2, false>(a, split_k, stream);
+      return epi ? launch_cfg<256, 256, EPI_DX, false>(a, 1, stream)
+                 : launch_cfg<256, 256, EPI_RAW, false>(a, split_k, stream);
     case 192:
-      return epi ? launch_cfg<192, 192, 64, 2, true>(a, 1, stream) : launch_cfg<192, 192, 64, 2, false>(a, split_k, stream);
+      return epi ? launch_cfg<192, 192, EPI_DX, false>(a, 1, stream)
+                 : launch_cfg<192, 192, EPI_RAW, false>(a, split_k, stream);
     case 128:
-      return epi ? launch_cfg<128, 128, 64, 2, true>(a, 1, stream) : launch_cfg<128, 128, 64, 2, false>(a, split_k, stream);
+      return epi ? launch_cfg<128, 128, EPI_DX, false>(a, 1, stream)
+                 : launch_cfg<128, 128, EPI_RAW, false>(a, split_k, stream);
     default:
       return EFQAT_ERR_BAD_SHAPE;
+  }
+}
+
+int launch_gemm_fwd_i8(const uint8_t* x_codes, int64_t lda, const int8_t* w_codes, int64_t ldb, int64_t M, int64_t N,
+                       int64_t K, const GemmPlan& plan, const float* s_x, const float* z_x, const float* s_w,
+                       const int32_t* wsum, void* y, int y_dtype, hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 16) || (lda % 16) || (ldb % 16)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || plan.split_k != 1) return EFQAT_ERR_BAD_SHAPE;
+  GemmArgs a{};
+  a.A = x_codes; a.lda = lda; a.a_rows = nullptr; a.B = w_codes; a.ldb = ldb;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)(ceil_div(K, 2 * KALIGN) * 2 * KALIGN);
+  a.s_x = s_x; a.z_x = z_x; a.s_w = s_w; a.wsum = wsum; a.y = y; a.y_dtype = y_dtype;
+  a.epi_vec = ((N % 8) == 0 && ((uintptr_t)y % 16) == 0) ? 1 : 0;
+  a.tiles_m = plan.tiles_m;
+  a.tiles_n = plan.tiles_n;
+  switch (plan.tile) {
+    case 256: return launch_cfg<256, 256, EPI_FWD, true>(a, 1, stream);
+    case 192: return launch_cfg<192, 192, EPI_FWD, true>(a, 1, stream);
+    case 128: return launch_cfg<128, 128, EPI_FWD, true>(a, 1, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
   }
 }
 
@@ -576,12 +692,12 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
 
 extern "C" int efqat_profile_enable(int on) {
   efqat::g_prof_on = on != 0;
-  efqat::g_prof_used[0] = efqat::g_prof_used[1] = 0;
+  efqat::g_prof_used[0] = efqat::g_prof_used[1] = efqat::g_prof_used[2] = 0;
   return EFQAT_OK;
 }
 
 extern "C" int efqat_profile_read(int which, double* total_ms, int64_t* launches) {
-  if (which < 0 || which > 1) return EFQAT_ERR_BAD_LAYOUT;
+  if (which < 0 || which > 2) return EFQAT_ERR_BAD_LAYOUT;
   if (!total_ms || !launches) return EFQAT_ERR_NULL_PTR;
   double sum = 0.0;
   const int n = efqat::g_prof_used[which];

@@ -292,3 +292,40 @@ def test_conv_bwd_matches_oracle(case):
     assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"].reshape(-1, c_in)))
     assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"].reshape(c_out, -1)))
     _check_bwd(out, ref, idx, idx_ref, X, W, (sx, zx, sw), kind, scatter, kind == "bf16", W.shape)
+
+
+# ---------------------------------------------------------------- low-precision forward (int8 matrix cores)
+FWD_CASES = [
+    (256, 256, 256, 8, 1.0, torch.float32),
+    (300, 208, 136, 4, 0.7, torch.float32),
+    (300, 200, 136, 4, 0.7, torch.bfloat16),        # c_in not a multiple of 16: padded operand copies
+    (517, 392, 264, 8, 0.8, torch.bfloat16),
+    (1, 16, 8, 8, 1.0, torch.float32),
+    (1024, 768, 3072, 8, 1.0, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "T%d_%dx%d_w%d_s%s_%s" % (
+    c[0], c[1], c[2], c[3], c[4], "f32" if c[5] == torch.float32 else "bf16"))
+def test_linear_fwd_int8_matches_oracle(case):
+    T, c_in, c_out, w_bits, shrink, ydt = case
+    X, W, _ = synth.linear_layer(900 + T + c_in, T, c_in, c_out, act_dtype="bf16")
+    sx, zx = orc.act_qparams_minmax(X, 8)
+    sw = orc.weight_scale_minmax(W, w_bits)
+    sx = np.float32(sx * np.float32(shrink)); sw = (sw * np.float32(shrink)).astype(np.float32)
+    zx = np.float32(zx + 0.3)                                     # forward uses round(Z_x)
+    xd, wd = act_tensor(X, "bf16"), dev(W)
+    fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=False, scale=dev(np.array([sx])),
+                          zero_point=dev(np.array([zx])))
+    fw = ef.fakequant_fwd(wd, ef.W_PER_ROW_SYM, w_bits, init_minmax=False, scale=dev(sw))
+    y = ef.linear_fwd(fx["codes"], fx["scale"], fx["zero_point"], fw["codes"], fw["scale"], y_dtype=ydt)
+    torch.cuda.synchronize()
+    ref = orc.linear_fwd(X, sx, zx, 8, W, sw, w_bits)
+    # exact integer accumulation; only the two fp32 scale multiplications (and the bf16 store) round
+    assert_max_err(host(y), ref, 2e-6 if ydt == torch.float32 else 2.0 ** -8, "Y")
+    if ydt == torch.float32:
+        xc, _, _ = orc.fakequant_act(X, sx, zx, 8)
+        wc, _, _ = orc.fakequant_weight(W, sw, w_bits)
+        acc = (xc - int(np.rint(float(zx)))) @ wc.T                 # int64, exact
+        got = y.cpu().numpy().astype(np.float64) / (float(sx) * sw.astype(np.float64)[None, :])
+        assert np.abs(got - acc).max() <= 2e-6 * max(1.0, np.abs(acc).max())

@@ -434,3 +434,22 @@ def test_non_integer_zero_point_reading():
     gX, gW, gS, gZ, gSw = _torch_ste_linear(X, W, dY, sx, zf, sw, 8, 8)
     np.testing.assert_allclose(out["dX"], gX, rtol=1e-10, atol=1e-12)
     assert abs(out["dZ_x"] - gZ) <= 1e-9 * max(1.0, abs(gZ))
+
+
+# ------------------------------------------------------------------ forward product (Sec. 3.1)
+def test_forward_is_exact_integer_product_times_scales():
+    X, W, dY, sx, zx, sw = _tiny_layer(seed=41, T=7, c_in=9, c_out=5, shrink=0.7, w_bits=4)
+    Y = orc.linear_fwd(X, sx, zx, 8, W, sw, 4)
+    xc, _, _ = orc.fakequant_act(X, sx, zx, 8)
+    wc, _, _ = orc.fakequant_weight(W, sw, 4)
+    z = int(np.rint(float(zx)))
+    for t in range(7):
+        for c in range(5):
+            acc = 0
+            for i in range(9):
+                acc += (int(xc[t, i]) - z) * int(wc[c, i])          # exact integer sum
+            assert abs(Y[t, c] - float(sx) * float(sw[c]) * acc) <= 1e-12 * max(1.0, abs(Y[t, c]))
+    # Eq. 5 is the gradient of <dY, Y>: the backward pins above use the same forward
+    out = orc.linear_bwd(dY, X, sx, zx, 8, W, sw, 4, np.arange(5))
+    _, _, Wq = orc.fakequant_weight(W, sw, 4)
+    np.testing.assert_allclose(out["dXq"], dY.astype(np.float64) @ Wq, rtol=1e-13)
