@@ -49,7 +49,7 @@ def parse_args():
 class Layer:
     """Device buffers of one layer, all allocated up front (nothing is allocated in a timed region)."""
 
-    def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth):
+    def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth, fracs):
         self.name, self.T, self.c_in, self.c_out = name, T, c_in, c_out
         self.a_bits, self.w_bits, self.layout = a_bits, w_bits, layout
         X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype)
@@ -73,9 +73,11 @@ class Layer:
         self.ds_x, self.dz_x = e(1, torch.float32), e(1, torch.float32)
         L = ef.lib()
         dyd = 1 if act_dtype == "bf16" else 0
-        need = max(L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, c_out, dyd, layout),
-                   L.efqat_fakequant_fwd_workspace_bytes(T, c_in, 0),
-                   L.efqat_channel_select_workspace_bytes(c_out))
+        # the backward workspace is not monotone in k: size it for every update fraction that will be run
+        ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
+        need = max([L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k_, dyd, layout) for k_ in ks] +
+                   [L.efqat_fakequant_fwd_workspace_bytes(T, c_in, 0),
+                    L.efqat_channel_select_workspace_bytes(c_out)])
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
 
     def forward_quant(self, ef):
@@ -148,12 +150,13 @@ def main():
     torch.cuda.set_device(0)
     cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg5": synth.CFG5}[args.workload]
     w_bits = cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0]
-    layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
-                    args.dy_layout, synth) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
     if args.fraction:
         num, den = (int(t) for t in args.fraction.split("/"))
     else:
         num, den = 1, 4
+    fracs = list(cfg["fractions"]) + [(num, den), (1, 1)]
+    layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
+                    args.dy_layout, synth, fracs) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
     def step():

@@ -108,6 +108,31 @@ __global__ __launch_bounds__(256) void k_rows_bf16(const T* __restrict__ in, int
   }
 }
 
+// 256 zero bytes that tile loads read in place of rows / columns outside an operand
+__global__ void k_zero_page(uint32_t* __restrict__ p) { p[threadIdx.x] = 0u; }
+
+// Compaction of the selected output channels of a token-major dY ("extract the rows of the output-gradient
+// matrix", done once per call):  out[t][m] = bf16(dY[t][idx[m]]), m < k;  0 for k <= m < kp.
+// One lane gathers 8 channels of one token and writes them with one 16-byte store.
+template <typename T>
+__global__ __launch_bounds__(256) void k_gather_cols(const T* __restrict__ dy, int64_t ld, int64_t rows,
+                                                     const int32_t* __restrict__ idx, int64_t k,
+                                                     bf16_t* __restrict__ out, int64_t kp) {
+  const int64_t cpr = kp >> 3;
+  const int64_t total = rows * cpr;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t t = e / cpr, c8 = e - t * cpr;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int64_t m = c8 * 8 + j;
+      v[j] = m < k ? rd<T>(dy, t * ld + idx[m]) : 0.0f;
+    }
+    *reinterpret_cast<uint4*>(out + t * kp + c8 * 8) =
+        make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // conv helpers (explicit im2col into workspace; the contractions then run on the same GEMM core)
 struct ConvGeom {
@@ -285,8 +310,11 @@ struct BwdPlan {
   int64_t ldt;     // Tw rounded up to 8
   bool need_dyn;   // token-major bf16 copy of dY needed
   bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
+  bool tn;         // dW product straight from token-major dY columns and the uint8 codes (no transposed copies)
+  bool tn_direct;  // ... with dY itself as the A operand (all channels selected)
+  int64_t kp;      // k rounded up to 8 (pitch of the compacted dY columns)
   GemmPlan plan_dx, plan_dw;
-  size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, total;
+  size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, b_zero, total;
 };
 
 static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, int taps, int64_t k,
@@ -298,16 +326,20 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   const bool direct_tok = dy_layout == EFQAT_DY_TOKEN_MAJOR && dy_dtype == EFQAT_BF16 && (c_out % 8) == 0;
   p.need_dyn = !direct_tok;
   const bool direct_rows = dy_layout == EFQAT_DY_CHANNEL_MAJOR && dy_dtype == EFQAT_BF16 && (T_out % 8) == 0;
-  p.need_sel = k > 0 && !direct_rows;
+  p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && !im2col && (c_in % 16) == 0;
+  p.tn_direct = p.tn && direct_tok && k == c_out;
+  p.kp = round_up(k, 8);
+  p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
   p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false);
-  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true) : GemmPlan{128, 1, 0, 0};
+  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !p.tn) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
   p.b_colA = im2col ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
   p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
-  p.b_xcT = k > 0 ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
-  p.b_sel = p.need_sel ? (size_t)k * p.ldt * 2 : 0; cv.take(p.b_sel);
+  p.b_xcT = (k > 0 && !p.tn) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
+  p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
+  p.b_zero = p.tn ? 256 : 0; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -334,6 +366,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   float* part_dx = (float*)cv.take(p.b_part_dx);
   bf16_t* xcT = (bf16_t*)cv.take(p.b_xcT);
   bf16_t* sel = (bf16_t*)cv.take(p.b_sel);
+  void* zero_page = cv.take(p.b_zero);
   float* part_dw = (float*)cv.take(p.b_part_dw);
   int rc;
 
@@ -386,6 +419,29 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
 
   if (io.k == 0) return EFQAT_OK;
 
+  if (p.tn) {
+    // ---- dW product straight from token-major operands: A = the selected columns of dY (compacted once, or dY
+    // itself when every channel is selected), B = the uint8 codes; transposition happens in the LDS reads
+    if (((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(64), 0, st, (uint32_t*)zero_page);
+    EFQAT_LAUNCH_CHECK();
+    const bf16_t* At = (const bf16_t*)io.dy;
+    int64_t ldat = c_out, acols = c_out;
+    if (!p.tn_direct) {
+      const int64_t chunks = T_out * (p.kp / 8);
+      if (io.dy_dtype == EFQAT_F32)
+        hipLaunchKernelGGL((k_gather_cols<float>), dim3(grid1d(chunks)), dim3(256), 0, st, (const float*)io.dy, c_out,
+                           T_out, io.idx, io.k, sel, p.kp);
+      else
+        hipLaunchKernelGGL((k_gather_cols<bf16_t>), dim3(grid1d(chunks)), dim3(256), 0, st, (const bf16_t*)io.dy,
+                           c_out, T_out, io.idx, io.k, sel, p.kp);
+      EFQAT_LAUNCH_CHECK();
+      At = sel; ldat = p.kp; acols = p.kp;
+    }
+    rc = launch_gemm_tn(At, ldat, acols, io.x_codes, c_in, c_in, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
+                        part_dw, st);
+    if (rc) return rc;
+  } else {
   // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16
   if (im2col) {
     dim3 grid((unsigned)ceil_div(p.ldt, 64), (unsigned)ceil_div(c_in, 64), (unsigned)taps);
@@ -423,6 +479,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   const int64_t Kw = p.need_sel ? p.ldt : T_out;
   rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.plan_dw, part_dw, nullptr, st);
   if (rc) return rc;
+  }
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0) ? 1 : 0;
   hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw, fvec,

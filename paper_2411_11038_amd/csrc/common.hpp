@@ -104,7 +104,7 @@ struct GemmPlan {
 };
 // Pure host function of the problem size (so the workspace query and the call agree).  allow_split = false
 // for the product with the fused dX epilogue.
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split);
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192 = true);
 
 // C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
 //   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.
@@ -114,6 +114,17 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split);
 int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb,
                    int64_t M, int64_t N, int64_t K, const GemmPlan& plan, float* out_partial,
                    const GemmEpilogueDx* epi, hipStream_t stream);
+
+// Weight-gradient product from token-major operands (no transposed copies):
+//   out[s][m][n] = sum over the K-slice s of A[t][m] * (B[t][n] - round(z_x)),  A bf16 [K][lda], B uint8 [K][ldb].
+// Columns >= a_cols / b_cols and rows >= K are taken as zero (read from zero_page: 256 zero bytes, 256-byte
+// aligned).  plan.tile must be 256 or 128.
+int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* B, int64_t ldb, int64_t b_cols,
+                   const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                   float* out_partial, hipStream_t stream);
+// event timing hooks shared by the product kernels (which: 0 dX, 1 dW, 2 forward)
+bool gemm_prof_begin(int which, hipStream_t st, int* slot);
+void gemm_prof_end(int which, hipStream_t st, int slot);
 
 // Forward product on int8 matrix cores: y[m][n] = S_x * S_w[n] * sum_k (x_codes[m][k] - round(Z_x)) * w_codes[n][k].
 // K, lda, ldb multiples of 16; wsum[n] = sum_k w_codes[n][k].

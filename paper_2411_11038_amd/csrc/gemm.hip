@@ -560,11 +560,12 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 struct TileModel { int t; int bpc; double rate; double epi_dx; };
 static const TileModel kTiles[3] = {{256, 1, 2500.0, 0.75}, {192, 1, 2100.0, 0.75}, {128, 2, 1000.0, 0.6}};
 
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split) {
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192) {
   GemmPlan best{};
   double best_t = 1e300;
   const int64_t ksteps = ceil_div(K, KALIGN);
   for (const TileModel& tm : kTiles) {
+    if (tm.t == 192 && !allow_192) continue;
     const int64_t tiles = ceil_div(M, tm.t) * ceil_div(N, tm.t);
     int64_t max_s = allow_split ? ksteps / 8 : 1;
     if (max_s < 1) max_s = 1;
@@ -597,7 +598,7 @@ static hipEvent_t g_prof_ev[3][kMaxProf][2];
 static int g_prof_made[3] = {0, 0, 0};
 static int g_prof_used[3] = {0, 0, 0};
 
-static bool prof_begin(int which, hipStream_t st, int* slot) {
+bool gemm_prof_begin(int which, hipStream_t st, int* slot) {
   if (!g_prof_on || g_prof_used[which] >= kMaxProf) return false;
   const int i = g_prof_used[which];
   if (i >= g_prof_made[which]) {
@@ -609,7 +610,7 @@ static bool prof_begin(int which, hipStream_t st, int* slot) {
   *slot = i;
   return true;
 }
-static void prof_end(int which, hipStream_t st, int slot) {
+void gemm_prof_end(int which, hipStream_t st, int slot) {
   if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
 }
 
@@ -626,9 +627,9 @@ static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
   int slot = 0;
   constexpr int kProf = EPI == EPI_DX ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
-  const bool timed = prof_begin(kProf, st, &slot);
+  const bool timed = gemm_prof_begin(kProf, st, &slot);
   hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) prof_end(kProf, st, slot);
+  if (timed) gemm_prof_end(kProf, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }

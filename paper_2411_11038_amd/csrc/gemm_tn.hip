@@ -1,0 +1,394 @@
+// Weight-gradient product straight from token-major operands (Eq. 5 right, restricted as in Alg. 1):
+//
+//   C[m][n] = sum_t A[t][m] * (B[t][n] - z),   A = selected columns of dY, bf16 [T][lda];  B = activation codes, u8 [T][ldb]
+//
+// Both operands have the contraction index t as their row index, i.e. they are "transposed" for the matrix
+// cores, which want K contiguous per lane.  Instead of transposing them through HBM, tiles are copied as they
+// are (global -> LDS, global_load_lds_dwordx4) and the MFMA fragments are read with the gfx950 LDS transpose
+// loads: ds_read_b64_tr_b16 for A (4 consecutive t of one m per lane), ds_read_b64_tr_b8 for B (8 consecutive
+// t of one n), whose bytes are turned into bf16 (code - z, exact) in registers.  The activation operand thus
+// costs one byte per element in HBM, L2 and LDS.
+//
+// 256 threads = 1 x 4 wavefronts, v_mfma_f32_32x32x16_bf16, K-stage of 64 tokens, two LDS stages, the same
+// software pipeline as the K-contiguous kernel.  Rows beyond K / columns beyond the operand widths are read
+// from a zero page, so no load needs a predicate.  Output: raw fp32 partial tiles (split-K).
+#include "common.hpp"
+
+#include <type_traits>
+
+namespace efqat {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+typedef short shortx4_t __attribute__((ext_vector_type(4)));
+typedef int intx2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+struct GemmTnArgs {
+  const bf16_t* A; int64_t lda;       // [K][lda], lda multiple of 8; columns >= a_cols are not read
+  const uint8_t* B; int64_t ldb;      // [K][ldb], ldb multiple of 16
+  int a_cols, b_cols;                 // readable widths (multiples of 8 / 16): beyond them the zero page is read
+  const void* zero_page;              // >= 256 bytes of zeros, 256-byte aligned
+  const float* z_x;
+  int M, N, K;
+  int k_per_split;                    // multiple of 64
+  int tiles_m, tiles_n;
+  float* out;                         // raw fp32 [split][M][N]
+};
+
+template <int T>
+struct TnCfg {
+  static constexpr int BM = T, BN = T;
+  // wavefront grid 1 x 4: every wavefront spans all rows of the tile, so each uint8 fragment of B is converted to
+  // bf16 by exactly one wavefront
+  static constexpr int WGM = 1, WGN = 4;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int RA = 2 * BM, RB = BN;                 // bytes per LDS row (one token)
+  static constexpr int CA = RA / 16, CB = RB / 16;           // 16-byte chunks per row
+  static constexpr int A_G = 64 * RA / 1024 / 4, B_G = 64 * RB / 1024 / 4;   // 1-KiB loads per wave and stage
+  static constexpr int LDS_A = 64 * RA, LDS_B = 64 * RB;
+  static constexpr int LDS_STAGE = LDS_A + LDS_B;
+  static constexpr int LDS_BYTES = 2 * LDS_STAGE;
+  static constexpr int KSH = RB == 256 ? 0 : 1;              // B swizzle: rows per 256 bytes = 1 << KSH
+  // physical 16-byte chunk of logical chunk c in token row k.  A: a 16-lane transpose read touches 4 rows x 32
+  // bytes, B: 8 rows x 16 bytes; these XORs spread each half-wave's 256 bytes over all 64 banks.
+  __device__ static __forceinline__ int swz_a(int c, int k) { return c ^ (4 * (k & 3)); }
+  __device__ static __forceinline__ int swz_b(int c, int k) { return c ^ (2 * ((k >> KSH) & (CB / 2 - 1))); }
+};
+
+// One wave-wide global -> LDS copy: lane l moves 16 bytes from its own src to lds_dst + 16 l.  Written as inline
+// assembly on purpose: the compiler models the LDS transpose-read builtins as possible LDS writes and would make
+// every one of them wait for all copies in flight (s_waitcnt vmcnt(0)), which serialises the pipeline.  The
+// kernel orders copies against reads itself (s_waitcnt vmcnt(0) + barrier once per stage).  M0 holds the LDS
+// destination; nothing else in this kernel uses M0, and volatile statements keep their order, so the copy always
+// sees the M0 value written just before it (s_nop: one wait state between an M0 write and its use).
+__device__ __forceinline__ void dma16(const char* src, char* lds_dst) {
+  const uint32_t m = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
+  asm volatile("s_mov_b32 m0, %0" ::"s"(m) : "m0");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src));
+}
+
+// Scheduling hint for one sub-step: one group per MFMA.  The LDS transpose reads of the next sub-step go with the
+// first half of the MFMAs, the byte -> bf16 conversions of what they return with the second half, and each of the
+// first NL groups carries one global->LDS load with its pointer increment.  Group sizes must be compile-time
+// constants, hence the recursion.
+template <int MF, int NRD, int NL, int NCV, int Q>
+struct TnSched {
+  static __device__ __forceinline__ void run() {
+    if constexpr (Q < MF) {
+      constexpr int H = MF / 2 > 0 ? MF / 2 : 1;
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if constexpr (Q < H) {
+        constexpr int nds = ((Q + 1) * NRD) / H - (Q * NRD) / H;
+        if constexpr (nds > 0) __builtin_amdgcn_sched_group_barrier(0x100, nds, 0);
+      }
+      if constexpr (Q < NL) {
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+      }
+      if constexpr (Q >= MF - H) {
+        constexpr int q2 = Q - (MF - H);
+        constexpr int ncv = ((q2 + 1) * NCV) / H - (q2 * NCV) / H;
+        if constexpr (ncv > 0) __builtin_amdgcn_sched_group_barrier(0x002, ncv, 0);
+      }
+      TnSched<MF, NRD, NL, NCV, Q + 1>::run();
+    }
+  }
+};
+
+template <int T>
+__global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  using C = TnCfg<T>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / C::WGN, wn = wave % C::WGN;
+
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int GM = 8;
+  const int per_group = GM * g.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GM;
+  const int gsize = (g.tiles_m - first_m) < GM ? (g.tiles_m - first_m) : GM;
+  const int tm = first_m + (pid % per_group) % gsize;
+  const int tn = (pid % per_group) / gsize;
+  const int m0 = tm * C::BM, n0 = tn * C::BN;
+
+  const int k_begin = blockIdx.y * g.k_per_split;
+  const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
+  const int span = k_end - k_begin;
+  const int nk = span > 0 ? (span + 63) / 64 : 0;
+
+  const int nfull = span > 0 ? span / 64 : 0;          // stages whose 64 token rows all exist
+
+  // ---- global -> LDS copies.  Load slot j of this wave covers the token rows (wave + 4 j) * RPI .. + RPI - 1 of
+  // a stage; lane l lands in row l / chunks-per-row, physical chunk l % chunks-per-row, and therefore fetches the
+  // logical chunk that the swizzle maps there.  Every slot keeps a running source pointer that moves on by one
+  // stage (64 token rows) after each use; slots whose columns lie outside the operand sit on the zero page with
+  // stride 0, so the steady-state loads need no predicate and no multiply.
+  constexpr int RPIA = 1024 / C::RA, RPIB = 1024 / C::RB;
+  const char* zero = (const char*)g.zero_page;
+  const int a_r0 = lane / C::CA, b_r0 = lane / C::CB;
+  const char* a_ptr[C::A_G];
+  const char* b_ptr[C::B_G];
+  uint32_t a_st[C::A_G], b_st[C::B_G];
+#pragma unroll
+  for (int j = 0; j < C::A_G; ++j) {
+    const int kr = (wave + 4 * j) * RPIA + a_r0;
+    const int col = m0 + C::swz_a(lane % C::CA, kr) * 8;
+    const bool on = col < g.a_cols;
+    a_ptr[j] = on ? (const char*)g.A + ((int64_t)(k_begin + kr) * g.lda + col) * 2 : zero;
+    a_st[j] = on ? (uint32_t)(g.lda * 128) : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < C::B_G; ++j) {
+    const int kr = (wave + 4 * j) * RPIB + b_r0;
+    const int col = n0 + C::swz_b(lane % C::CB, kr) * 16;
+    const bool on = col < g.b_cols;
+    b_ptr[j] = on ? (const char*)g.B + (int64_t)(k_begin + kr) * g.ldb + col : zero;
+    b_st[j] = on ? (uint32_t)(g.ldb * 64) : 0u;
+  }
+  constexpr int LPS = C::A_G + C::B_G;
+  using Checked = std::integral_constant<bool, true>;
+  using Unchecked = std::integral_constant<bool, false>;
+  // issues load slots t0 .. t1-1 of stage kt; every slot must be issued exactly once per stage, in stage order
+  auto issue_range = [&](auto checked, int kt, int buf, int t0, int t1) {
+    char* sa = smem + buf * C::LDS_STAGE;
+    char* sb = sa + C::LDS_A;
+    const int kb = kt * 64;
+#pragma unroll
+    for (int t = t0; t < t1; ++t) {
+      if (t < C::A_G) {
+        const char* src = a_ptr[t];
+        if constexpr (decltype(checked)::value) {
+          if (kb + (wave + 4 * t) * RPIA + a_r0 >= span) src = zero;
+        }
+        dma16(src, sa + (wave + 4 * t) * 1024);
+        a_ptr[t] += a_st[t];
+      } else {
+        const int u = t - C::A_G;
+        const char* src = b_ptr[u];
+        if constexpr (decltype(checked)::value) {
+          if (kb + (wave + 4 * u) * RPIB + b_r0 >= span) src = zero;
+        }
+        dma16(src, sb + (wave + 4 * u) * 1024);
+        b_ptr[u] += b_st[u];
+      }
+    }
+  };
+
+  floatx16_t acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // ---- fragment reads.  16-lane group q = lane / 16: m (n) half mb = 16 (q & 1), K half h = q >> 1; s = lane % 16.
+  //   A, transpose read r in {0,1}: lane addresses 8 bytes = 4 m at token 16*sub + 8h + 4r + s/4,
+  //      m = 32 i + mb + 4 (s % 4);  result: lane owns m = 32 i + mb + s, tokens 8h + 4r + 0..3.
+  //      Its 16-byte chunk is 4 i + c0 (c0 < 4), which the swizzle moves to 4 (i ^ (s/4)) + c0: four base
+  //      addresses per LDS buffer (one per i % 4) and compile-time offsets for i / 4, r and the sub-step.
+  //   B: lane addresses 8 bytes = 8 n at token 16*sub + 8h + s/2, n = wave_n + 32 j + mb + 8 (s % 2);
+  //      result: lane owns n = ... + mb + s, tokens 8h + 0..7.
+  static_assert(C::WGM == 1 || C::TM <= 4, "A fragment addressing");
+  const int s16 = lane & 15, q = lane >> 4;
+  const int mb = 16 * (q & 1), h = q >> 1;
+  int a_base[2][4], b_base[2][C::TN];           // LDS byte offsets of sub-step 0, per buffer
+  {
+    const int k = 8 * h + (s16 >> 2), kk = (s16 >> 2) & 3;
+    const int c0 = (mb >> 3) + ((s16 & 3) >> 1);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a_base[0][u] = k * C::RA + ((4 * ((u + wm * (C::WM / 32)) ^ kk) + c0) << 4) + 8 * (s16 & 1);
+      a_base[1][u] = a_base[0][u] + C::LDS_STAGE;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int k = 8 * h + (s16 >> 1);
+    const int nbyte = wn * C::WN + 32 * j + mb + 8 * (s16 & 1);
+    b_base[0][j] = C::LDS_A + k * C::RB + (C::swz_b(nbyte >> 4, k) << 4) + (nbyte & 15);
+    b_base[1][j] = b_base[0][j] + C::LDS_STAGE;
+  }
+  const float z = rintf(g.z_x[0]);
+  shortx4_t af[2][C::TM][2];
+  intx2_t braw[2][C::TN];
+  bf16x8_t bfr[2][C::TN];
+  auto load_frags = [&](auto bufc, int sub, int rb) {
+    constexpr int buf = decltype(bufc)::value;
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+      braw[rb][j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][j] + sub * 16 * C::RB));
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        af[rb][i][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4_t*)(
+            smem + a_base[buf][i & 3] + (i >> 2) * 256 + r * 4 * C::RA + sub * 16 * C::RA));
+  };
+  // 8 activation codes -> (code - z) as bf16: integers of magnitude <= 255 are exact
+  auto convert = [&](int rb) {
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+      const uint32_t w0 = (uint32_t)braw[rb][j][0], w1 = (uint32_t)braw[rb][j][1];
+      float f[8];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        f[t] = (float)((w0 >> (8 * t)) & 0xFFu) - z;
+        f[4 + t] = (float)((w1 >> (8 * t)) & 0xFFu) - z;
+      }
+      uint32_t p[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) p[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
+      const uint4 pk = make_uint4(p[0], p[1], p[2], p[3]);
+      bfr[rb][j] = __builtin_bit_cast(bf16x8_t, pk);
+    }
+  };
+  auto mfma_all = [&](int rb) {
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      struct { shortx4_t lo, hi; } a2 = {af[rb][i][0], af[rb][i][1]};
+      const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, a2);
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, bfr[rb][j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  constexpr int P0 = (LPS + 2) / 3, P1 = (LPS - P0 + 1) / 2, P2 = LPS - P0 - P1;
+  auto stage_sync = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // ---- main loop, two LDS stages of 64 tokens, four sub-steps of 16 tokens each.  During the MFMAs of sub-step s
+  // the fragments of sub-step s+1 are read and its activation bytes converted; sub-steps 0 and 1 also issue the
+  // 2nd and 3rd thirds of the loads of stage kt+1; after sub-step 2 everybody synchronises (stage kt+1 complete,
+  // buffer kt free); sub-step 3 reads the first fragments of stage kt+1 and issues the first third of stage kt+2.
+  // Invariant: when stage kt starts, the first third of stage kt+1 is in flight iff kt+1 < nfull.
+  constexpr int MF = C::TM * C::TN, NRD = 2 * C::TM + C::TN, NCV = 20 * C::TN;
+  auto stage = [&](auto bufc, auto steadyc, int kt) {
+    constexpr int cur = decltype(bufc)::value;
+    constexpr bool ST = decltype(steadyc)::value;
+    using Other = std::integral_constant<int, cur ^ 1>;
+    bool more1 = true;
+    if constexpr (!ST) {
+      more1 = kt + 1 < nk;
+      if (kt + 1 < nfull) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, LPS);
+      else if (more1) issue_range(Checked{}, kt + 1, cur ^ 1, 0, LPS);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 1, 1);
+    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, P0 + P1);
+    mfma_all(0);
+    convert(1);
+    if constexpr (ST) TnSched<MF, NRD, P1, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 2, 0);
+    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0 + P1, LPS);
+    mfma_all(1);
+    convert(0);
+    if constexpr (ST) TnSched<MF, NRD, P2, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 3, 1);
+    mfma_all(0);
+    convert(1);
+    if constexpr (ST) TnSched<MF, NRD, 0, NCV, 0>::run();
+    stage_sync();
+    if (ST || more1) load_frags(Other{}, 0, 0);
+    if (ST || kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
+    mfma_all(1);
+    if (ST || more1) convert(0);
+    if constexpr (ST) TnSched<MF, NRD, P0, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
+  using Steady = std::integral_constant<bool, true>;
+  using Drain = std::integral_constant<bool, false>;
+
+  if (nk > 0) issue_range(Checked{}, 0, 0, 0, LPS);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (1 < nfull) issue_range(Unchecked{}, 1, 1, 0, P0);
+  if (nk > 0) {
+    load_frags(B0{}, 0, 0);
+    convert(0);
+  }
+  int kt = 0;
+  for (; kt + 3 < nfull; kt += 2) {                    // stages kt+1 .. kt+3 are full: branch-free pair of stages
+    stage(B0{}, Steady{}, kt);
+    stage(B1{}, Steady{}, kt + 1);
+  }
+  for (; kt < nk; kt += 2) {                           // the last (up to four) stages, including a ragged one
+    stage(B0{}, Drain{}, kt);
+    if (kt + 1 < nk) stage(B1{}, Drain{}, kt + 1);
+  }
+
+  // ---- raw fp32 partial tile.  Accumulator layout of the 32x32 MFMA: column lane & 31, rows 8 (r/4) + 4 (lane/32) + r%4.
+  const int fr = lane & 31, fh = lane >> 5;
+  float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+      const int col = n0 + wn * C::WN + j * 32 + fr;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * C::WM + i * 32 + 8 * (r >> 2) + 4 * fh + (r & 3);
+        if (row < g.M && col < g.N) out[(int64_t)row * g.N + col] = acc[i][j][r];
+      }
+    }
+#endif
+}
+
+template <int T>
+static int launch_tn_cfg(const GemmTnArgs& a, int split_k, hipStream_t st) {
+  using C = TnCfg<T>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)k_gemm_tn<T>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
+        hipSuccess)
+      return EFQAT_ERR_HIP;
+    attr_done = true;
+  }
+  dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
+  int slot = 0;
+  const bool timed = gemm_prof_begin(1, st, &slot);
+  hipLaunchKernelGGL((k_gemm_tn<T>), grid, dim3(256), C::LDS_BYTES, st, a);
+  if (timed) gemm_prof_end(1, st, slot);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* B, int64_t ldb, int64_t b_cols,
+                   const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                   float* out_partial, hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (lda % 8) || (ldb % 16) || (a_cols % 8) || (b_cols % 16)) return EFQAT_ERR_BAD_SHAPE;
+  if (lda >= (1 << 24) || ldb >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;   // 32-bit per-stage pointer strides
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || a_cols > lda || b_cols > ldb) return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)A % 16) || ((uintptr_t)B % 16) || ((uintptr_t)zero_page % 256)) return EFQAT_ERR_ALIGNMENT;
+  GemmTnArgs a{};
+  a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.a_cols = (int)a_cols; a.b_cols = (int)b_cols;
+  a.zero_page = zero_page; a.z_x = z_x;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)(ceil_div(ceil_div(K, 64), plan.split_k) * 64);
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  a.out = out_partial;
+  switch (plan.tile) {
+    case 256: return launch_tn_cfg<256>(a, plan.split_k, stream);
+    case 128: return launch_tn_cfg<128>(a, plan.split_k, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
+  }
+}
+
+}  // namespace efqat

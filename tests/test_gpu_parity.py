@@ -215,6 +215,14 @@ LIN_CASES = [
     (1, 8, 8, "bf16", 8, 8, 1.0, (1, 1), 0, False),               # single token
     (1024, 768, 768, "bf16", 8, 8, 0.8, (1, 20), 0, False),       # BERT-width, split-K path
     (1024, 768, 768, "bf16", 8, 8, 0.8, (1, 20), 1, False),
+    # c_in a multiple of 16 and token-major dY: weight gradient straight from the uint8 codes (LDS transpose reads)
+    (300, 208, 136, "bf16", 8, 4, 0.7, (1, 4), 0, False),
+    (517, 400, 264, "bf16", 8, 8, 0.8, (1, 2), 0, True),
+    (300, 208, 136, "bf16", 8, 8, 0.7, (1, 1), 0, False),         # every channel: dY itself is the operand
+    (300, 208, 130, "bf16", 8, 8, 0.7, (1, 1), 0, False),         # ... C_out not a multiple of 8: compacted copy
+    (333, 272, 200, "f32", 8, 8, 0.7, (1, 1), 0, True),
+    (70, 16, 24, "bf16", 8, 8, 1.0, (1, 3), 0, False),
+    (2048, 512, 640, "bf16", 8, 8, 0.8, (1, 1), 0, False),        # several 256-wide tiles, split-K
 ]
 
 
