@@ -3,6 +3,8 @@
 // clip masks and reduce the quantizer-parameter gradients.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace efqat {
 
 // ------------------------------------------------------------------------------------------------
@@ -40,8 +42,11 @@ __global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in
                                                         int64_t Cn, const int32_t* __restrict__ colmap,
                                                         const float* __restrict__ rowscale,
                                                         const float* __restrict__ subz, bf16_t* __restrict__ out,
-                                                        int64_t ldo, int64_t out_off, int64_t i_pad, int vec) {
+                                                        int64_t ldo, int64_t out_off, int64_t i_pad, int vec,
+                                                        uint32_t* __restrict__ zero_page) {
   __shared__ bf16_t tile[64][66];                     // tile[i][j]
+  // optional by-product: 256 bytes of zeros for a later kernel of the same call (saves a launch)
+  if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64) zero_page[threadIdx.x] = 0u;
   const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
   const float sub = subz ? rintf(subz[0]) : 0.0f;
   if (vec && j0 + 64 <= Cn) {
@@ -108,28 +113,33 @@ __global__ __launch_bounds__(256) void k_rows_bf16(const T* __restrict__ in, int
   }
 }
 
-// 256 zero bytes that tile loads read in place of rows / columns outside an operand
-__global__ void k_zero_page(uint32_t* __restrict__ p) { p[threadIdx.x] = 0u; }
-
-// Compaction of the selected output channels of a token-major dY ("extract the rows of the output-gradient
-// matrix", done once per call):  out[t][m] = bf16(dY[t][idx[m]]), m < k;  0 for k <= m < kp.
-// One lane gathers 8 channels of one token and writes them with one 16-byte store.
+// Compaction of the selected output channels of a token-major dY (the channel extraction step of Alg. 1, done
+// once per call):  out[t][m] = bf16(dY[t][idx[m]]), m < k;  0 for k <= m < kp.
+// A lane owns two neighbouring compacted channels (their source columns stay in registers); a wavefront thus
+// reads 128 selected channels of one token - a span of a few cache lines, since idx ascends - and writes 256
+// contiguous bytes.  The four wavefronts of a block take every fourth token row of the block's row range.
+constexpr int kGatherRows = 32;                       // token rows per block
 template <typename T>
 __global__ __launch_bounds__(256) void k_gather_cols(const T* __restrict__ dy, int64_t ld, int64_t rows,
                                                      const int32_t* __restrict__ idx, int64_t k,
                                                      bf16_t* __restrict__ out, int64_t kp) {
-  const int64_t cpr = kp >> 3;
-  const int64_t total = rows * cpr;
-  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t t = e / cpr, c8 = e - t * cpr;
-    float v[8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t m0 = 2 * ((int64_t)blockIdx.x * 64 + lane);
+  if (m0 >= kp) return;
+  const int64_t c0 = m0 < k ? (int64_t)idx[m0] : -1, c1 = m0 + 1 < k ? (int64_t)idx[m0 + 1] : -1;
+  for (int64_t t0 = (int64_t)blockIdx.y * kGatherRows; t0 < rows; t0 += (int64_t)gridDim.y * kGatherRows) {
+    float a[kGatherRows / 4], b[kGatherRows / 4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int64_t m = c8 * 8 + j;
-      v[j] = m < k ? rd<T>(dy, t * ld + idx[m]) : 0.0f;
+    for (int r = 0; r < kGatherRows / 4; ++r) {
+      const int64_t t = t0 + wave + 4 * r;
+      a[r] = (c0 >= 0 && t < rows) ? rd<T>(dy, t * ld + c0) : 0.0f;
+      b[r] = (c1 >= 0 && t < rows) ? rd<T>(dy, t * ld + c1) : 0.0f;
     }
-    *reinterpret_cast<uint4*>(out + t * kp + c8 * 8) =
-        make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+#pragma unroll
+    for (int r = 0; r < kGatherRows / 4; ++r) {
+      const int64_t t = t0 + wave + 4 * r;
+      if (t < rows) *reinterpret_cast<uint32_t*>(out + t * kp + m0) = pack_bf16x2(a[r], b[r]);
+    }
   }
 }
 
@@ -288,14 +298,14 @@ static inline unsigned grid1d(int64_t total, int per_block = 256) {
 template <typename T>
 static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, const int32_t* colmap,
                              const float* rowscale, const float* subz, bf16_t* out, int64_t ldo, int64_t out_off,
-                             int64_t i_pad, hipStream_t st) {
+                             int64_t i_pad, hipStream_t st, uint32_t* zero_page = nullptr) {
   dim3 grid((unsigned)ceil_div(i_pad, 64), (unsigned)ceil_div(Cn, 64));
   if (grid.y > 65535) return EFQAT_ERR_BAD_SHAPE;
   // 16-byte stores need an 8-element aligned destination; 4-wide loads a dense, 4-element aligned source
   if ((ldo % 8) || (out_off % 8) || (i_pad % 8) || ((uintptr_t)out % 16)) return EFQAT_ERR_ALIGNMENT;
   const int vec = (!colmap && (ld_in % 4) == 0 && ((uintptr_t)in % (4 * sizeof(T))) == 0) ? 1 : 0;
   hipLaunchKernelGGL((k_transpose_bf16<T>), grid, dim3(256), 0, st, in, ld_in, R, Cn, colmap, rowscale, subz, out,
-                     ldo, out_off, i_pad, vec);
+                     ldo, out_off, i_pad, vec, zero_page);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -373,7 +383,8 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
   for (int tap = 0; tap < taps; ++tap) {
     rc = transpose_to_bf16<int8_t>(io.w_codes + (int64_t)tap * c_in, (int64_t)taps * c_in, c_out, c_in, nullptr,
-                                   io.s_w, nullptr, wqT, p.Kx, (int64_t)tap * p.ldc, p.ldc, st);
+                                   io.s_w, nullptr, wqT, p.Kx, (int64_t)tap * p.ldc, p.ldc, st,
+                                   (tap == 0 && p.tn) ? (uint32_t*)zero_page : nullptr);
     if (rc) return rc;
   }
 
@@ -423,18 +434,16 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     // ---- dW product straight from token-major operands: A = the selected columns of dY (compacted once, or dY
     // itself when every channel is selected), B = the uint8 codes; transposition happens in the LDS reads
     if (((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
-    hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(64), 0, st, (uint32_t*)zero_page);
-    EFQAT_LAUNCH_CHECK();
     const bf16_t* At = (const bf16_t*)io.dy;
     int64_t ldat = c_out, acols = c_out;
     if (!p.tn_direct) {
-      const int64_t chunks = T_out * (p.kp / 8);
+      const dim3 ggrid((unsigned)ceil_div(p.kp, 128), (unsigned)std::min<int64_t>(ceil_div(T_out, kGatherRows), 65535));
       if (io.dy_dtype == EFQAT_F32)
-        hipLaunchKernelGGL((k_gather_cols<float>), dim3(grid1d(chunks)), dim3(256), 0, st, (const float*)io.dy, c_out,
-                           T_out, io.idx, io.k, sel, p.kp);
+        hipLaunchKernelGGL((k_gather_cols<float>), ggrid, dim3(256), 0, st, (const float*)io.dy, c_out, T_out, io.idx,
+                           io.k, sel, p.kp);
       else
-        hipLaunchKernelGGL((k_gather_cols<bf16_t>), dim3(grid1d(chunks)), dim3(256), 0, st, (const bf16_t*)io.dy,
-                           c_out, T_out, io.idx, io.k, sel, p.kp);
+        hipLaunchKernelGGL((k_gather_cols<bf16_t>), ggrid, dim3(256), 0, st, (const bf16_t*)io.dy, c_out, T_out,
+                           io.idx, io.k, sel, p.kp);
       EFQAT_LAUNCH_CHECK();
       At = sel; ldat = p.kp; acols = p.kp;
     }

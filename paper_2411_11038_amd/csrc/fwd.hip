@@ -1,4 +1,4 @@
-// Low-precision forward product of a quantized linear layer (Sec. 3.1: Y = X_q W_q^T "in low precision"):
+// Low-precision forward product of a quantized linear layer (Sec. 3.1: Y = X_q W_q^T computed on integer codes):
 // the 8-bit codes go straight to the int8 matrix cores, the quantizer scales and the zero point are applied
 // once per output element in the epilogue.
 #include "common.hpp"
