@@ -134,6 +134,27 @@ def network_top_k(importances, k_total: int):
     return out
 
 
+def layer_top_k(weights, k_layers: int):
+    """EfQAT-LWPN (Table 2): the block is a whole layer, its importance the mean |w| over
+    all of the layer's weights (Eq. 6 with one block per layer); the k_layers most
+    important layers are unfrozen entirely, the others frozen entirely.  Returns the
+    ascending list of unfrozen layers and the per-layer channel count (C_out or 0).
+    Ties go to the earlier layer."""
+    imp = np.array([np.mean(np.abs(np.asarray(w, dtype=np.float64))) for w in weights])
+    sel = top_k_channels(imp, k_layers)
+    chosen = set(int(i) for i in sel)
+    k_per_layer = np.array([np.asarray(w).shape[0] if l in chosen else 0 for l, w in enumerate(weights)],
+                           dtype=np.int64)
+    return sel, k_per_layer, imp
+
+
+def bias_grad(dY):
+    """Gradient of a bias added per output channel, Y = X_q W_q^T + b: db[c] = sum_t dY[t, c].
+    Biases stay unfrozen whatever the update fraction (Sec. 3.4, Alg. 1 optimizer step)."""
+    d = np.asarray(dY, dtype=np.float64)
+    return d.reshape(-1, d.shape[-1]).sum(axis=0)
+
+
 # --------------------------------------------------------------------------
 # Quantizer-parameter gradients (derived; see module header)
 # --------------------------------------------------------------------------

@@ -149,6 +149,47 @@ def test_network_topk_balances_across_layers():
     assert [s.tolist() for s in sel] == [[0, 1, 2], [0, 1], [0, 1]]
 
 
+def test_layer_topk_lwpn():
+    # Table 2, LWPN: whole layers are the blocks.  Layers of different shapes; importances set by
+    # construction (constant |w| per layer), so the ranking is known without the oracle.
+    rng = np.random.default_rng(5)
+    mags = [0.3, 0.9, 0.1, 0.9, 0.5]
+    shapes = [(4, 6), (3, 5), (8, 2), (2, 9), (5, 5)]
+    ws = [m * rng.choice([-1.0, 1.0], size=sh) for m, sh in zip(mags, shapes)]
+    sel, kpl, imp = orc.layer_top_k(ws, 3)
+    np.testing.assert_allclose(imp, mags, rtol=1e-15)
+    assert list(sel) == [1, 3, 4]                       # 0.9, 0.9 (tie -> both), then 0.5
+    assert list(kpl) == [0, 3, 0, 2, 5]
+    sel, kpl, _ = orc.layer_top_k(ws, 1)
+    assert list(sel) == [1] and list(kpl) == [0, 3, 0, 0, 0]   # tie goes to the earlier layer
+    sel, kpl, _ = orc.layer_top_k(ws, 0)
+    assert len(sel) == 0 and not kpl.any()
+    sel, kpl, _ = orc.layer_top_k(ws, 5)
+    assert list(kpl) == [4, 3, 8, 2, 5]
+    # the layer importance is the mean over all weights = mean of the channel means (equal block sizes)
+    w = rng.normal(size=(7, 11))
+    _, _, imp = orc.layer_top_k([w], 1)
+    assert abs(imp[0] - orc.channel_importance(w).mean()) < 1e-15
+
+
+def test_bias_grad_is_gradient_of_bias():
+    # db is the derivative of sum(dY * (Y0 + b)) with respect to b: check by exact finite differences
+    # (the function is linear in b) and against torch autograd of a broadcast add.
+    rng = np.random.default_rng(6)
+    dY = rng.normal(size=(37, 5))
+    db = orc.bias_grad(dY)
+    for c in range(5):
+        e = np.zeros(5); e[c] = 1.0
+        np.testing.assert_allclose(np.sum(dY * (0.0 + e[None, :])), db[c], rtol=1e-13)
+    y0 = torch.zeros(37, 5, dtype=torch.float64)
+    b = torch.zeros(5, dtype=torch.float64, requires_grad=True)
+    (y0 + b).backward(torch.from_numpy(dY))
+    np.testing.assert_allclose(db, b.grad.numpy(), rtol=1e-13)
+    # conv-shaped dY [N, Ho, Wo, C]: sum over every axis but the channel
+    d4 = rng.normal(size=(2, 3, 4, 5))
+    np.testing.assert_allclose(orc.bias_grad(d4), d4.sum(axis=(0, 1, 2)), rtol=1e-13)
+
+
 def test_ops_model_golden():
     rows = _rows("ops_bound.txt")
     for r in rows:
