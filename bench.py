@@ -241,6 +241,23 @@ def main():
                    kernel_tops=ops / (kms / max(kn, 1) * len(layers) / 1e3) / 1e12 if kn else None,
                    peak_tops=5000.0, note="Y = X_q W_q^T from the 8-bit codes, v_mfma_i32_32x32x32_i8, all layers")
 
+    # bias gradient (always-updated parameters), HBM bound: one read of dY.  Not part of the step or of `value`.
+    bias = None
+    if not args.no_sweep:
+        dbs = [torch.empty(l.c_out, dtype=torch.float32, device="cuda") for l in layers]
+        bws = [torch.empty(max(ef.lib().efqat_bias_grad_workspace_bytes(l.T, l.c_out, args.dy_layout), 256),
+                           dtype=torch.uint8, device="cuda") for l in layers]
+
+        def bias_all():
+            for l, d_, w_ in zip(layers, dbs, bws):
+                ef.bias_grad(l.dy, dy_layout=args.dy_layout, ws=w_, out=d_)
+        for _ in range(3):
+            bias_all()
+        tb = time_region(torch, bias_all, max(3, args.steps // 2))
+        nbytes = sum(l.dy.numel() * l.dy.element_size() for l in layers)
+        bias = dict(ms=tb * 1e3, gbps=nbytes / tb / 1e9, peak_gbps=8000.0,
+                    note="db = column sums of dY, all layers, two launches per layer")
+
     out = dict(metric="QAT backward time + TFLOP/s per layer vs update fraction; speedup over full bwd",
                value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
@@ -249,7 +266,7 @@ def main():
                    args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
                    num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
                    k=ks, step="fakequant(X,W) + select + restricted backward, every layer"),
-               roofline=roofline, sweep=sweep, forward_int8=fwd,
+               roofline=roofline, sweep=sweep, forward_int8=fwd, bias_grad=bias,
                paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")

@@ -131,6 +131,34 @@ int efqat_network_select(const double* scores, const int64_t* layer_off, int64_t
                          int64_t total, int64_t k_total, int32_t* idx, int32_t* k_per_layer,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* EfQAT-LWPN (Table 2): the blocks are whole layers; the importance of a layer is the mean
+ * |w| over all of its weights (Eq. 6 with one block per layer), which equals the mean of its
+ * per-channel scores because every channel of a layer has the same number of weights.  The
+ * k_layers most important layers are unfrozen entirely (their channel count is reported),
+ * the others frozen entirely (count 0); ties go to the earlier layer.
+ *   scores       in   double[layer_off[n_layers]] per-channel scores, layer after layer (device)
+ *   layer_off    in   int64[n_layers+1] ascending prefix offsets (device)
+ *   k_layers     0..n_layers
+ *   layer_scores out, nullable  double[n_layers]
+ *   layer_idx    out  int32[k_layers] ascending (may be NULL when k_layers == 0)
+ *   k_per_layer  out  int32[n_layers]: C_out of the layer if it is unfrozen, else 0 */
+size_t efqat_layer_select_workspace_bytes(int64_t n_layers);
+int efqat_layer_select(const double* scores, const int64_t* layer_off, int64_t n_layers,
+                       int64_t k_layers, double* layer_scores, int32_t* layer_idx,
+                       int32_t* k_per_layer, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------ bias gradient
+ * db[c] = sum_t dY[t][c] for every output channel: biases (and normalisation parameters) are
+ * never frozen (Sec. 3.4; the optimizer step of Alg. 1 always updates them).  For a
+ * convolution pass T = N*Ho*Wo.
+ *   dy   in   [T][c_out] (token major) or [c_out][T] (channel major), fp32 or bf16
+ *   db   out  float[c_out], fully overwritten
+ * fp32 partial sums over chunks of tokens, summed in double precision in a fixed order
+ * (bit-reproducible). */
+size_t efqat_bias_grad_workspace_bytes(int64_t T, int64_t c_out, int dy_layout);
+int efqat_bias_grad(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_out,
+                    float* db, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ linear backward
  * Backward step of Alg. 1 for one layer Y = X_q W_q^T, X_q = S_x (x_codes - Z_x),
  * W_q[c][:] = S_w[c] w_codes[c][:]:

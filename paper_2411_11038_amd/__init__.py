@@ -6,7 +6,7 @@ include/efqat.h and returns the library's outputs.  There is no CPU fallback: wi
 built library (or without a GPU for the compute calls) these functions raise.
 """
 from .binding import (  # noqa: F401
-    EfqatError, lib, lib_path, k_from_ratio, fakequant_fwd, channel_select, network_select,
+    EfqatError, lib, lib_path, k_from_ratio, fakequant_fwd, channel_select, network_select, layer_select, bias_grad,
     linear_bwd, conv_bwd, linear_fwd, F32, BF16, ACT_PER_TENSOR_ASYM, W_PER_ROW_SYM, DY_TOKEN_MAJOR,
     DY_CHANNEL_MAJOR, EXPORTS, profile_enable, profile_read,
 )

@@ -16,6 +16,8 @@ EXPORTS = [
     "efqat_fakequant_fwd_workspace_bytes", "efqat_fakequant_fwd",
     "efqat_channel_select_workspace_bytes", "efqat_channel_select",
     "efqat_network_select_workspace_bytes", "efqat_network_select",
+    "efqat_layer_select_workspace_bytes", "efqat_layer_select",
+    "efqat_bias_grad_workspace_bytes", "efqat_bias_grad",
     "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
     "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd",
     "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
@@ -63,6 +65,14 @@ def lib():
     L.efqat_network_select_workspace_bytes.argtypes = [i64]
     L.efqat_network_select.restype = ci
     L.efqat_network_select.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.efqat_layer_select_workspace_bytes.restype = sz
+    L.efqat_layer_select_workspace_bytes.argtypes = [i64]
+    L.efqat_layer_select.restype = ci
+    L.efqat_layer_select.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
+    L.efqat_bias_grad_workspace_bytes.restype = sz
+    L.efqat_bias_grad_workspace_bytes.argtypes = [i64, i64, ci]
+    L.efqat_bias_grad.restype = ci
+    L.efqat_bias_grad.argtypes = [vp, ci, ci, i64, i64, vp, vp, sz, vp]
     L.efqat_linear_bwd_workspace_bytes.restype = sz
     L.efqat_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     L.efqat_linear_bwd.restype = ci
@@ -200,6 +210,38 @@ def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, 
                                 _p(idx) if k_total > 0 else None, _p(kpl), _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_network_select")
     return idx, kpl
+
+
+def layer_select(scores: torch.Tensor, layer_off: torch.Tensor, k_layers: int, ws=None):
+    """EfQAT-LWPN.  Returns (layer_idx int32[k_layers], k_per_layer int32[n_layers], layer_scores double[n_layers])."""
+    L = lib()
+    n_layers = layer_off.numel() - 1
+    lidx = torch.empty(max(k_layers, 0), dtype=torch.int32, device=scores.device)
+    kpl = torch.empty(n_layers, dtype=torch.int32, device=scores.device)
+    ls = torch.empty(n_layers, dtype=torch.float64, device=scores.device)
+    if ws is None:
+        ws = _ws(L.efqat_layer_select_workspace_bytes(n_layers), scores)
+    rc = L.efqat_layer_select(_p(scores), _p(layer_off), n_layers, k_layers, _p(ls),
+                              _p(lidx) if k_layers > 0 else None, _p(kpl), _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_layer_select")
+    return lidx, kpl, ls
+
+
+def bias_grad(dy: torch.Tensor, dy_layout=DY_TOKEN_MAJOR, ws=None, out=None):
+    """db[c] = sum over tokens of dY.  dy: [T, c_out] (token major; leading dims are flattened) or [c_out, T]."""
+    L = lib()
+    if dy_layout == DY_TOKEN_MAJOR:
+        c_out = dy.shape[-1]
+        T = dy.numel() // c_out
+    else:
+        c_out = dy.shape[0]
+        T = dy.numel() // c_out
+    db = out if out is not None else torch.empty(c_out, dtype=torch.float32, device=dy.device)
+    if ws is None:
+        ws = _ws(L.efqat_bias_grad_workspace_bytes(T, c_out, dy_layout), dy)
+    rc = L.efqat_bias_grad(_p(dy), _dt(dy), dy_layout, T, c_out, _p(db), _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_bias_grad")
+    return db
 
 
 def _bwd_outputs(x, w, k, dx_dtype, scatter):

@@ -253,3 +253,70 @@ extern "C" int efqat_network_select(const double* scores, const int64_t* layer_o
   }
   return EFQAT_OK;
 }
+
+// ------------------------------------------------------------------------------------------------
+// EfQAT-LWPN (Table 2): blocks are whole layers.  Every channel of a layer has the same number of weights, so the
+// layer's mean |w| is the mean of its channel means: one block per layer reduces them in double precision in a
+// fixed order.
+namespace efqat {
+
+__global__ __launch_bounds__(256) void k_layer_means(const double* __restrict__ scores,
+                                                     const int64_t* __restrict__ layer_off,
+                                                     double* __restrict__ layer_scores) {
+  __shared__ double red[256];
+  const int64_t b = layer_off[blockIdx.x], e = layer_off[blockIdx.x + 1];
+  double s = 0.0;
+  for (int64_t i = b + threadIdx.x; i < e; i += 256) s += scores[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) layer_scores[blockIdx.x] = e > b ? red[0] / (double)(e - b) : 0.0;
+}
+
+// k_per_layer[l] = channels of layer l if l is among the (ascending) selected layers, else 0
+__global__ void k_layer_flags(const int64_t* __restrict__ layer_off, int64_t n_layers,
+                              const int32_t* __restrict__ layer_idx, int64_t k_layers,
+                              int32_t* __restrict__ k_per_layer) {
+  const int64_t l = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= n_layers) return;
+  int64_t lo = 0, hi = k_layers;                      // binary search for l in layer_idx
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (layer_idx[mid] < l) lo = mid + 1; else hi = mid;
+  }
+  const bool on = lo < k_layers && layer_idx[lo] == l;
+  k_per_layer[l] = on ? (int32_t)(layer_off[l + 1] - layer_off[l]) : 0;
+}
+
+}  // namespace efqat
+
+using namespace efqat;
+
+extern "C" size_t efqat_layer_select_workspace_bytes(int64_t n_layers) {
+  return round_up((size_t)(n_layers > 0 ? n_layers : 1) * sizeof(double), 256);
+}
+
+extern "C" int efqat_layer_select(const double* scores, const int64_t* layer_off, int64_t n_layers,
+                                  int64_t k_layers, double* layer_scores, int32_t* layer_idx,
+                                  int32_t* k_per_layer, void* ws, size_t ws_bytes, void* stream) {
+  if (n_layers <= 0 || n_layers > INT32_MAX) return EFQAT_ERR_BAD_SHAPE;
+  if (k_layers < 0 || k_layers > n_layers) return EFQAT_ERR_BAD_K;
+  if (!scores || !layer_off || !k_per_layer || !ws || (k_layers > 0 && !layer_idx)) return EFQAT_ERR_NULL_PTR;
+  if (ws_bytes < efqat_layer_select_workspace_bytes(n_layers)) return EFQAT_ERR_WORKSPACE;
+  if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  double* ls = layer_scores ? layer_scores : (double*)ws;
+  hipLaunchKernelGGL(k_layer_means, dim3((unsigned)n_layers), dim3(256), 0, st, scores, layer_off, ls);
+  EFQAT_LAUNCH_CHECK();
+  if (k_layers > 0) {
+    hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, ls, n_layers, k_layers, layer_idx);
+    EFQAT_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_layer_flags, dim3((unsigned)ceil_div(n_layers, 256)), dim3(256), 0, st, layer_off, n_layers,
+                     layer_idx, k_layers, k_per_layer);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}

@@ -65,6 +65,17 @@ def test_argument_validation_needs_no_device():
     assert L.efqat_channel_select(fake, 8, 4, 2, None, fake, fake, 8, None) == -6
     assert L.efqat_network_select(fake, fake, 2, 8, 9, fake, fake, fake, 1 << 20, None) == -4
     assert L.efqat_network_select(fake, None, 2, 8, 3, fake, fake, fake, 1 << 20, None) == -1
+    assert L.efqat_layer_select(fake, fake, 4, 5, None, fake, fake, fake, 1 << 20, None) == -4
+    assert L.efqat_layer_select(fake, fake, 0, 0, None, fake, fake, fake, 1 << 20, None) == -2
+    assert L.efqat_layer_select(fake, fake, 4, 2, None, None, fake, fake, 1 << 20, None) == -1
+    assert L.efqat_layer_select(fake, fake, 4, 2, None, fake, fake, fake, 8, None) == -6
+    # bias gradient
+    assert L.efqat_bias_grad(None, 1, 0, 8, 8, fake, fake, 1 << 20, None) == -1
+    assert L.efqat_bias_grad(fake, 1, 0, 0, 8, fake, fake, 1 << 20, None) == -2
+    assert L.efqat_bias_grad(fake, 5, 0, 8, 8, fake, fake, 1 << 20, None) == -8
+    assert L.efqat_bias_grad(fake, 1, 3, 8, 8, fake, fake, 1 << 20, None) == -5
+    assert L.efqat_bias_grad(fake, 1, 0, 8, 8, fake, fake, 16, None) == -6
+    assert L.efqat_bias_grad(fake, 1, 0, 8, 8, fake, fake + 4, 1 << 20, None) == -9
 
     # linear backward
     def lin(dy=fake, T=8, c_in=8, c_out=8, k=2, idx=fake, dw=fake, ws=fake, wsb=1 << 30, dyd=1, lay=0, sc=0):
@@ -101,6 +112,9 @@ def test_workspace_queries_are_host_only_and_monotone():
     assert L.efqat_conv_bwd_workspace_bytes(64, 14, 14, 256, 256, 3, 3, 1, 1, 64, 1, 0) > 0
     assert L.efqat_channel_select_workspace_bytes(11008) >= 11008 * 8
     assert L.efqat_fakequant_fwd_workspace_bytes(12288, 768, 0) >= 8192
+    assert L.efqat_bias_grad_workspace_bytes(12288, 3072, 0) >= (12288 // 64) * 3072 * 4
+    assert L.efqat_bias_grad_workspace_bytes(12288, 3072, 1) >= 3072 * 4
+    assert L.efqat_layer_select_workspace_bytes(48) >= 48 * 8
 
 
 def test_product_path_has_no_oracle_or_cpu_fallback():

@@ -76,6 +76,20 @@ def test_cfg2_bert_ffn_full(layer, frac):
     assert np.all(np.abs(host(out["ds_w"]) - dS_w) <= 1e-3 * row_l2 + 1e-30)
 
 
+@pytest.mark.parametrize("layer", [0, 1])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_cfg2_bias_grad_full(layer, layout):
+    cfg = synth.CFG2
+    name, T, c_in, c_out = cfg["layers"][layer]
+    _, _, dY = synth.linear_layer(cfg["seed"] + layer, T, c_in, c_out, act_dtype="bf16")
+    dyh = dY if layout == 0 else np.ascontiguousarray(dY.T)
+    db = ef.bias_grad(act_tensor(dyh, "bf16"), dy_layout=layout)
+    torch.cuda.synchronize()
+    ref = orc.bias_grad(dY)
+    scale = np.sqrt((dY.astype(np.float64) ** 2).sum(axis=0))
+    assert np.max(np.abs(host(db) - ref) / scale) <= 1e-5
+
+
 @pytest.mark.parametrize("layer,w_bits", [(0, 4), (1, 8)])
 def test_cfg3_attention_projections_full(layer, w_bits):
     cfg = synth.CFG3

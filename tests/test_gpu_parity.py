@@ -128,6 +128,44 @@ def test_network_select_cwpn():
         assert idx.cpu().numpy().tolist() == np.concatenate(ref).astype(np.int64).tolist() if k_total else True
 
 
+def test_layer_select_lwpn():
+    shapes = [(64, 32), (48, 100), (200, 8), (16, 16), (16, 16), (33, 7)]
+    ws, scores, offs = [], [], [0]
+    for i, (c, b) in enumerate(shapes):
+        W = synth.normal(70 + i, 1, (c, b), std=0.02 * (1 + 0.25 * ((i * 5) % 4))).astype(np.float32)
+        ws.append(W); scores.append(orc.channel_importance(W)); offs.append(offs[-1] + c)
+    ws[4] = ws[3].copy(); scores[4] = scores[3].copy()           # two layers with identical importance
+    flat = dev(np.concatenate(scores)); off_d = dev(np.array(offs, dtype=np.int64))
+    for k_layers in (0, 1, 2, 3, 4, len(shapes)):
+        lidx, kpl, ls = ef.layer_select(flat, off_d, k_layers)
+        torch.cuda.synchronize()
+        sel, kpl_ref, imp = orc.layer_top_k(ws, k_layers)
+        np.testing.assert_allclose(ls.cpu().numpy(), imp, rtol=1e-12)
+        assert lidx.cpu().numpy().tolist() == [int(v) for v in sel]
+        assert kpl.cpu().numpy().tolist() == [int(v) for v in kpl_ref]
+
+
+BIAS_CASES = [
+    # T, c_out, kind, layout
+    (517, 264, "bf16", 0), (517, 264, "f32", 0), (300, 77, "bf16", 0), (300, 77, "f32", 0), (1, 8, "bf16", 0),
+    (2048, 1024, "bf16", 0), (517, 264, "bf16", 1), (9000, 5, "f32", 1), (300, 77, "f32", 1), (4096, 520, "bf16", 1),
+]
+
+
+@pytest.mark.parametrize("T,c_out,kind,layout", BIAS_CASES, ids=lambda v: str(v))
+def test_bias_grad_matches_oracle(T, c_out, kind, layout):
+    dY = synth.normal(900 + T + c_out, 3, (T, c_out), std=1.0)
+    dY = synth.as_bf16_values(dY) if kind == "bf16" else dY.astype(np.float32)
+    dy_host = dY if layout == ef.DY_TOKEN_MAJOR else np.ascontiguousarray(dY.T)
+    db = ef.bias_grad(act_tensor(dy_host, kind), dy_layout=layout)
+    torch.cuda.synchronize()
+    ref = orc.bias_grad(dY)
+    # fp32 partial sums over at most 256 terms per lane, then fp64: error relative to the size of a
+    # random-sign sum, the l2 norm of the column
+    scale = np.sqrt((np.asarray(dY, dtype=np.float64) ** 2).sum(axis=0))
+    assert np.max(np.abs(db.cpu().numpy().astype(np.float64) - ref) / scale) <= 1e-5
+
+
 # ---------------------------------------------------------------- linear backward
 def _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter, dx_dtype=None):
     T, c_in = X.shape; c_out = W.shape[0]
