@@ -20,6 +20,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -36,7 +38,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
     ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -49,55 +51,79 @@ def parse_args():
 class Layer:
     """Device buffers of one layer, all allocated up front (nothing is allocated in a timed region)."""
 
-    def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth, fracs):
-        self.name, self.T, self.c_in, self.c_out = name, T, c_in, c_out
+    def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth, fracs,
+                 conv=None):
+        self.name, self.c_in, self.c_out, self.conv = name, c_in, c_out, conv
         self.a_bits, self.w_bits, self.layout = a_bits, w_bits, layout
-        X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype)
+        L = ef.lib()
+        dyd = 1 if act_dtype == "bf16" else 0
+        ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
+        if conv is None:
+            X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype)
+            self.T, self.T_in, self.taps = T, T, 1
+            bwd_ws = [L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k_, dyd, layout) for k_ in ks]
+        else:
+            g = conv
+            X, W, dY = synth.conv_layer(seed, g["N"], g["H"], g["W"], c_in, c_out, g["kh"], g["kw"], g["stride"],
+                                        g["pad"], act_dtype=act_dtype)
+            self.T = int(np.prod(dY.shape[:3]))         # output pixels
+            self.T_in = int(np.prod(X.shape[:3]))       # input pixels
+            self.taps = g["kh"] * g["kw"]
+            bwd_ws = [L.efqat_conv_bwd_workspace_bytes(g["N"], g["H"], g["W"], c_in, c_out, g["kh"], g["kw"],
+                                                       g["stride"], g["pad"], k_, dyd, layout) for k_ in ks]
         self.host = (X, W, dY)
         tdt = torch.bfloat16 if act_dtype == "bf16" else torch.float32
         self.x = torch.from_numpy(X).to(tdt).cuda()
         self.w = torch.from_numpy(W).cuda()
-        dyh = dY if layout == 0 else dY.T.copy()
+        dyh = dY if layout == 0 else dY.reshape(-1, c_out).T.copy()
         self.dy = torch.from_numpy(dyh).to(tdt).cuda()
         dev = self.x.device
         e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
-        self.fx = dict(codes=e((T, c_in), torch.uint8), clip_bits=e((T, (c_in + 31) // 32), torch.int32),
+        block = self.taps * c_in                         # weights per output channel
+        self.fx = dict(codes=e(X.shape, torch.uint8), clip_bits=e((self.T_in, (c_in + 31) // 32), torch.int32),
                        scale=e(1, torch.float32), zero_point=e(1, torch.float32))
-        self.fw = dict(codes=e((c_out, c_in), torch.int8), clip_bits=e((c_out, (c_in + 31) // 32), torch.int32),
+        self.fw = dict(codes=e(W.shape, torch.int8), clip_bits=e((c_out, (block + 31) // 32), torch.int32),
                        scale=e(c_out, torch.float32))
         self.scores = e(c_out, torch.float64)
         self.idx_full = e(c_out, torch.int32)
-        self.dx = e((T, c_in), tdt)
-        self.dw = e((c_out, c_in), torch.float32)       # compact [k, c_in] uses the first k rows
+        self.dx = e(X.shape, tdt)
+        self.dw = e(W.shape, torch.float32)              # compact [k, ...] uses the first k rows
         self.ds_w = e(c_out, torch.float32)
         self.ds_x, self.dz_x = e(1, torch.float32), e(1, torch.float32)
-        L = ef.lib()
-        dyd = 1 if act_dtype == "bf16" else 0
         # the backward workspace is not monotone in k: size it for every update fraction that will be run
-        ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
-        need = max([L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k_, dyd, layout) for k_ in ks] +
-                   [L.efqat_fakequant_fwd_workspace_bytes(T, c_in, 0),
-                    L.efqat_channel_select_workspace_bytes(c_out)])
+        need = max(bwd_ws + [L.efqat_fakequant_fwd_workspace_bytes(self.T_in, c_in, 0),
+                             L.efqat_channel_select_workspace_bytes(c_out)])
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
 
     def forward_quant(self, ef):
-        ef.fakequant_fwd(self.x, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=self.fx)
-        ef.fakequant_fwd(self.w, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws, out=self.fw)
+        x2 = self.x.view(self.T_in, self.c_in)
+        w2 = self.w.view(self.c_out, -1)
+        fx2 = dict(self.fx, codes=self.fx["codes"].view(self.T_in, self.c_in))
+        fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
+        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=fx2)
+        ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws, out=fw2)
 
     def select(self, ef, k):
         idx = self.idx_full[:k]
-        ef.channel_select(self.w, k, ws=self.ws, out=dict(scores=self.scores, idx=idx))
+        ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws, out=dict(scores=self.scores, idx=idx))
         return idx
 
     def backward(self, ef, idx):
         k = int(idx.numel())
         out = dict(dx=self.dx, dw=self.dw[:max(k, 1)], ds_w=self.ds_w[:max(k, 1)], ds_x=self.ds_x, dz_x=self.dz_x)
-        ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
-                      self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
-                      idx if k else None, dy_layout=self.layout, ws=self.ws, out=out)
+        if self.conv is None:
+            ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
+                          self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
+                          idx if k else None, dy_layout=self.layout, ws=self.ws, out=out)
+        else:
+            ef.conv_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
+                        self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
+                        idx if k else None, stride=self.conv["stride"], pad=self.conv["pad"],
+                        dy_layout=self.layout, ws=self.ws, out=out)
 
     def flops(self, k):
-        return 2.0 * self.T * self.c_in * (self.c_out + k)
+        # Eq. 7 / Eq. 8 op counts (x2 for multiply + add): dX over every channel, dW over the k selected ones
+        return 2.0 * self.T * self.c_in * self.taps * (self.c_out + k)
 
 
 def time_region(torch, fn, steps):
@@ -125,7 +151,10 @@ def cpu_baseline(layers, num, den, a_bits, w_bits):
         sw = orc.weight_scale_minmax(W, w_bits)
         k = orc.k_from_ratio(lay.c_out, num, den)
         idx = orc.top_k_channels(orc.channel_importance(W), k)
-        orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
+        if lay.conv is None:
+            orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
+        else:
+            orc.conv_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx, stride=lay.conv["stride"], pad=lay.conv["pad"])
         fl += lay.flops(k)
     dt = time.perf_counter() - t0
     return dict(value=fl / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
@@ -148,15 +177,20 @@ def main():
         b.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg5": synth.CFG5}[args.workload]
+    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg4": synth.CFG4, "cfg5": synth.CFG5}[args.workload]
     w_bits = cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0]
     if args.fraction:
         num, den = (int(t) for t in args.fraction.split("/"))
     else:
         num, den = 1, 4
     fracs = list(cfg["fractions"]) + [(num, den), (1, 1)]
-    layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
-                    args.dy_layout, synth, fracs) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
+    if "layers" in cfg:
+        layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
+                        args.dy_layout, synth, fracs) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
+    else:   # the convolution pair of config 4
+        layers = [Layer(ef, torch, n, cfg["seed"] + i, 0, cfg[n]["c_in"], cfg[n]["c_out"], cfg["act_dtype"],
+                        cfg["a_bits"], w_bits, args.dy_layout, synth, fracs, conv=cfg[n])
+                  for i, n in enumerate(("conv", "conv1x1"))]
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
     def step():
@@ -176,7 +210,7 @@ def main():
     value = flops / sec / 1e12
 
     # dominant kernel: the dX product (always the full C_out); algorithmic flops per launch
-    dx_flops = sum(2.0 * l.T * l.c_in * l.c_out for l in layers) / len(layers)
+    dx_flops = sum(2.0 * l.T * l.c_in * l.taps * l.c_out for l in layers) / len(layers)
     dx_avg_s = dx_ms / max(dx_n, 1) / 1e3
     achieved = dx_flops / dx_avg_s / 1e12 if dx_n else 0.0
     roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
@@ -220,7 +254,7 @@ def main():
     # low-precision forward (int8 matrix cores), not part of the step or of `value`: the paper leaves the forward
     # pass out of its timings
     fwd = None
-    if not args.no_sweep:
+    if not args.no_sweep and all(l.conv is None for l in layers):
         ys = [torch.empty((l.T, l.c_out), dtype=l.x.dtype if l.x.dtype == torch.bfloat16 else torch.float32,
                           device="cuda") for l in layers]
         fws = [torch.empty(max(ef.lib().efqat_linear_fwd_workspace_bytes(l.T, l.c_in, l.c_out), 256),

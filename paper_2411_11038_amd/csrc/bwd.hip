@@ -37,18 +37,49 @@ __device__ __forceinline__ void unpack4b(uint32_t v, float (&o)[4]) {
   for (int t = 0; t < 4; ++t) o[t] = (float)(T)((v >> (8 * t)) & 0xFFu);
 }
 
+struct ConvGeom {
+  int N, H, W, c_in, c_out, KH, KW, stride, pad, Ho, Wo;
+};
+
+// Extras of the transposing copy, all zero / off for a plain 2-D transpose.  blockIdx.z = tap of a convolution:
+//   weights:      tap t reads in + t * z_in and writes at column offset out_off + t * z_out;
+//   activations:  (conv = 1) source row i is an output pixel (n, ho, wo); tap t reads the input pixel
+//                 (n, ho*s + kh - p, wo*s + kw - p), or contributes 0 when that lies outside the image (the
+//                 padding is zero in the de-quantised domain), and writes output rows t * z_orow + j.
+struct TransposeExtra {
+  int64_t z_in, z_out, z_orow;
+  int conv;
+  ConvGeom g;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in, int64_t ld_in, int64_t R,
                                                         int64_t Cn, const int32_t* __restrict__ colmap,
                                                         const float* __restrict__ rowscale,
                                                         const float* __restrict__ subz, bf16_t* __restrict__ out,
                                                         int64_t ldo, int64_t out_off, int64_t i_pad, int vec,
-                                                        uint32_t* __restrict__ zero_page) {
+                                                        uint32_t* __restrict__ zero_page, const TransposeExtra ex) {
   __shared__ bf16_t tile[64][66];                     // tile[i][j]
   // optional by-product: 256 bytes of zeros for a later kernel of the same call (saves a launch)
-  if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64) zero_page[threadIdx.x] = 0u;
+  if (zero_page && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64)
+    zero_page[threadIdx.x] = 0u;
   const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
   const float sub = subz ? rintf(subz[0]) : 0.0f;
+  const int tap = blockIdx.z;
+  in += (int64_t)tap * ex.z_in;
+  out += (int64_t)tap * ex.z_out + (int64_t)tap * ex.z_orow * ldo;
+  // source row of logical row i, or -1: contributes zeros
+  auto src_row = [&](int64_t i) -> int64_t {
+    if (i >= R) return -1;
+    if (!ex.conv) return i;
+    const ConvGeom& g = ex.g;
+    const int wo = (int)(i % g.Wo);
+    const int ho = (int)((i / g.Wo) % g.Ho);
+    const int n = (int)(i / ((int64_t)g.Wo * g.Ho));
+    const int h = ho * g.stride + tap / g.KW - g.pad, w = wo * g.stride + tap % g.KW - g.pad;
+    if (h < 0 || h >= g.H || w < 0 || w >= g.W) return -1;
+    return ((int64_t)n * g.H + h) * g.W + w;
+  };
   if (vec && j0 + 64 <= Cn) {
     // dense source, 4 consecutive columns per lane (one 4..16-byte load)
     const int jq = (threadIdx.x & 15) * 4, ib = threadIdx.x >> 4;
@@ -56,9 +87,10 @@ __global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in
     for (int rr = 0; rr < 4; ++rr) {
       const int li = ib + 16 * rr;
       const int64_t i = i0 + li;
+      const int64_t si = src_row(i);
       float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (i < R) {
-        const typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(in + i * ld_in + j0 + jq);
+      if (si >= 0) {
+        const typename Vec4<T>::type raw = *reinterpret_cast<const typename Vec4<T>::type*>(in + si * ld_in + j0 + jq);
         if constexpr (sizeof(T) == 1) unpack4b<T>(raw, v); else unpack4(raw, v);
         const float rs = rowscale ? rowscale[i] : 1.0f;
 #pragma unroll
@@ -75,9 +107,10 @@ __global__ __launch_bounds__(256) void k_transpose_bf16(const T* __restrict__ in
     for (int rr = 0; rr < 16; ++rr) {
       const int li = ty + 4 * rr;
       const int64_t i = i0 + li;
+      const int64_t si = src_row(i);
       float v = 0.0f;
-      if (i < R && j < Cn) {
-        v = rd<T>(in, i * ld_in + jc) - sub;
+      if (si >= 0 && j < Cn) {
+        v = rd<T>(in, si * ld_in + jc) - sub;
         if (rowscale) v *= rowscale[i];
       }
       tile[li][tx] = f32_to_bf16(v);
@@ -145,10 +178,6 @@ __global__ __launch_bounds__(256) void k_gather_cols(const T* __restrict__ dy, i
 
 // ------------------------------------------------------------------------------------------------
 // conv helpers (explicit im2col into workspace; the contractions then run on the same GEMM core)
-struct ConvGeom {
-  int N, H, W, c_in, c_out, KH, KW, stride, pad, Ho, Wo;
-};
-
 // dX operand: colA[(n,h,w)][tap*ldc + co] = dYn[(n,ho,wo)][co] with ho*stride + kh - pad = h (else 0).
 // dYn is the token-major bf16 copy of dY with pitch ldc (multiple of 8).
 __global__ __launch_bounds__(256) void k_im2col_dy(const bf16_t* __restrict__ dyn, int64_t ldc, ConvGeom g,
@@ -173,41 +202,6 @@ __global__ __launch_bounds__(256) void k_im2col_dy(const bf16_t* __restrict__ dy
         v = *reinterpret_cast<const uint4*>(dyn + (((int64_t)n * g.Ho + ho) * g.Wo + wo) * ldc + c8 * 8);
     }
     *reinterpret_cast<uint4*>(col + (r * taps + tap) * ldc + c8 * 8) = v;
-  }
-}
-
-// dW operand: colXT[(tap,ci)][(n,ho,wo)] = x_codes[n][ho*s+kh-p][wo*s+kw-p][ci] - round(Z_x)  (0 outside the
-// image: the padding is zero in the de-quantised domain).  Tiled transpose, blockIdx.z = tap.
-__global__ __launch_bounds__(256) void k_im2colT_x(const uint8_t* __restrict__ xc, const float* __restrict__ z_x,
-                                                   ConvGeom g, bf16_t* __restrict__ out, int64_t ldk) {
-  __shared__ bf16_t tile[64][66];
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int tap = blockIdx.z, kh = tap / g.KW, kw = tap % g.KW;
-  const int64_t Kp = (int64_t)g.N * g.Ho * g.Wo;
-  const int64_t i0 = (int64_t)blockIdx.x * 64, j0 = (int64_t)blockIdx.y * 64;
-  const float z = rintf(z_x[0]);
-  const int64_t j = j0 + tx;
-#pragma unroll 4
-  for (int rr = 0; rr < 16; ++rr) {
-    const int li = ty + 4 * rr;
-    const int64_t i = i0 + li;                        // (n,ho,wo)
-    float v = 0.0f;
-    if (i < Kp && j < g.c_in) {
-      const int wo = (int)(i % g.Wo);
-      const int ho = (int)((i / g.Wo) % g.Ho);
-      const int n = (int)(i / ((int64_t)g.Wo * g.Ho));
-      const int h = ho * g.stride + kh - g.pad, w = wo * g.stride + kw - g.pad;
-      if (h >= 0 && h < g.H && w >= 0 && w < g.W)
-        v = (float)xc[(((int64_t)n * g.H + h) * g.W + w) * g.c_in + j] - z;
-    }
-    tile[li][tx] = (bf16_t)(__float_as_uint(v) >> 16);  // small integers: exact
-  }
-  __syncthreads();
-#pragma unroll 4
-  for (int rr = 0; rr < 16; ++rr) {
-    const int lj = ty + 4 * rr;
-    const int64_t jo = j0 + lj, io = i0 + tx;
-    if (jo < g.c_in && io < ldk) out[((int64_t)tap * g.c_in + jo) * ldk + io] = tile[tx][lj];
   }
 }
 
@@ -298,14 +292,17 @@ static inline unsigned grid1d(int64_t total, int per_block = 256) {
 template <typename T>
 static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, const int32_t* colmap,
                              const float* rowscale, const float* subz, bf16_t* out, int64_t ldo, int64_t out_off,
-                             int64_t i_pad, hipStream_t st, uint32_t* zero_page = nullptr) {
-  dim3 grid((unsigned)ceil_div(i_pad, 64), (unsigned)ceil_div(Cn, 64));
+                             int64_t i_pad, hipStream_t st, uint32_t* zero_page = nullptr, int taps = 1,
+                             const TransposeExtra* extra = nullptr) {
+  dim3 grid((unsigned)ceil_div(i_pad, 64), (unsigned)ceil_div(Cn, 64), (unsigned)taps);
+  TransposeExtra ex{};
+  if (extra) ex = *extra;
   if (grid.y > 65535) return EFQAT_ERR_BAD_SHAPE;
   // 16-byte stores need an 8-element aligned destination; 4-wide loads a dense, 4-element aligned source
   if ((ldo % 8) || (out_off % 8) || (i_pad % 8) || ((uintptr_t)out % 16)) return EFQAT_ERR_ALIGNMENT;
   const int vec = (!colmap && (ld_in % 4) == 0 && ((uintptr_t)in % (4 * sizeof(T))) == 0) ? 1 : 0;
   hipLaunchKernelGGL((k_transpose_bf16<T>), grid, dim3(256), 0, st, in, ld_in, R, Cn, colmap, rowscale, subz, out,
-                     ldo, out_off, i_pad, vec, zero_page);
+                     ldo, out_off, i_pad, vec, zero_page, ex);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -381,10 +378,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   int rc;
 
   // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
-  for (int tap = 0; tap < taps; ++tap) {
-    rc = transpose_to_bf16<int8_t>(io.w_codes + (int64_t)tap * c_in, (int64_t)taps * c_in, c_out, c_in, nullptr,
-                                   io.s_w, nullptr, wqT, p.Kx, (int64_t)tap * p.ldc, p.ldc, st,
-                                   (tap == 0 && p.tn) ? (uint32_t*)zero_page : nullptr);
+  {
+    TransposeExtra ex{};
+    ex.z_in = c_in; ex.z_out = p.ldc;                 // one launch for all taps
+    rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
+                                   p.Kx, 0, p.ldc, st, p.tn ? (uint32_t*)zero_page : nullptr, taps, &ex);
     if (rc) return rc;
   }
 
@@ -453,9 +451,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   } else {
   // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16
   if (im2col) {
-    dim3 grid((unsigned)ceil_div(p.ldt, 64), (unsigned)ceil_div(c_in, 64), (unsigned)taps);
-    hipLaunchKernelGGL(k_im2colT_x, grid, dim3(256), 0, st, io.x_codes, io.z_x, *cg, xcT, p.ldt);
-    EFQAT_LAUNCH_CHECK();
+    TransposeExtra ex{};
+    ex.z_orow = c_in; ex.conv = 1; ex.g = *cg;        // xcT[(tap, ci)][(n, ho, wo)], one launch for all taps
+    rc = transpose_to_bf16<uint8_t>(io.x_codes, c_in, T_out, c_in, nullptr, nullptr, io.z_x, xcT, p.ldt, 0, p.ldt,
+                                    st, nullptr, taps, &ex);
+    if (rc) return rc;
   } else {
     rc = transpose_to_bf16<uint8_t>(io.x_codes, c_in, T_out, c_in, nullptr, nullptr, io.z_x, xcT, p.ldt, 0, p.ldt, st);
     if (rc) return rc;
