@@ -36,8 +36,8 @@ DX_KERNEL_TRAFFIC_BYTES = {("cfg2", 0): 0.5 * (143.3e6 + 18.9e6 + 245.6e6 + 75.6
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
     ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")

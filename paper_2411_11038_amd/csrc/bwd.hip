@@ -207,8 +207,8 @@ __global__ __launch_bounds__(256) void k_im2col_dy(const bf16_t* __restrict__ dy
 
 // ------------------------------------------------------------------------------------------------
 // dS_x, dZ_x: ordered sum of the per-block partials written by the dX epilogue.
-__global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, int64_t n,
-                                                      float* __restrict__ ds_x, float* __restrict__ dz_x) {
+__device__ __forceinline__ void sum_partials_block(const float* __restrict__ part, int64_t n,
+                                                   float* __restrict__ ds_x, float* __restrict__ dz_x) {
   double a = 0.0, b = 0.0;
   for (int64_t i = threadIdx.x; i < n; i += 256) { a += (double)part[2 * i]; b += (double)part[2 * i + 1]; }
   a = wave_sum(a); b = wave_sum(b);
@@ -221,6 +221,11 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
   }
 }
 
+__global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, int64_t n,
+                                                      float* __restrict__ ds_x, float* __restrict__ dz_x) {
+  sum_partials_block(part, n, ds_x, dz_x);
+}
+
 // Second pass of the restricted weight gradient: ordered split-K sum, S_x scaling, straight-through mask
 // of the weight quantizer and the per-row scale gradient
 //   dW[c][j] = in range ? dW_q : 0,  dS_w[c] = sum_j dW_q * (in range ? code - w/S_w : code),  c = idx[m].
@@ -229,7 +234,13 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
                                                    const int8_t* __restrict__ w_codes,
                                                    const uint32_t* __restrict__ w_clip, const float* __restrict__ w,
                                                    const float* __restrict__ s_w, const int32_t* __restrict__ idx,
-                                                   float* __restrict__ dw, int scatter, float* __restrict__ ds_w) {
+                                                   float* __restrict__ dw, int scatter, float* __restrict__ ds_w,
+                                                   const float* __restrict__ part_dx, int64_t n_part_dx,
+                                                   float* __restrict__ ds_x, float* __restrict__ dz_x) {
+  if ((int64_t)blockIdx.x == k) {                     // one extra block: dS_x, dZ_x from the dX epilogue's partials
+    sum_partials_block(part_dx, n_part_dx, ds_x, dz_x);
+    return;
+  }
   const int64_t m = blockIdx.x;
   const int64_t c = idx[m];
   const int64_t wpr = (ncols + 31) >> 5;
@@ -422,11 +433,12 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
   rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx,
-                     (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n, io.ds_x, io.dz_x);
-  EFQAT_LAUNCH_CHECK();
-
-  if (io.k == 0) return EFQAT_OK;
+  const int64_t n_part_dx = (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n;
+  if (io.k == 0) {
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx, n_part_dx, io.ds_x, io.dz_x);
+    EFQAT_LAUNCH_CHECK();
+    return EFQAT_OK;
+  }
 
   if (p.tn) {
     // ---- dW product straight from token-major operands: A = the selected columns of dY (compacted once, or dY
@@ -491,8 +503,10 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   }
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0) ? 1 : 0;
-  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw, fvec,
-                     io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w);
+  // k blocks for the rows of dW plus one that finishes dS_x, dZ_x
+  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k + 1), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw,
+                     fvec, io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w, part_dx,
+                     n_part_dx, io.ds_x, io.dz_x);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
