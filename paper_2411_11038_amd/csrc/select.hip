@@ -39,6 +39,9 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   __shared__ long long s_need;
   __shared__ int wsum_gt[16], wsum_eq[16];
   __shared__ long long s_base_gt, s_base_eq;
+  __shared__ unsigned long long cand_key[64];
+  __shared__ int cand_idx[64];
+  __shared__ int s_bin_count, s_ncand;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   // Up to KPT keys per thread stay in registers for all passes (n <= 12288); longer inputs are re-read.
   constexpr int KPT = 12;
@@ -77,6 +80,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   if (tid == 0) {
     s_prefix = first_pass == 7 ? 0ull : (vor >> (8 * (first_pass + 1)));   // the shared high bytes
     s_need = k;
+    s_bin_count = 1 << 30;
   }
   for (int b = tid; b < 16 * 256; b += 1024) (&hist[0][0])[b] = 0u;
   __syncthreads();
@@ -123,9 +127,56 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
         else { a += h3; if (a + h2 >= need) d = 2; else { a += h2; if (a + h1 >= need) d = 1; else { a += h1; d = 0; } } }
         s_need = need - a;                              // still to take among keys whose byte equals d
         s_prefix = (prefix << 8) | (unsigned long long)(4 * lane + d);
+        s_bin_count = d == 3 ? h3 : d == 2 ? h2 : d == 1 ? h1 : h0;
       }
+      if (lane == 0) s_ncand = 0;
     }
     __syncthreads();
+    // Few keys left under the chosen prefix: finish at once instead of one pass per remaining byte.  The
+    // candidates are gathered (in any order) and ranked by one wavefront under (key descending, index ascending).
+    if (pass > 0 && s_bin_count <= 64) {
+      const unsigned long long np = s_prefix;
+      if (cached) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+          const int64_t i = (int64_t)q * 1024 + tid;
+          if (i < n && (keys[q] >> (8 * pass)) == np) {
+            const int slot = atomicAdd(&s_ncand, 1);
+            cand_key[slot] = keys[q]; cand_idx[slot] = (int)i;
+          }
+        }
+      } else {
+        for (int64_t i = tid; i < n; i += 1024) {
+          const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
+          if ((key >> (8 * pass)) == np) {
+            const int slot = atomicAdd(&s_ncand, 1);
+            cand_key[slot] = key; cand_idx[slot] = (int)i;
+          }
+        }
+      }
+      __syncthreads();
+      if (wv == 0) {
+        const int nc = s_ncand;                         // == s_bin_count
+        const int need = (int)s_need;                   // 1 .. nc
+        const bool on = lane < nc;
+        const unsigned long long mk = on ? cand_key[lane] : 0ull;
+        const int mi = on ? cand_idx[lane] : 0;
+        int rank = 0;
+        for (int j = 0; j < nc; ++j) {
+          const unsigned long long kj = cand_key[j];
+          const int ij = cand_idx[j];
+          rank += (kj > mk || (kj == mk && ij < mi)) ? 1 : 0;
+        }
+        const unsigned long long hit = __ballot(on && rank == need - 1);   // exactly one lane
+        const int src = __ffsll((long long)hit) - 1;
+        const unsigned int tlo = __shfl((unsigned int)mk, src, kWave), thi = __shfl((unsigned int)(mk >> 32), src, kWave);
+        const unsigned long long Tk = ((unsigned long long)thi << 32) | tlo;
+        const unsigned long long eqtake = __ballot(on && mk == Tk && rank < need);
+        if (lane == 0) { s_prefix = Tk; s_need = __popcll(eqtake); }
+      }
+      __syncthreads();
+      break;
+    }
   }
   const unsigned long long T = s_prefix;
   const long long need = s_need;
