@@ -63,12 +63,10 @@ __global__ __launch_bounds__(256) void k_minmax_partial(const T* __restrict__ x,
 }
 
 // Eq. 2: S_x = (beta - alpha) / (2^b - 1), Z_x = -round(alpha / S_x), each a single-precision op.
-// Called by all 256 threads of a block: reduces the per-block (min, max) pairs and returns S_x, Z_x to every
-// thread (min and max are exact in any order, so every block gets identical values).
-__device__ __forceinline__ void act_qparams_from_partials(const float* __restrict__ part, int nparts, int bits,
-                                                          float* s_out, float* z_out) {
+__global__ __launch_bounds__(256) void k_act_qparams(const float* __restrict__ part, int nparts, int bits,
+                                                     float* __restrict__ scale, float* __restrict__ zp) {
   float lo = INFINITY, hi = -INFINITY;
-  for (int i = threadIdx.x; i < nparts; i += 256) {
+  for (int i = threadIdx.x; i < nparts; i += blockDim.x) {
     lo = fminf(lo, part[2 * i]); hi = fmaxf(hi, part[2 * i + 1]);
   }
   lo = wave_min(lo); hi = wave_max(hi);
@@ -76,13 +74,15 @@ __device__ __forceinline__ void act_qparams_from_partials(const float* __restric
   const int w = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) { s_lo[w] = lo; s_hi[w] = hi; }
   __syncthreads();
-  const float alpha = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
-  const float beta = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
-  const float qmax = (float)((1 << bits) - 1);
-  float s = __fdiv_rn(__fsub_rn(beta, alpha), qmax);
-  if (!(s > 0.0f)) s = 1.0f;                         // zero range
-  *s_out = s;
-  *z_out = 0.0f - rintf(__fdiv_rn(alpha, s));
+  if (threadIdx.x == 0) {
+    const float alpha = fminf(fminf(s_lo[0], s_lo[1]), fminf(s_lo[2], s_lo[3]));
+    const float beta = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+    const float qmax = (float)((1 << bits) - 1);
+    float s = __fdiv_rn(__fsub_rn(beta, alpha), qmax);
+    if (!(s > 0.0f)) s = 1.0f;                       // zero range
+    scale[0] = s;
+    zp[0] = 0.0f - rintf(__fdiv_rn(alpha, s));
+  }
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -94,9 +94,8 @@ __device__ __forceinline__ void act_qparams_from_partials(const float* __restric
 template <typename T, int MODE, bool INIT>
 __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64_t rows, int64_t cols, int vec,
                                                   int bits, float* __restrict__ scale,
-                                                  float* __restrict__ zp, uint8_t* __restrict__ codes,
-                                                  uint32_t* __restrict__ clip, bf16_t* __restrict__ xq,
-                                                  const float* __restrict__ minmax_part, int nparts) {
+                                                  const float* __restrict__ zp, uint8_t* __restrict__ codes,
+                                                  uint32_t* __restrict__ clip, bf16_t* __restrict__ xq) {
   const int lane = threadIdx.x & 63;
   const int64_t segs = ceil_div(cols, 512);
   const int64_t total = rows * segs;
@@ -105,17 +104,8 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
   float lo, hi, z = 0.0f, s_act = 1.0f;
   if (MODE == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
     lo = 0.0f; hi = (float)((1 << bits) - 1);
-    if (minmax_part) {
-      // min/max initialisation: every block derives S_x, Z_x from the partial extrema (no separate launch);
-      // block 0 publishes them
-      float zz;
-      act_qparams_from_partials(minmax_part, nparts, bits, &s_act, &zz);
-      if (blockIdx.x == 0 && threadIdx.x == 0) { scale[0] = s_act; zp[0] = zz; }
-      z = zz;                                          // already integer valued
-    } else {
-      s_act = scale[0];
-      z = rintf(zp[0]);
-    }
+    s_act = scale[0];
+    z = rintf(zp[0]);
   } else {
     hi = (float)((1 << (bits - 1)) - 1); lo = -hi;
   }
@@ -218,15 +208,14 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
   const int64_t n = rows * cols;
   const int vec_flat = aligned_to(x, 16) ? 1 : 0;
   const int vec_row = (vec_flat && cols % 8 == 0 && aligned_to(codes, 8) && (!xq || aligned_to(xq, 16))) ? 1 : 0;
-  const float* act_part = nullptr;
-  int act_nparts = 0;
   if (init_minmax && mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {
     int64_t np64 = ceil_div(n, 256 * 16);
     const int nparts = (int)(np64 < 1024 ? np64 : 1024);
     float* part = (float*)ws;
     hipLaunchKernelGGL((k_minmax_partial<T>), dim3(nparts), dim3(256), 0, st, x, n, vec_flat, part);
     EFQAT_LAUNCH_CHECK();
-    act_part = part; act_nparts = nparts;
+    hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(256), 0, st, part, nparts, bits, scale, zp);
+    EFQAT_LAUNCH_CHECK();
   }
   const bool row_items = init_minmax && mode == EFQAT_QUANT_W_PER_ROW_SYM;   // one wavefront per row
   const int64_t items = row_items ? rows : rows * ceil_div(cols, 512);
@@ -234,13 +223,13 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
   if (blocks > 256 * 32) blocks = 256 * 32;
   if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM, false>), dim3((unsigned)blocks), dim3(256), 0,
-                       st, x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq, act_part, act_nparts);
+                       st, x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   else if (init_minmax)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, true>), dim3((unsigned)blocks), dim3(256), 0, st, x,
-                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq, act_part, act_nparts);
+                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   else
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, false>), dim3((unsigned)blocks), dim3(256), 0, st, x,
-                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq, act_part, act_nparts);
+                       rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
