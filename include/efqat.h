@@ -159,6 +159,19 @@ size_t efqat_bias_grad_workspace_bytes(int64_t T, int64_t c_out, int dy_layout);
 int efqat_bias_grad(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_out,
                     float* db, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------ options
+ * Process-wide overrides for tests and measurements (like the profiling hooks below they are
+ * the library's only state).  EFQAT_OPT_DX_KERNEL chooses the kernel of the dX product
+ * (Eq. 5 left) of efqat_linear_bwd where both apply (bf16 token-major dY, C_out % 8 == 0,
+ * C_in % 16 == 0): AUTO picks by problem size, BF16 always stages a bf16 copy of W_q^T, INT8
+ * always reads the weight operand from the int8 codes.  All choices give identical results.
+ * Changes the workspace size: query it after setting the option. */
+#define EFQAT_OPT_DX_KERNEL 1
+#define EFQAT_DX_KERNEL_AUTO 0
+#define EFQAT_DX_KERNEL_BF16 1
+#define EFQAT_DX_KERNEL_INT8 2
+int efqat_set_option(int option, int value);
+
 /* ------------------------------------------------------------------ linear backward
  * Backward step of Alg. 1 for one layer Y = X_q W_q^T, X_q = S_x (x_codes - Z_x),
  * W_q[c][:] = S_w[c] w_codes[c][:]:

@@ -21,7 +21,7 @@ EXPORTS = [
     "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
     "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd",
     "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
-    "efqat_profile_enable", "efqat_profile_read",
+    "efqat_profile_enable", "efqat_profile_read", "efqat_set_option",
 ]
 
 
@@ -87,6 +87,8 @@ def lib():
     L.efqat_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.efqat_linear_fwd.restype = ci
     L.efqat_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
+    L.efqat_set_option.restype = ci
+    L.efqat_set_option.argtypes = [ci, ci]
     L.efqat_profile_enable.restype = ci
     L.efqat_profile_enable.argtypes = [ci]
     L.efqat_profile_read.restype = ci
@@ -210,6 +212,14 @@ def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, 
                                 _p(idx) if k_total > 0 else None, _p(kpl), _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_network_select")
     return idx, kpl
+
+
+OPT_DX_KERNEL, DX_KERNEL_AUTO, DX_KERNEL_BF16, DX_KERNEL_INT8 = 1, 0, 1, 2
+
+
+def set_option(option: int, value: int):
+    """Process-wide override (tests, measurements); see efqat_set_option in include/efqat.h."""
+    _check(lib().efqat_set_option(option, value), "efqat_set_option")
 
 
 def layer_select(scores: torch.Tensor, layer_off: torch.Tensor, k_layers: int, ws=None):

@@ -146,6 +146,9 @@ __global__ __launch_bounds__(256) void k_rows_bf16(const T* __restrict__ in, int
   }
 }
 
+// 256 zero bytes that tile loads read in place of rows / columns outside an operand
+__global__ void k_zero_page(uint32_t* __restrict__ p) { p[threadIdx.x] = 0u; }
+
 // Compaction of the selected output channels of a token-major dY (the channel extraction step of Alg. 1, done
 // once per call):  out[t][m] = bf16(dY[t][idx[m]]), m < k;  0 for k <= m < kp.
 // A lane owns two neighbouring compacted channels (their source columns stay in registers); a wavefront thus
@@ -318,6 +321,9 @@ static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, 
   return EFQAT_OK;
 }
 
+// Process-wide override of the dX kernel choice (efqat_set_option), for tests and measurements.
+static int g_opt_dx_kernel = EFQAT_DX_KERNEL_AUTO;
+
 // Plan of one backward call: sizes of every workspace slice (shared by the size query and the call).
 struct BwdPlan {
   int64_t Mx;      // rows of dX as a matrix (T, or N*H*W)
@@ -330,6 +336,8 @@ struct BwdPlan {
   bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
   bool tn;         // dW product straight from token-major dY columns and the uint8 codes (no transposed copies)
   bool tn_direct;  // ... with dY itself as the A operand (all channels selected)
+  bool dx8;        // dX product with the weight operand read from the int8 codes (no bf16 W_q^T copy)
+  int dx8_tile;
   int64_t kp;      // k rounded up to 8 (pitch of the compacted dY columns)
   GemmPlan plan_dx, plan_dw;
   size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, b_zero, total;
@@ -349,15 +357,23 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.kp = round_up(k, 8);
   p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
   p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false);
+  p.dx8 = false; p.dx8_tile = 0;
+  // Large products (the planner's 256 x 256 case) with a bf16 token-major dY read the weight operand straight
+  // from the int8 codes: same speed as the bf16 kernel on these shapes, and no transposed bf16 copy of W_q.
+  if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16 &&
+      (p.plan_dx.tile == 256 || g_opt_dx_kernel == EFQAT_DX_KERNEL_INT8)) {
+    p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
+    p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
+  }
   p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !p.tn) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
-  p.b_wqT = (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
+  p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
   p.b_colA = im2col ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
   p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
   p.b_xcT = (k > 0 && !p.tn) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
-  p.b_zero = p.tn ? 256 : 0; cv.take(p.b_zero);
+  p.b_zero = (p.tn || p.dx8) ? 256 : 0; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -389,7 +405,10 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   int rc;
 
   // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
-  {
+  if (p.dx8) {
+    hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(64), 0, st, (uint32_t*)zero_page);
+    EFQAT_LAUNCH_CHECK();
+  } else {
     TransposeExtra ex{};
     ex.z_in = c_in; ex.z_out = p.ldc;                 // one launch for all taps
     rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
@@ -431,7 +450,12 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     A = colA; lda = p.Kx;
   }
   GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
-  rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
+  if (p.dx8) {
+    if (((uintptr_t)io.w_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
+    rc = launch_gemm_dx8(dy_tok, c_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out, p.dx8_tile, epi, st);
+  } else {
+    rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
+  }
   if (rc) return rc;
   const int64_t n_part_dx = (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n;
   if (io.k == 0) {
@@ -534,6 +558,14 @@ static int check_common(const BwdIo& io, int64_t c_out, const void* ws) {
 }  // namespace efqat
 
 using namespace efqat;
+
+extern "C" int efqat_set_option(int option, int value) {
+  if (option != EFQAT_OPT_DX_KERNEL) return EFQAT_ERR_BAD_LAYOUT;
+  if (value != EFQAT_DX_KERNEL_AUTO && value != EFQAT_DX_KERNEL_BF16 && value != EFQAT_DX_KERNEL_INT8)
+    return EFQAT_ERR_BAD_LAYOUT;
+  g_opt_dx_kernel = value;
+  return EFQAT_OK;
+}
 
 extern "C" size_t efqat_linear_bwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out, int64_t k, int dy_dtype,
                                                    int dy_layout) {

@@ -122,6 +122,12 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
 int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* B, int64_t ldb, int64_t b_cols,
                    const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
                    float* out_partial, hipStream_t stream);
+// dX product with the weight operand read from the int8 codes (K-major [C_out][ldb]) and scaled by s_w[c] in
+// registers, fused dX epilogue.  dy: bf16 [M][lda]; N = C_in multiple of 16; tile 256 or 128.  The partial-sum
+// array of the epilogue needs ceil(M / tile) * ceil(N / tile) pairs.
+int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
+                    const void* zero_page, int64_t M, int64_t N, int64_t K, int tile, const GemmEpilogueDx& epi,
+                    hipStream_t stream);
 // event timing hooks shared by the product kernels (which: 0 dX, 1 dW, 2 forward)
 bool gemm_prof_begin(int which, hipStream_t st, int* slot);
 void gemm_prof_end(int which, hipStream_t st, int slot);

@@ -13,10 +13,11 @@
 
 #include <type_traits>
 
+#include "gemm_epilogue.hpp"
+
 namespace efqat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef int intx4_t __attribute__((ext_vector_type(4)));
 typedef int intx16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -26,22 +27,7 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 #endif
 constexpr int KALIGN = 64;  // split-K slices start on multiples of this many K elements
 
-enum { EPI_RAW = 0, EPI_DX = 1, EPI_FWD = 2 };
 
-struct GemmArgs {
-  const void* A; int64_t lda; const int32_t* a_rows;   // lda / ldb / K in elements (bf16 or int8)
-  const void* B; int64_t ldb;
-  int M, N, K;
-  int k_per_split;        // multiple of KALIGN
-  int tiles_m, tiles_n;
-  float* out;             // raw fp32 [split][M][N]
-  // fused dX epilogue
-  const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype;
-  const float* s_x; const float* z_x; void* dx; int dx_dtype; float* partial;
-  int epi_vec;            // 8-wide vector accesses allowed in the fused epilogue
-  // forward epilogue (int8 product): y = s_x * s_w[n] * (acc + (128 - round(z_x)) * wsum[n])
-  const float* s_w; const int32_t* wsum; void* y; int y_dtype;
-};
 
 // BM x BN output tile per 256-thread block; one LDS stage holds 128 bytes of K per tile row (64 bf16 or 128 int8),
 // S stages.
@@ -334,152 +320,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
         }
       }
   } else if constexpr (EPI == EPI_DX) {
-    // dX = dX_q where the activation was not clipped (straight-through), 0 elsewhere; block partial sums
-    // of dS_x = sum dX_q * (in range ? (code - Z) - x/S : code - Z) and dZ_x = sum dX_q * (in range ? 0 : -S).
-    // The accumulators go through LDS (32 rows of the wave's tile at a time) so that every lane then owns
-    // 8 consecutive columns of one row: 8-byte code loads, 16-byte x loads and 16-byte dX stores.
-    constexpr int PITCH = C::WN + 8;                   // floats; 4*PITCH = 32 (mod 64) banks
-    constexpr int CPR = C::WN / 8;                     // 8-column chunks per row
-    constexpr int RPP = 64 / CPR;                      // rows per pass of the wavefront (lanes beyond RPP*CPR idle)
-    constexpr int NPASS = (32 + RPP - 1) / RPP;
-    float* stage = reinterpret_cast<float*>(smem) + wave * 32 * PITCH;
-    const float s = g.s_x[0];
-    const float z = rintf(g.z_x[0]);
-    const float ninv_s = -1.0f / s;
-    const int64_t wpr = (g.N + 31) >> 5;
-    const int row_l0 = lane / CPR, ch = lane % CPR;
-    const int gcol = n0 + wn * C::WN + ch * 8;
-    float ps = 0.0f, pz = 0.0f;
-    const bool lane_on = row_l0 < RPP && gcol < g.N;
-    if (g.epi_vec) {
-      // Vector path (N % 8 == 0, aligned pointers): a lane's 8-column chunk is entirely inside the matrix.
-      // The global inputs of 32-row slab i+1 are fetched while slab i is computed, so their latency is hidden
-      // even with a single resident block per CU.
-      struct Inputs { uint2 cw; uint4 xa, xb; uint32_t mb; };
-      Inputs in[2][NPASS];
-      auto fetch = [&](int i, int b) {
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-          const int row_l = p * RPP + row_l0;
-          const int grow = m0 + wm * C::WM + i * 32 + row_l;
-          if (lane_on && row_l < 32 && grow < g.M) {
-            const int64_t e = (int64_t)grow * g.N + gcol;
-            in[b][p].mb = g.x_clip[(int64_t)grow * wpr + (gcol >> 5)] >> (gcol & 31);
-            in[b][p].cw = *reinterpret_cast<const uint2*>(g.x_codes + e);
-            if (g.x_dtype == EFQAT_F32) {
-              in[b][p].xa = *reinterpret_cast<const uint4*>((const float*)g.x + e);
-              in[b][p].xb = *reinterpret_cast<const uint4*>((const float*)g.x + e + 4);
-            } else {
-              in[b][p].xa = *reinterpret_cast<const uint4*>((const bf16_t*)g.x + e);
-            }
-          }
-        }
-      };
-      fetch(0, 0);
-#pragma unroll
-      for (int i = 0; i < C::TM; ++i) {
-        const int b = i & 1;
-        if (i > 0) __syncthreads();
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
-        __syncthreads();
-        if (i + 1 < C::TM) fetch(i + 1, b ^ 1);
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-          const int row_l = p * RPP + row_l0;
-          const int grow = m0 + wm * C::WM + i * 32 + row_l;
-          if (lane_on && row_l < 32 && grow < g.M) {
-            const float4 a0 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8);
-            const float4 a1 = *reinterpret_cast<const float4*>(stage + row_l * PITCH + ch * 8 + 4);
-            const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-            const int64_t e = (int64_t)grow * g.N + gcol;
-            const Inputs& q8 = in[b][p];
-            float xv[8];
-            if (g.x_dtype == EFQAT_F32) {
-              xv[0] = __uint_as_float(q8.xa.x); xv[1] = __uint_as_float(q8.xa.y);
-              xv[2] = __uint_as_float(q8.xa.z); xv[3] = __uint_as_float(q8.xa.w);
-              xv[4] = __uint_as_float(q8.xb.x); xv[5] = __uint_as_float(q8.xb.y);
-              xv[6] = __uint_as_float(q8.xb.z); xv[7] = __uint_as_float(q8.xb.w);
-            } else {
-              const uint32_t xw[4] = {q8.xa.x, q8.xa.y, q8.xa.z, q8.xa.w};
-#pragma unroll
-              for (int t = 0; t < 4; ++t) {
-                xv[2 * t] = __uint_as_float(xw[t] << 16);
-                xv[2 * t + 1] = __uint_as_float(xw[t] & 0xFFFF0000u);
-              }
-            }
-            float o[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-              const uint32_t byte = ((t < 4 ? q8.cw.x : q8.cw.y) >> (8 * (t & 3))) & 0xFFu;
-              const float q = (float)byte - z;
-              const bool inr = (q8.mb >> t) & 1u;
-              const float gs = inr ? fmaf(xv[t], ninv_s, q) : q;
-              ps = fmaf(a[t], gs, ps);
-              o[t] = inr ? a[t] : 0.0f;
-              pz += a[t] - o[t];
-            }
-            if (g.dx_dtype == EFQAT_F32) {
-              *reinterpret_cast<float4*>((float*)g.dx + e) = make_float4(o[0], o[1], o[2], o[3]);
-              *reinterpret_cast<float4*>((float*)g.dx + e + 4) = make_float4(o[4], o[5], o[6], o[7]);
-            } else {
-              *reinterpret_cast<uint4*>((bf16_t*)g.dx + e) =
-                  make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
-                             pack_bf16x2(o[6], o[7]));
-            }
-          }
-        }
-      }
-    } else {
-      // Element-wise path for ragged widths / unaligned pointers.
-#pragma unroll
-      for (int i = 0; i < C::TM; ++i) {
-        if (i > 0) __syncthreads();
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-          const int row_l = p * RPP + row_l0;
-          const int grow = m0 + wm * C::WM + i * 32 + row_l;
-          if (lane_on && row_l < 32 && grow < g.M) {
-            const int64_t e = (int64_t)grow * g.N + gcol;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-              if (gcol + t < g.N) {
-                const float av = stage[row_l * PITCH + ch * 8 + t];
-                const float q = (float)g.x_codes[e + t] - z;
-                const float xv = g.x_dtype == EFQAT_F32 ? ((const float*)g.x)[e + t]
-                                                        : bf16_to_f32(((const bf16_t*)g.x)[e + t]);
-                const bool inr = (g.x_clip[(int64_t)grow * wpr + ((gcol + t) >> 5)] >> ((gcol + t) & 31)) & 1u;
-                const float gs = inr ? fmaf(xv, ninv_s, q) : q;
-                ps = fmaf(av, gs, ps);
-                const float ov = inr ? av : 0.0f;
-                pz += av - ov;
-                if (g.dx_dtype == EFQAT_F32) ((float*)g.dx)[e + t] = ov;
-                else ((bf16_t*)g.dx)[e + t] = f32_to_bf16(ov);
-              }
-            }
-          }
-        }
-      }
-    }
-    ps = wave_sum(ps);
-    pz = wave_sum(pz);
-    __syncthreads();                                   // staging area is dead: reuse for the block sum
-    float* red = reinterpret_cast<float*>(smem);
-    if (lane == 0) { red[2 * wave] = ps; red[2 * wave + 1] = pz; }
-    __syncthreads();
-    if (tid == 0) {
-      g.partial[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
-      g.partial[2 * blockIdx.x + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
-    }
+    epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
   } else {
     // Forward epilogue: the int32 sums are over (code - 128) * w, so
     //   y[m][n] = S_x * S_w[n] * (acc + (128 - round(Z_x)) * sum_k w[n][k]).

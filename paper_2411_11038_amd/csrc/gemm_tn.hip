@@ -16,10 +16,11 @@
 
 #include <type_traits>
 
+#include "gemm_epilogue.hpp"
+
 namespace efqat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef short shortx4_t __attribute__((ext_vector_type(4)));
 typedef int intx2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -351,6 +352,287 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------------
+// Input-gradient product with the weight operand taken straight from the int8 codes (Eq. 5 left):
+//
+//   dX_q[t][i] = sum_c dY[t][c] * (S_w[c] * code[c][i]),   A = dY bf16 [T][lda] (K = c contiguous),
+//                                                          B = weight codes int8 [C_out][ldb] (K = c is the row)
+//
+// A tiles are staged and read like any K-contiguous operand (128-byte rows, 16-byte fragment reads); B tiles are
+// copied as they lie and read with ds_read_b64_tr_b8, then turned into bf16(S_w[c] * code) in registers with the
+// 64 scales of the stage, which travel through LDS as well.  bf16(S_w * code) is the same rounding a materialised
+// bf16 copy of W_q would apply, so results do not depend on which kernel runs.  Compared with that copy the
+// weight operand costs half the bytes in L2, L1 and LDS (a 256 x 256 stage is 48 KB instead of 64 KB), and the
+// transposed bf16 matrix is never written.  Same wavefront grid (1 x 4), pipeline and load discipline as k_gemm_tn;
+// the epilogue is the fused straight-through / dS_x / dZ_x epilogue shared with the K-contiguous kernel.
+template <int T>
+struct Dx8Cfg {
+  static constexpr int BM = T, BN = T;
+  static constexpr int WGM = 1, WGN = 4;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int RB = BN;                              // bytes per LDS row of B (one channel c)
+  static constexpr int CB = RB / 16;
+  static constexpr int A_G = BM / 8 / 4, B_G = 64 * RB / 1024 / 4;   // 1-KiB loads per wave and stage
+  static constexpr int LDS_A = BM * 128, LDS_B = 64 * RB, LDS_S = 4 * 256;   // scales: one copy per wavefront
+  static constexpr int LDS_STAGE = LDS_A + LDS_B + LDS_S;
+  static constexpr int LDS_LOOP = 2 * LDS_STAGE;
+  static constexpr int LDS_EPI = 4 * 32 * (WN + 8) * 4;
+  static constexpr int LDS_BYTES = LDS_LOOP > LDS_EPI ? LDS_LOOP : LDS_EPI;
+  static constexpr int KSH = RB == 256 ? 0 : 1;
+  __device__ static __forceinline__ int swz_a(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+  __device__ static __forceinline__ int swz_b(int c, int k) { return c ^ (2 * ((k >> KSH) & (CB / 2 - 1))); }
+};
+
+// one wave-wide global -> LDS copy of 4 bytes per lane (the 64 scales of a stage)
+__device__ __forceinline__ void dma4(const char* src, char* lds_dst) {
+  const uint32_t m = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
+  asm volatile("s_mov_b32 m0, %0" ::"s"(m) : "m0");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src));
+}
+
+struct GemmDx8Args {
+  GemmArgs g;              // A = dY, B = weight codes, M = T, N = C_in, K = C_out, fused dX epilogue fields
+  int b_cols;              // readable width of B (multiple of 16)
+  const void* zero_page;   // >= 256 zero bytes
+};
+
+template <int T>
+__global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  using C = Dx8Cfg<T>;
+  const GemmArgs& g = ga.g;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = 0, wn = wave;
+
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int GM = 8;
+  const int per_group = GM * g.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GM;
+  const int gsize = (g.tiles_m - first_m) < GM ? (g.tiles_m - first_m) : GM;
+  const int tm = first_m + (pid % per_group) % gsize;
+  const int tn = (pid % per_group) / gsize;
+  const int m0 = tm * C::BM, n0 = tn * C::BN;
+
+  const int K = g.K;
+  const int nk = (K + 63) / 64;
+  const int nfull = K / 64;
+  const char* zero = (const char*)ga.zero_page;
+
+  // ---- global -> LDS copies with running pointers (one 64-bit add per copy; slots outside the operands rest on
+  // the zero page with stride 0).  A: slot j covers tile rows (wave + 4 j) * 8 .. + 7, lane l lands in row l / 8,
+  // physical chunk l % 8.  B: slot j covers channel rows (wave + 4 j) * RPIB .. of the stage.
+  constexpr int RPIB = 1024 / C::RB;
+  const int a_lrow = lane >> 3;
+  const int a_lch = (lane & 7) ^ (((wave * 8 + a_lrow) >> 1) & 7);   // logical chunk fetched by this lane (same for all j)
+  const int b_r0 = lane / C::CB;
+  const char* a_ptr[C::A_G];
+  const char* b_ptr[C::B_G];
+  uint32_t b_st[C::B_G];
+#pragma unroll
+  for (int j = 0; j < C::A_G; ++j) {
+    int gm = m0 + (wave + 4 * j) * 8 + a_lrow;
+    gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row (outputs discarded)
+    a_ptr[j] = (const char*)g.A + ((int64_t)gm * g.lda) * 2 + a_lch * 16;
+  }
+#pragma unroll
+  for (int j = 0; j < C::B_G; ++j) {
+    const int kr = (wave + 4 * j) * RPIB + b_r0;
+    const int col = n0 + C::swz_b(lane % C::CB, kr) * 16;
+    const bool on = col < ga.b_cols;
+    b_ptr[j] = on ? (const char*)g.B + (int64_t)kr * g.ldb + col : zero;
+    b_st[j] = on ? (uint32_t)(g.ldb * 64) : 0u;
+  }
+  const char* s_ptr = (const char*)g.s_w + lane * 4;   // the scale of channel kt * 64 + lane
+  constexpr int LPS = C::A_G + C::B_G + 1;
+  using Checked = std::integral_constant<bool, true>;
+  using Unchecked = std::integral_constant<bool, false>;
+  auto issue_range = [&](auto checked, int kt, int buf, int t0, int t1) {
+    char* sa = smem + buf * C::LDS_STAGE;
+    char* sb = sa + C::LDS_A;
+    char* ss = sb + C::LDS_B;
+    const int kb = kt * 64;
+#pragma unroll
+    for (int t = t0; t < t1; ++t) {
+      if (t < C::A_G) {
+        const char* src = a_ptr[t];
+        if constexpr (decltype(checked)::value) {
+          if (kb + a_lch * 8 >= K) src = zero;          // K is a multiple of 8: a chunk is all in or all out
+        }
+        dma16(src, sa + (wave + 4 * t) * 1024);
+        a_ptr[t] += 128;
+      } else if (t < C::A_G + C::B_G) {
+        const int u = t - C::A_G;
+        const char* src = b_ptr[u];
+        if constexpr (decltype(checked)::value) {
+          if (kb + (wave + 4 * u) * RPIB + b_r0 >= K) src = zero;
+        }
+        dma16(src, sb + (wave + 4 * u) * 1024);
+        b_ptr[u] += b_st[u];
+      } else {
+        // every wavefront fetches its own copy of the stage's 64 scales: no branch in the loop body
+        const char* src = s_ptr;
+        if constexpr (decltype(checked)::value) {
+          if (kb + lane >= K) src = zero;
+        }
+        dma4(src, ss + wave * 256);
+        s_ptr += 256;
+      }
+    }
+  };
+
+  floatx16_t acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // ---- fragment reads.  A (rows = tokens, 16 bytes = 8 channels): lane owns row 32 i + lane % 32, channels
+  // 16 sub + 8 (lane / 32) + 0..7.  B (transpose read): lane addresses 8 columns of channel 16 sub + 8 h + s / 2 and
+  // ends up with column 32 j + lane % 32, channels 16 sub + 8 h + 0..7, h = lane / 32.
+  const int fr = lane & 31, fh = lane >> 5;
+  const int s16 = lane & 15, q = lane >> 4;
+  const int mb = 16 * (q & 1);
+  int b_base[2][C::TN];
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int k = 8 * fh + (s16 >> 1);
+    const int nbyte = wn * C::WN + 32 * j + mb + 8 * (s16 & 1);
+    b_base[0][j] = C::LDS_A + k * C::RB + (C::swz_b(nbyte >> 4, k) << 4) + (nbyte & 15);
+    b_base[1][j] = b_base[0][j] + C::LDS_STAGE;
+  }
+  typedef int intx4_t __attribute__((ext_vector_type(4)));
+  intx4_t af[2][C::TM];
+  intx2_t braw[2][C::TN];
+  float4 sc[2][2];
+  bf16x8_t bfr[2][C::TN];
+  auto load_frags = [&](auto bufc, int sub, int rb) {
+    constexpr int buf = decltype(bufc)::value;
+    const char* st = smem + buf * C::LDS_STAGE;
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+      braw[rb][j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][j] + sub * 16 * C::RB));
+    const float4* sp = reinterpret_cast<const float4*>(st + C::LDS_A + C::LDS_B + wave * 256 + (16 * sub + 8 * fh) * 4);
+    sc[rb][0] = sp[0];
+    sc[rb][1] = sp[1];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+      af[rb][i] = *reinterpret_cast<const intx4_t*>(st + C::swz_a(32 * i + fr, 2 * sub + fh));
+  };
+  // 8 weight codes of one column -> bf16(S_w[c] * code): code + 128 is an unsigned byte, so
+  // S_w * code = fma(byte, S_w, -128 S_w), rounded once like the product itself
+  auto convert = [&](int rb) {
+    const float sv[8] = {sc[rb][0].x, sc[rb][0].y, sc[rb][0].z, sc[rb][0].w,
+                         sc[rb][1].x, sc[rb][1].y, sc[rb][1].z, sc[rb][1].w};
+    float mv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) mv[t] = -128.0f * sv[t];
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+      const uint32_t w0 = (uint32_t)braw[rb][j][0] ^ 0x80808080u, w1 = (uint32_t)braw[rb][j][1] ^ 0x80808080u;
+      float f[8];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        f[t] = fmaf((float)((w0 >> (8 * t)) & 0xFFu), sv[t], mv[t]);
+        f[4 + t] = fmaf((float)((w1 >> (8 * t)) & 0xFFu), sv[4 + t], mv[4 + t]);
+      }
+      uint32_t p[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) p[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
+      const uint4 pk = make_uint4(p[0], p[1], p[2], p[3]);
+      bfr[rb][j] = __builtin_bit_cast(bf16x8_t, pk);
+    }
+  };
+  auto mfma_all = [&](int rb) {
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[rb][i]), bfr[rb][j],
+                                                            acc[i][j], 0, 0, 0);
+  };
+
+  constexpr int P0 = (LPS + 2) / 3, P1 = (LPS - P0 + 1) / 2, P2 = LPS - P0 - P1;
+  auto stage_sync = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // ---- main loop: the schedule of k_gemm_tn (two LDS stages, four sub-steps, loads of the next stage in thirds)
+  constexpr int MF = C::TM * C::TN, NRD = C::TM + C::TN + 2, NCV = 22 * C::TN + 8;
+  auto stage = [&](auto bufc, auto steadyc, int kt) {
+    constexpr int cur = decltype(bufc)::value;
+    constexpr bool ST = decltype(steadyc)::value;
+    using Other = std::integral_constant<int, cur ^ 1>;
+    bool more1 = true;
+    if constexpr (!ST) {
+      more1 = kt + 1 < nk;
+      if (kt + 1 < nfull) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, LPS);
+      else if (more1) issue_range(Checked{}, kt + 1, cur ^ 1, 0, LPS);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 1, 1);
+    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, P0 + P1);
+    mfma_all(0);
+    convert(1);
+    if constexpr (ST) TnSched<MF, NRD, P1, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 2, 0);
+    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0 + P1, LPS);
+    mfma_all(1);
+    convert(0);
+    if constexpr (ST) TnSched<MF, NRD, P2, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(bufc, 3, 1);
+    mfma_all(0);
+    convert(1);
+    if constexpr (ST) TnSched<MF, NRD, 0, NCV, 0>::run();
+    stage_sync();
+    if (ST || more1) load_frags(Other{}, 0, 0);
+    if (ST || kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
+    mfma_all(1);
+    if (ST || more1) convert(0);
+    if constexpr (ST) TnSched<MF, NRD, P0, NCV, 0>::run();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
+  using Steady = std::integral_constant<bool, true>;
+  using Drain = std::integral_constant<bool, false>;
+
+  if (nk > 0) issue_range(Checked{}, 0, 0, 0, LPS);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (1 < nfull) issue_range(Unchecked{}, 1, 1, 0, P0);
+  if (nk > 0) {
+    load_frags(B0{}, 0, 0);
+    convert(0);
+  }
+  int kt = 0;
+  for (; kt + 3 < nfull; kt += 2) {
+    stage(B0{}, Steady{}, kt);
+    stage(B1{}, Steady{}, kt + 1);
+  }
+  for (; kt < nk; kt += 2) {
+    stage(B0{}, Drain{}, kt);
+    if (kt + 1 < nk) stage(B1{}, Drain{}, kt + 1);
+  }
+  __syncthreads();
+
+  epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
+#endif
+}
+
 template <int T>
 static int launch_tn_cfg(const GemmTnArgs& a, int split_k, hipStream_t st) {
   using C = TnCfg<T>;
@@ -387,6 +669,50 @@ int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* 
   switch (plan.tile) {
     case 256: return launch_tn_cfg<256>(a, plan.split_k, stream);
     case 128: return launch_tn_cfg<128>(a, plan.split_k, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
+  }
+}
+
+
+template <int T>
+static int launch_dx8_cfg(const GemmDx8Args& a, hipStream_t st) {
+  using C = Dx8Cfg<T>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
+        hipSuccess)
+      return EFQAT_ERR_HIP;
+    attr_done = true;
+  }
+  dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n));
+  int slot = 0;
+  const bool timed = gemm_prof_begin(0, st, &slot);
+  hipLaunchKernelGGL((k_gemm_dx8<T>), grid, dim3(256), C::LDS_BYTES, st, a);
+  if (timed) gemm_prof_end(0, st, slot);
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
+                    const void* zero_page, int64_t M, int64_t N, int64_t K, int tile, const GemmEpilogueDx& epi,
+                    hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 8) || (lda % 8) || (ldb % 16) || (N % 16)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldb >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)dy % 16) || ((uintptr_t)w_codes % 16) || ((uintptr_t)s_w % 4) || ((uintptr_t)zero_page % 256))
+    return EFQAT_ERR_ALIGNMENT;
+  GemmDx8Args a{};
+  a.g.A = dy; a.g.lda = lda; a.g.B = w_codes; a.g.ldb = ldb;
+  a.g.M = (int)M; a.g.N = (int)N; a.g.K = (int)K;
+  a.g.s_w = s_w;
+  a.g.x_codes = epi.x_codes; a.g.x_clip = epi.x_clip; a.g.x = epi.x; a.g.x_dtype = epi.x_dtype;
+  a.g.s_x = epi.s_x; a.g.z_x = epi.z_x; a.g.dx = epi.dx; a.g.dx_dtype = epi.dx_dtype; a.g.partial = epi.partial;
+  a.g.epi_vec = gemm_epilogue_vec_ok(epi, N) ? 1 : 0;
+  a.g.tiles_m = (int)ceil_div(M, tile); a.g.tiles_n = (int)ceil_div(N, tile);
+  a.b_cols = (int)N;
+  a.zero_page = zero_page;
+  switch (tile) {
+    case 256: return launch_dx8_cfg<256>(a, stream);
+    case 128: return launch_dx8_cfg<128>(a, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }

@@ -279,6 +279,39 @@ def test_linear_bwd_matches_oracle(case):
     _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
 
 
+# dX product with the weight operand read from the int8 codes (bf16 token-major dY, C_out % 8 == 0, C_in % 16 == 0):
+# forced through the option hook so that both tile sizes meet ragged edges in every dimension
+DX8_CASES = [
+    # T, c_in, c_out, a_bits, w_bits, shrink, (num, den), scatter
+    (300, 208, 136, 8, 4, 0.7, (1, 4), False),      # 128 tile; K tail 136 % 64 = 8, N tail, M tail
+    (517, 400, 264, 8, 8, 0.8, (1, 2), True),
+    (70, 16, 24, 8, 8, 1.0, (1, 3), False),         # one partial stage, one partial tile
+    (129, 144, 64, 8, 8, 0.7, (0, 1), False),       # exactly one full stage, r = 0
+    (260, 128, 448, 8, 8, 0.8, (1, 20), False),     # seven full stages (pipelined loop + drain), full-width tile
+    (2048, 512, 640, 8, 8, 0.8, (1, 1), False),     # 256 tile, everything a multiple of the tile
+    (1100, 528, 200, 8, 4, 0.7, (1, 4), False),     # 256 tile with tails in M, N and K
+    (1030, 768, 1096, 8, 8, 0.8, (1, 20), False),   # 256 tile, 17 full stages + tail
+]
+
+
+@pytest.mark.parametrize("case", DX8_CASES, ids=lambda c: "T%d_%dx%d_w%d_r%d-%d" % (c[0], c[1], c[2], c[4],
+                                                                                    c[6][0], c[6][1]))
+def test_linear_bwd_int8_weight_operand(case):
+    T, c_in, c_out, a_bits, w_bits, shrink, (num, den), scatter = case
+    X, W, dY = synth.linear_layer(3000 + T + c_in, T, c_in, c_out, act_dtype="bf16")
+    try:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_INT8)
+        out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter)
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16)
+        out2, *_ = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter)
+    finally:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
+    _check_bwd(out, ref, idx, idx_ref, X, W, qp, "bf16", scatter, True, W.shape)
+    # both kernels round S_w * code to bf16 once and accumulate in fp32; only the fp32 summation order differs, so
+    # the bf16 outputs agree to an ulp or two of the largest element
+    assert_max_err(host(out["dx"]), host(out2["dx"]), 8e-3, "dX int8-operand vs bf16-operand kernel")
+
+
 def test_linear_bwd_dx_independent_of_fraction_and_fp32_dx():
     X, W, dY = synth.linear_layer(77, 260, 136, 200, act_dtype="bf16")
     outs = []
