@@ -70,34 +70,6 @@ __device__ __forceinline__ void dma16(const char* src, char* lds_dst) {
   asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src));
 }
 
-// Scheduling hint for one sub-step: one group per MFMA.  The LDS transpose reads of the next sub-step go with the
-// first half of the MFMAs, the byte -> bf16 conversions of what they return with the second half, and each of the
-// first NL groups carries one global->LDS load with its pointer increment.  Group sizes must be compile-time
-// constants, hence the recursion.
-template <int MF, int NRD, int NL, int NCV, int Q>
-struct TnSched {
-  static __device__ __forceinline__ void run() {
-    if constexpr (Q < MF) {
-      constexpr int H = MF / 2 > 0 ? MF / 2 : 1;
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if constexpr (Q < H) {
-        constexpr int nds = ((Q + 1) * NRD) / H - (Q * NRD) / H;
-        if constexpr (nds > 0) __builtin_amdgcn_sched_group_barrier(0x100, nds, 0);
-      }
-      if constexpr (Q < NL) {
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-      }
-      if constexpr (Q >= MF - H) {
-        constexpr int q2 = Q - (MF - H);
-        constexpr int ncv = ((q2 + 1) * NCV) / H - (q2 * NCV) / H;
-        if constexpr (ncv > 0) __builtin_amdgcn_sched_group_barrier(0x002, ncv, 0);
-      }
-      TnSched<MF, NRD, NL, NCV, Q + 1>::run();
-    }
-  }
-};
-
 template <int T>
 __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -220,47 +192,50 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
   const float z = rintf(g.z_x[0]);
   shortx4_t af[2][C::TM][2];
   intx2_t braw[2][C::TN];
-  bf16x8_t bfr[2][C::TN];
-  auto load_frags = [&](auto bufc, int sub, int rb) {
+  uint32_t bw[2][C::TN][4];                         // converted B fragments: 4 words of two bf16 each
+  // LDS read number r of a sub-step: the B codes, then the two halves of every A fragment
+  constexpr int NRD = C::TN + 2 * C::TM;
+  auto lds_read = [&](auto bufc, int sub, int rb, int r) {
     constexpr int buf = decltype(bufc)::value;
-#pragma unroll
-    for (int j = 0; j < C::TN; ++j)
-      braw[rb][j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][j] + sub * 16 * C::RB));
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-      for (int r = 0; r < 2; ++r)
-        af[rb][i][r] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4_t*)(
-            smem + a_base[buf][i & 3] + (i >> 2) * 256 + r * 4 * C::RA + sub * 16 * C::RA));
+    if (r < C::TN) {
+      braw[rb][r] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][r] + sub * 16 * C::RB));
+    } else {
+      const int i = (r - C::TN) >> 1, hh = (r - C::TN) & 1;
+      af[rb][i][hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4_t*)(
+          smem + a_base[buf][i & 3] + (i >> 2) * 256 + hh * 4 * C::RA + sub * 16 * C::RA));
+    }
   };
-  // 8 activation codes -> (code - z) as bf16: integers of magnitude <= 255 are exact
+  auto load_frags = [&](auto bufc, int sub, int rb) {
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) lds_read(bufc, sub, rb, r);
+  };
+  // Activation codes -> (code - z) as bf16: integers of magnitude <= 255 are exact.  Piece p of fragment j makes
+  // elements 2p and 2p + 1 (5 VALU operations).
+  constexpr int NPIECE = 4 * C::TN;
+  auto conv_piece = [&](int rb, int piece) {
+    const int j = piece >> 2, pp = piece & 3;
+    const uint32_t w = (uint32_t)braw[rb][j][pp >> 1];
+    const int sh = 16 * (pp & 1);
+    const float f0 = (float)((w >> sh) & 0xFFu) - z;
+    const float f1 = (float)((w >> (sh + 8)) & 0xFFu) - z;
+    bw[rb][j][pp] = pack_bf16x2(f0, f1);
+  };
   auto convert = [&](int rb) {
 #pragma unroll
-    for (int j = 0; j < C::TN; ++j) {
-      const uint32_t w0 = (uint32_t)braw[rb][j][0], w1 = (uint32_t)braw[rb][j][1];
-      float f[8];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        f[t] = (float)((w0 >> (8 * t)) & 0xFFu) - z;
-        f[4 + t] = (float)((w1 >> (8 * t)) & 0xFFu) - z;
-      }
-      uint32_t p[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) p[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
-      const uint4 pk = make_uint4(p[0], p[1], p[2], p[3]);
-      bfr[rb][j] = __builtin_bit_cast(bf16x8_t, pk);
-    }
+    for (int piece = 0; piece < NPIECE; ++piece) conv_piece(rb, piece);
+  };
+  auto mfma_one = [&](int rb, int i, int j) {
+    struct { shortx4_t lo, hi; } a2 = {af[rb][i][0], af[rb][i][1]};
+    const uint4 pk = make_uint4(bw[rb][j][0], bw[rb][j][1], bw[rb][j][2], bw[rb][j][3]);
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a2),
+                                                        __builtin_bit_cast(bf16x8_t, pk), acc[i][j], 0, 0, 0);
   };
   auto mfma_all = [&](int rb) {
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i) {
-      struct { shortx4_t lo, hi; } a2 = {af[rb][i][0], af[rb][i][1]};
-      const bf16x8_t a8 = __builtin_bit_cast(bf16x8_t, a2);
+    for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, bfr[rb][j], acc[i][j], 0, 0, 0);
-    }
+      for (int j = 0; j < C::TN; ++j) mfma_one(rb, i, j);
   };
 
   constexpr int P0 = (LPS + 2) / 3, P1 = (LPS - P0 + 1) / 2, P2 = LPS - P0 - P1;
@@ -276,41 +251,64 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
   // 2nd and 3rd thirds of the loads of stage kt+1; after sub-step 2 everybody synchronises (stage kt+1 complete,
   // buffer kt free); sub-step 3 reads the first fragments of stage kt+1 and issues the first third of stage kt+2.
   // Invariant: when stage kt starts, the first third of stage kt+1 is in flight iff kt+1 < nfull.
-  constexpr int MF = C::TM * C::TN, NRD = 2 * C::TM + C::TN, NCV = 20 * C::TN;
+  //
+  // A steady-state sub-step has its instruction order pinned, one group per MFMA (the compiler's own interleaving
+  // left the conversions of some sub-steps in one clump behind the last MFMA): the MFMAs of fragment set rb; in the
+  // first half the LDS reads of the next sub-step (set rb ^ 1), in the second half the conversion of what they
+  // returned; the first t1 - t0 groups also issue one global->LDS copy each (stage kt_i into buffer buf_i).
+  constexpr int MF = C::TM * C::TN, HF = MF / 2;
+  static_assert(HF >= 1 && P0 <= MF && P1 <= MF && P2 <= MF, "copies per sub-step must not exceed its MFMAs");
+  auto substep = [&](auto bufn, int sub_next, int rb, int kt_i, int buf_i, int t0, int t1) {
+#pragma unroll
+    for (int qq = 0; qq < MF; ++qq) {
+      mfma_one(rb, qq / C::TN, qq % C::TN);
+      if (qq < HF) {
+#pragma unroll
+        for (int r = (qq * NRD) / HF; r < ((qq + 1) * NRD) / HF; ++r) lds_read(bufn, sub_next, rb ^ 1, r);
+      }
+      if (qq < t1 - t0) issue_range(Unchecked{}, kt_i, buf_i, t0 + qq, t0 + qq + 1);
+      if (qq >= MF - HF) {
+        const int q2 = qq - (MF - HF);
+#pragma unroll
+        for (int piece = (q2 * NPIECE) / HF; piece < ((q2 + 1) * NPIECE) / HF; ++piece) conv_piece(rb ^ 1, piece);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   auto stage = [&](auto bufc, auto steadyc, int kt) {
     constexpr int cur = decltype(bufc)::value;
     constexpr bool ST = decltype(steadyc)::value;
     using Other = std::integral_constant<int, cur ^ 1>;
-    bool more1 = true;
-    if constexpr (!ST) {
-      more1 = kt + 1 < nk;
+    if constexpr (ST) {
+      __builtin_amdgcn_sched_barrier(0);
+      substep(bufc, 1, 0, kt + 1, cur ^ 1, P0, P0 + P1);
+      substep(bufc, 2, 1, kt + 1, cur ^ 1, P0 + P1, LPS);
+      substep(bufc, 3, 0, 0, 0, 0, 0);
+      stage_sync();
+      substep(Other{}, 0, 1, kt + 2, cur, 0, P0);
+    } else {
+      const bool more1 = kt + 1 < nk;
       if (kt + 1 < nfull) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, LPS);
       else if (more1) issue_range(Checked{}, kt + 1, cur ^ 1, 0, LPS);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 1, 1);
+      mfma_all(0);
+      convert(1);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 2, 0);
+      mfma_all(1);
+      convert(0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 3, 1);
+      mfma_all(0);
+      convert(1);
+      stage_sync();
+      if (more1) load_frags(Other{}, 0, 0);
+      if (kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
+      mfma_all(1);
+      if (more1) convert(0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 1, 1);
-    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, P0 + P1);
-    mfma_all(0);
-    convert(1);
-    if constexpr (ST) TnSched<MF, NRD, P1, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 2, 0);
-    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0 + P1, LPS);
-    mfma_all(1);
-    convert(0);
-    if constexpr (ST) TnSched<MF, NRD, P2, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 3, 1);
-    mfma_all(0);
-    convert(1);
-    if constexpr (ST) TnSched<MF, NRD, 0, NCV, 0>::run();
-    stage_sync();
-    if (ST || more1) load_frags(Other{}, 0, 0);
-    if (ST || kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
-    mfma_all(1);
-    if (ST || more1) convert(0);
-    if constexpr (ST) TnSched<MF, NRD, P0, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
   };
   using B0 = std::integral_constant<int, 0>;
   using B1 = std::integral_constant<int, 1>;
@@ -511,53 +509,60 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   typedef int intx4_t __attribute__((ext_vector_type(4)));
   intx4_t af[2][C::TM];
   intx2_t braw[2][C::TN];
-  float4 sc[2][2];
-  bf16x8_t bfr[2][C::TN];
-  auto load_frags = [&](auto bufc, int sub, int rb) {
+  float scf[2][8], mvf[2][8];                       // the 8 scales of a lane's K positions, and -128 * scale
+  uint32_t bw[2][C::TN][4];                         // converted B fragments: 4 words of two bf16 each
+  // LDS read number r of a sub-step: B codes, the scales, then the A fragments
+  constexpr int NRD = C::TN + 2 + C::TM;
+  auto lds_read = [&](auto bufc, int sub, int rb, int r) {
     constexpr int buf = decltype(bufc)::value;
     const char* st = smem + buf * C::LDS_STAGE;
-#pragma unroll
-    for (int j = 0; j < C::TN; ++j)
-      braw[rb][j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][j] + sub * 16 * C::RB));
-    const float4* sp = reinterpret_cast<const float4*>(st + C::LDS_A + C::LDS_B + wave * 256 + (16 * sub + 8 * fh) * 4);
-    sc[rb][0] = sp[0];
-    sc[rb][1] = sp[1];
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
+    if (r < C::TN) {
+      braw[rb][r] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+          (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][r] + sub * 16 * C::RB));
+    } else if (r < C::TN + 2) {
+      const int hlf = r - C::TN;
+      const float4 v = *reinterpret_cast<const float4*>(st + C::LDS_A + C::LDS_B + wave * 256 +
+                                                        (16 * sub + 8 * fh + 4 * hlf) * 4);
+      scf[rb][4 * hlf] = v.x; scf[rb][4 * hlf + 1] = v.y; scf[rb][4 * hlf + 2] = v.z; scf[rb][4 * hlf + 3] = v.w;
+    } else {
+      const int i = r - C::TN - 2;
       af[rb][i] = *reinterpret_cast<const intx4_t*>(st + C::swz_a(32 * i + fr, 2 * sub + fh));
-  };
-  // 8 weight codes of one column -> bf16(S_w[c] * code): code + 128 is an unsigned byte, so
-  // S_w * code = fma(byte, S_w, -128 S_w), rounded once like the product itself
-  auto convert = [&](int rb) {
-    const float sv[8] = {sc[rb][0].x, sc[rb][0].y, sc[rb][0].z, sc[rb][0].w,
-                         sc[rb][1].x, sc[rb][1].y, sc[rb][1].z, sc[rb][1].w};
-    float mv[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) mv[t] = -128.0f * sv[t];
-#pragma unroll
-    for (int j = 0; j < C::TN; ++j) {
-      const uint32_t w0 = (uint32_t)braw[rb][j][0] ^ 0x80808080u, w1 = (uint32_t)braw[rb][j][1] ^ 0x80808080u;
-      float f[8];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        f[t] = fmaf((float)((w0 >> (8 * t)) & 0xFFu), sv[t], mv[t]);
-        f[4 + t] = fmaf((float)((w1 >> (8 * t)) & 0xFFu), sv[4 + t], mv[4 + t]);
-      }
-      uint32_t p[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) p[t] = pack_bf16x2(f[2 * t], f[2 * t + 1]);
-      const uint4 pk = make_uint4(p[0], p[1], p[2], p[3]);
-      bfr[rb][j] = __builtin_bit_cast(bf16x8_t, pk);
     }
+  };
+  auto load_frags = [&](auto bufc, int sub, int rb) {
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) lds_read(bufc, sub, rb, r);
+  };
+  // Weight codes -> bf16(S_w[c] * code): code + 128 is an unsigned byte, so S_w * code = fma(byte, S_w, -128 S_w),
+  // rounded once like the product itself.  Piece p of fragment j makes elements 2p and 2p + 1 (5 VALU operations).
+  constexpr int NPIECE = 4 * C::TN;
+  auto conv_offsets = [&](int rb) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) mvf[rb][t] = -128.0f * scf[rb][t];
+  };
+  auto conv_piece = [&](int rb, int piece) {
+    const int j = piece >> 2, pp = piece & 3;
+    const uint32_t w = (uint32_t)braw[rb][j][pp >> 1] ^ 0x80808080u;
+    const int sh = 16 * (pp & 1);
+    const float f0 = fmaf((float)((w >> sh) & 0xFFu), scf[rb][2 * pp], mvf[rb][2 * pp]);
+    const float f1 = fmaf((float)((w >> (sh + 8)) & 0xFFu), scf[rb][2 * pp + 1], mvf[rb][2 * pp + 1]);
+    bw[rb][j][pp] = pack_bf16x2(f0, f1);
+  };
+  auto convert = [&](int rb) {
+    conv_offsets(rb);
+#pragma unroll
+    for (int piece = 0; piece < NPIECE; ++piece) conv_piece(rb, piece);
+  };
+  auto mfma_one = [&](int rb, int i, int j) {
+    const uint4 pk = make_uint4(bw[rb][j][0], bw[rb][j][1], bw[rb][j][2], bw[rb][j][3]);
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[rb][i]),
+                                                        __builtin_bit_cast(bf16x8_t, pk), acc[i][j], 0, 0, 0);
   };
   auto mfma_all = [&](int rb) {
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-      for (int j = 0; j < C::TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[rb][i]), bfr[rb][j],
-                                                            acc[i][j], 0, 0, 0);
+      for (int j = 0; j < C::TN; ++j) mfma_one(rb, i, j);
   };
 
   constexpr int P0 = (LPS + 2) / 3, P1 = (LPS - P0 + 1) / 2, P2 = LPS - P0 - P1;
@@ -568,42 +573,65 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
     __builtin_amdgcn_sched_barrier(0);
   };
 
+  // One steady-state sub-step with its instruction order pinned, one group per MFMA: the MFMAs of fragment set rb;
+  // in the first half the LDS reads of the next sub-step (set rb ^ 1), in the second half the conversion of what
+  // they returned; the first t1 - t0 groups also issue one global->LDS copy each (stage kt_i into buffer buf_i).
+  constexpr int MF = C::TM * C::TN, HF = MF / 2;
+  static_assert(HF >= 1 && P0 <= MF && P1 <= MF && P2 <= MF, "copies per sub-step must not exceed its MFMAs");
+  auto substep = [&](auto bufn, int sub_next, int rb, int kt_i, int buf_i, int t0, int t1) {
+#pragma unroll
+    for (int qq = 0; qq < MF; ++qq) {
+      mfma_one(rb, qq / C::TN, qq % C::TN);
+      if (qq < HF) {
+#pragma unroll
+        for (int r = (qq * NRD) / HF; r < ((qq + 1) * NRD) / HF; ++r) lds_read(bufn, sub_next, rb ^ 1, r);
+      }
+      if (qq < t1 - t0) issue_range(Unchecked{}, kt_i, buf_i, t0 + qq, t0 + qq + 1);
+      if (qq == HF - 1) conv_offsets(rb ^ 1);
+      if (qq >= MF - HF) {
+        const int q2 = qq - (MF - HF);
+#pragma unroll
+        for (int piece = (q2 * NPIECE) / HF; piece < ((q2 + 1) * NPIECE) / HF; ++piece) conv_piece(rb ^ 1, piece);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   // ---- main loop: the schedule of k_gemm_tn (two LDS stages, four sub-steps, loads of the next stage in thirds)
-  constexpr int MF = C::TM * C::TN, NRD = C::TM + C::TN + 2, NCV = 22 * C::TN + 8;
   auto stage = [&](auto bufc, auto steadyc, int kt) {
     constexpr int cur = decltype(bufc)::value;
     constexpr bool ST = decltype(steadyc)::value;
     using Other = std::integral_constant<int, cur ^ 1>;
-    bool more1 = true;
-    if constexpr (!ST) {
-      more1 = kt + 1 < nk;
+    if constexpr (ST) {
+      __builtin_amdgcn_sched_barrier(0);
+      substep(bufc, 1, 0, kt + 1, cur ^ 1, P0, P0 + P1);
+      substep(bufc, 2, 1, kt + 1, cur ^ 1, P0 + P1, LPS);
+      substep(bufc, 3, 0, 0, 0, 0, 0);
+      stage_sync();
+      substep(Other{}, 0, 1, kt + 2, cur, 0, P0);
+    } else {
+      const bool more1 = kt + 1 < nk;
       if (kt + 1 < nfull) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, LPS);
       else if (more1) issue_range(Checked{}, kt + 1, cur ^ 1, 0, LPS);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 1, 1);
+      mfma_all(0);
+      convert(1);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 2, 0);
+      mfma_all(1);
+      convert(0);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(bufc, 3, 1);
+      mfma_all(0);
+      convert(1);
+      stage_sync();
+      if (more1) load_frags(Other{}, 0, 0);
+      if (kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
+      mfma_all(1);
+      if (more1) convert(0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 1, 1);
-    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0, P0 + P1);
-    mfma_all(0);
-    convert(1);
-    if constexpr (ST) TnSched<MF, NRD, P1, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 2, 0);
-    if constexpr (ST) issue_range(Unchecked{}, kt + 1, cur ^ 1, P0 + P1, LPS);
-    mfma_all(1);
-    convert(0);
-    if constexpr (ST) TnSched<MF, NRD, P2, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(bufc, 3, 1);
-    mfma_all(0);
-    convert(1);
-    if constexpr (ST) TnSched<MF, NRD, 0, NCV, 0>::run();
-    stage_sync();
-    if (ST || more1) load_frags(Other{}, 0, 0);
-    if (ST || kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, cur, 0, P0);
-    mfma_all(1);
-    if (ST || more1) convert(0);
-    if constexpr (ST) TnSched<MF, NRD, P0, NCV, 0>::run();
-    __builtin_amdgcn_sched_barrier(0);
   };
   using B0 = std::integral_constant<int, 0>;
   using B1 = std::integral_constant<int, 1>;
