@@ -38,7 +38,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -177,7 +177,8 @@ def main():
         b.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg4": synth.CFG4, "cfg5": synth.CFG5}[args.workload]
+    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg4": synth.CFG4,
+           "cfg5": synth.CFG5}[args.workload]     # cfg3: the four linears of one encoder layer (the stack repeats them 12x)
     w_bits = cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0]
     if args.fraction:
         num, den = (int(t) for t in args.fraction.split("/"))

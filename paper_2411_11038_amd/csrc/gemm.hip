@@ -25,6 +25,9 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 #ifndef EFQAT_GEMM_AUX
 #define EFQAT_GEMM_AUX 0   // cache-policy bits of the global->LDS tile loads (sc0 = 1, nt = 2, sc1 = 16)
 #endif
+#ifndef EFQAT_GEMM_GM
+#define EFQAT_GEMM_GM 8   // row tiles per group of the block -> tile walk
+#endif
 constexpr int KALIGN = 64;  // split-K slices start on multiples of this many K elements
 
 
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   int pid = blockIdx.x;
   const int nblk = gridDim.x;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  const int GM = 8;
+  const int GM = EFQAT_GEMM_GM;
   const int per_group = GM * g.tiles_n;
   const int group = pid / per_group;
   const int first_m = group * GM;
