@@ -336,6 +336,8 @@ struct BwdPlan {
   bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
   bool tn;         // dW product straight from token-major dY columns and the uint8 codes (no transposed copies)
   bool tn_direct;  // ... with dY itself as the A operand (all channels selected)
+  bool cdw;        // convolution dW product with the im2col gather of the codes inside the tile loads
+  bool cdx;        // convolution dX product with the im2col gather inside the tile loads (no im2col matrix)
   bool dx8;        // dX product with the weight operand read from the int8 codes (no bf16 W_q^T copy)
   int dx8_tile;
   int64_t kp;      // k rounded up to 8 (pitch of the compacted dY columns)
@@ -344,7 +346,7 @@ struct BwdPlan {
 };
 
 static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, int taps, int64_t k,
-                         int dy_dtype, int dy_layout, bool im2col) {
+                         int dy_dtype, int dy_layout, bool im2col, const ConvGeom* cg = nullptr) {
   BwdPlan p{};
   p.Mx = T_in; p.Tw = T_out; p.Nw = (int64_t)taps * c_in;
   p.ldc = round_up(c_out, 8); p.ldt = round_up(T_out, 8);
@@ -352,11 +354,14 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   const bool direct_tok = dy_layout == EFQAT_DY_TOKEN_MAJOR && dy_dtype == EFQAT_BF16 && (c_out % 8) == 0;
   p.need_dyn = !direct_tok;
   const bool direct_rows = dy_layout == EFQAT_DY_CHANNEL_MAJOR && dy_dtype == EFQAT_BF16 && (T_out % 8) == 0;
-  p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && !im2col && (c_in % 16) == 0;
+  p.cdw = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && im2col && cg && (c_in % 128) == 0;
+  p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && ((!im2col && (c_in % 16) == 0) || p.cdw);
   p.tn_direct = p.tn && direct_tok && k == c_out;
   p.kp = round_up(k, 8);
   p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
-  p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false);
+  // stride-1 convolutions whose channel pitch is a multiple of the 64-element K stage gather dY in the tile loads
+  p.cdx = im2col && cg && cg->stride == 1 && (p.ldc % 64) == 0 && cg->H <= 65535 && cg->W <= 65535;
+  p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, true, !p.cdx);
   p.dx8 = false; p.dx8_tile = 0;
   // Large products (the planner's 256 x 256 case) with a bf16 token-major dY read the weight operand straight
   // from the int8 codes: same speed as the bf16 kernel on these shapes, and no transposed bf16 copy of W_q.
@@ -365,15 +370,15 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
     p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
     p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
   }
-  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !p.tn) : GemmPlan{128, 1, 0, 0};
+  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !p.tn, !p.cdw) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
-  p.b_colA = im2col ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
+  p.b_colA = (im2col && !p.cdx) ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
   p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
   p.b_xcT = (k > 0 && !p.tn) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
-  p.b_zero = (p.tn || p.dx8) ? 256 : 0; cv.take(p.b_zero);
+  p.b_zero = (p.tn || p.dx8 || p.cdx) ? 256 : 0; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -392,7 +397,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   const int taps = cg ? cg->KH * cg->KW : 1;
   // a 1x1 / stride 1 / no-padding convolution is a linear layer over pixels: no im2col needed
   const bool im2col = cg != nullptr && !(taps == 1 && cg->stride == 1 && cg->pad == 0);
-  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col);
+  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col, cg);
   WsCarver cv(ws);
   bf16_t* wqT = (bf16_t*)cv.take(p.b_wqT);
   bf16_t* dyn = (bf16_t*)cv.take(p.b_dyn);
@@ -412,7 +417,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     TransposeExtra ex{};
     ex.z_in = c_in; ex.z_out = p.ldc;                 // one launch for all taps
     rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
-                                   p.Kx, 0, p.ldc, st, p.tn ? (uint32_t*)zero_page : nullptr, taps, &ex);
+                                   p.Kx, 0, p.ldc, st, (p.tn || p.cdx) ? (uint32_t*)zero_page : nullptr, taps, &ex);
     if (rc) return rc;
   }
 
@@ -443,7 +448,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   // ---- dX product with the fused straight-through / qparam epilogue
   const bf16_t* A = dy_tok;
   int64_t lda = p.ldc;
-  if (im2col) {
+  if (im2col && !p.cdx) {
     hipLaunchKernelGGL(k_im2col_dy, dim3(grid1d(T_in * taps * (p.ldc / 8))), dim3(256), 0, st, dy_tok, p.ldc, *cg,
                        colA);
     EFQAT_LAUNCH_CHECK();
@@ -453,6 +458,9 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   if (p.dx8) {
     if (((uintptr_t)io.w_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
     rc = launch_gemm_dx8(dy_tok, c_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out, p.dx8_tile, epi, st);
+  } else if (p.cdx) {
+    const ConvDxMap cm{cg->H, cg->W, cg->Ho, cg->Wo, cg->KW, cg->pad, zero_page};
+    rc = launch_gemm_nt_conv_dx(dy_tok, p.ldc, wqT, p.Kx, p.Mx, c_in, p.Kx, cm, p.plan_dx, epi, st);
   } else {
     rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
   }
@@ -481,8 +489,14 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
       EFQAT_LAUNCH_CHECK();
       At = sel; ldat = p.kp; acols = p.kp;
     }
-    rc = launch_gemm_tn(At, ldat, acols, io.x_codes, c_in, c_in, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
-                        part_dw, st);
+    if (p.cdw) {
+      const ConvDwMap cm{cg->H, cg->W, cg->Ho, cg->Wo, cg->KW, cg->stride, cg->pad, (int)c_in};
+      rc = launch_gemm_tn_conv(At, ldat, acols, io.x_codes, cm, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
+                               part_dw, st);
+    } else {
+      rc = launch_gemm_tn(At, ldat, acols, io.x_codes, c_in, c_in, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
+                          part_dw, st);
+    }
     if (rc) return rc;
   } else {
   // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16
@@ -612,7 +626,7 @@ extern "C" size_t efqat_conv_bwd_workspace_bytes(int64_t N, int64_t H, int64_t W
   if (conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g) || k < 0 || k > c_out) return 0;
   const bool im2col = !(g.KH * g.KW == 1 && g.stride == 1 && g.pad == 0);
   return make_plan((int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, g.KH * g.KW, k, dy_dtype, dy_layout,
-                   im2col).total;
+                   im2col, &g).total;
 }
 
 extern "C" int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,

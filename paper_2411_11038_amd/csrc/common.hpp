@@ -104,7 +104,7 @@ struct GemmPlan {
 };
 // Pure host function of the problem size (so the workspace query and the call agree).  allow_split = false
 // for the product with the fused dX epilogue.
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192 = true);
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192 = true, bool allow_256 = true);
 
 // C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
 //   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.
@@ -122,6 +122,21 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
 int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* B, int64_t ldb, int64_t b_cols,
                    const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
                    float* out_partial, hipStream_t stream);
+// dW product of a convolution without a materialised im2col matrix: A = compacted dY columns [N*Ho*Wo][lda] as in
+// launch_gemm_tn, B = the activation codes x_codes NHWC gathered with the tap map inside the tile loads.
+// N = KH*KW*c_in, c_in % 128 == 0 (a 128-wide column tile lies inside one tap), plan.tile == 128.
+struct ConvDwMap { int H, W, Ho, Wo, KW, stride, pad, c_in; };
+int launch_gemm_tn_conv(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* x_codes, const ConvDwMap& cm,
+                        const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                        float* out_partial, hipStream_t stream);
+// dX product of a stride-1 convolution without a materialised im2col matrix: row m of the A operand is the input
+// pixel (n, h, w); its K = (tap, c_out) elements are gathered from the token-major dY [N*Ho*Wo][ldc] inside the
+// tile loads (zero_page, 256 zero bytes, stands in for taps that fall outside the output image).  ldc % 64 == 0,
+// K = KH*KW*ldc, plan.tile 192 or 128, no split-K.
+struct ConvDxMap { int H, W, Ho, Wo, KW, pad; const void* zero_page; };
+int launch_gemm_nt_conv_dx(const bf16_t* dy_tok, int64_t ldc, const bf16_t* wqT, int64_t ldb, int64_t M, int64_t N,
+                           int64_t K, const ConvDxMap& cm, const GemmPlan& plan, const GemmEpilogueDx& epi,
+                           hipStream_t stream);
 // dX product with the weight operand read from the int8 codes (K-major [C_out][ldb]) and scaled by s_w[c] in
 // registers, fused dX epilogue.  dy: bf16 [M][lda]; N = C_in multiple of 16; tile 256 or 128.  The partial-sum
 // array of the epilogue needs ceil(M / tile) * ceil(N / tile) pairs.

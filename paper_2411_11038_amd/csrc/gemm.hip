@@ -22,9 +22,6 @@ typedef int intx4_t __attribute__((ext_vector_type(4)));
 typedef int intx16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-#ifndef EFQAT_GEMM_AUX
-#define EFQAT_GEMM_AUX 0   // cache-policy bits of the global->LDS tile loads (sc0 = 1, nt = 2, sc1 = 16)
-#endif
 #ifndef EFQAT_GEMM_GM
 #define EFQAT_GEMM_GM 8   // row tiles per group of the block -> tile walk
 #endif
@@ -81,7 +78,8 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // EPI: EPI_RAW fp32 partial tiles (split-K), EPI_DX fused dX epilogue, EPI_FWD forward epilogue.
 // I8: operands are int8 codes (A unsigned, re-biased by 128 in registers) on v_mfma_i32_32x32x32_i8; else bf16.
-template <int BM, int BN, int EPI, bool I8>
+// CONV: the A operand is gathered from a token-major dY with the im2col map of a stride-1 convolution (see GemmArgs).
+template <int BM, int BN, int EPI, bool I8, bool CONV = false>
 __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the body uses gfx950-only builtins; the host pass needs only the launch stub
   constexpr int S = 2;
@@ -107,11 +105,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const int tm = first_m + (pid % per_group) % gsize;
   const int tn = (pid % per_group) / gsize;
   const int m0 = tm * BM, n0 = tn * BN;
-#ifdef EFQAT_GEMM_DEBUG_SAMETILE
-  const int lm0 = 0, ln0 = 0;
-#else
   const int lm0 = m0, ln0 = n0;
-#endif
 
   const int k_begin = blockIdx.y * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
@@ -123,13 +117,37 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const int lch = slot ^ (((wave * C::RPI + lrow) / C::R256) & (C::CPRW - 1));
   const char* a_ptr[C::A_G];
   const char* b_ptr[C::B_G];
+  int cv_q0[CONV ? C::A_G : 1], cv_hw[CONV ? C::A_G : 1];   // CONV: n * Ho * Wo and (h << 16 | w) of the slot's pixel
 #pragma unroll
   for (int j = 0; j < C::A_G; ++j) {
     int gm = lm0 + (wave + 4 * j) * C::RPI + lrow;
     gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row
-    const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
-    a_ptr[j] = (const char*)g.A + (src * g.lda + k_begin) * ESZ + lch * 16;
+    if constexpr (CONV) {
+      const int hw = g.cv_H * g.cv_W;
+      const int n = gm / hw, rem = gm - n * hw;
+      const int h = rem / g.cv_W, w = rem - h * g.cv_W;
+      cv_q0[j] = n * g.cv_Ho * g.cv_Wo;
+      cv_hw[j] = (h << 16) | w;
+      a_ptr[j] = nullptr;
+    } else {
+      const int64_t src = g.a_rows ? (int64_t)g.a_rows[gm] : (int64_t)gm;
+      a_ptr[j] = (const char*)g.A + (src * g.lda + k_begin) * ESZ + lch * 16;
+    }
   }
+  // source of this lane's 16 bytes of A-slot j in stage kt
+  auto a_src = [&](int j, int kt) -> const char* {
+    if constexpr (CONV) {
+      const int sidx = k_begin / 64 + kt;              // 64-channel stage index along K = (tap, channel)
+      const int tap = (int)(((uint64_t)(uint32_t)sidx * g.cv_m_spt) >> 32), cst = sidx - tap * g.cv_spt;
+      const int kh = (int)(((uint64_t)(uint32_t)tap * g.cv_m_kw) >> 32), kw = tap - kh * g.cv_KW;
+      const int ho = (cv_hw[j] >> 16) + g.cv_pad - kh, wo = (cv_hw[j] & 0xFFFF) + g.cv_pad - kw;
+      const bool ok = (unsigned)ho < (unsigned)g.cv_Ho && (unsigned)wo < (unsigned)g.cv_Wo;
+      const int64_t pix = (int64_t)cv_q0[j] + ho * g.cv_Wo + wo;
+      return ok ? (const char*)g.A + (pix * g.lda + cst * 64) * 2 + lch * 16 : (const char*)g.cv_zero;
+    } else {
+      return a_ptr[j] + kt * 128;
+    }
+  };
 #pragma unroll
   for (int j = 0; j < C::B_G; ++j) {
     int gn = ln0 + (wave + 4 * j) * C::RPI + lrow;
@@ -147,10 +165,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     const int koff = kt * 128;                          // bytes
 #pragma unroll
     for (int j = 0; j < C::A_G; ++j)
-      __builtin_amdgcn_global_load_lds(a_ptr[j] + koff, (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, EFQAT_GEMM_AUX);
+      __builtin_amdgcn_global_load_lds(a_src(j, kt), (lds_ptr_t)(sa + (wave + 4 * j) * 1024), 16, 0, 0);
 #pragma unroll
     for (int j = 0; j < C::B_G; ++j)
-      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, EFQAT_GEMM_AUX);
+      __builtin_amdgcn_global_load_lds(b_ptr[j] + koff, (lds_ptr_t)(sb + (wave + 4 * j) * 1024), 16, 0, 0);
   };
   // any stage: a ragged last stage goes through registers.  K is a multiple of 8, so a 16-byte chunk is
   // all in or all out; missing chunks are written as zeros.
@@ -164,7 +182,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       const bool ok = (koff + lch * 16) < span * ESZ;
 #pragma unroll
       for (int j = 0; j < C::A_G; ++j) {
-        const uint4 v = ok ? *reinterpret_cast<const uint4*>(a_ptr[j] + koff) : make_uint4(0, 0, 0, 0);
+        const uint4 v = ok ? *reinterpret_cast<const uint4*>(a_src(j, kt)) : make_uint4(0, 0, 0, 0);
         *reinterpret_cast<uint4*>(sa + (wave + 4 * j) * 1024 + lane * 16) = v;
       }
 #pragma unroll
@@ -235,10 +253,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 #pragma unroll
     for (int t = t0; t < t1; ++t) {
       if (t < C::A_G)
-        __builtin_amdgcn_global_load_lds(a_ptr[t] + koff, (lds_ptr_t)(sa + (wave + 4 * t) * 1024), 16, 0, EFQAT_GEMM_AUX);
+        __builtin_amdgcn_global_load_lds(a_src(t, kt), (lds_ptr_t)(sa + (wave + 4 * t) * 1024), 16, 0, 0);
       else
         __builtin_amdgcn_global_load_lds(b_ptr[t - C::A_G] + koff,
-                                         (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, EFQAT_GEMM_AUX);
+                                         (lds_ptr_t)(sb + (wave + 4 * (t - C::A_G)) * 1024), 16, 0, 0);
     }
   };
   auto stage_sync = [&]() {
@@ -259,16 +277,12 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     const int cur = kt & 1;
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 1, 1);
-#ifndef EFQAT_GEMM_DEBUG_NOLOAD
     issue_range(kt + 1, cur ^ 1, P0, P0 + P1);
-#endif
     mfma_all(0);
     SchedPattern<MF, NR, P1, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
     load_frags(cur, 2, 0);
-#ifndef EFQAT_GEMM_DEBUG_NOLOAD
     issue_range(kt + 1, cur ^ 1, P0 + P1, LPS);
-#endif
     mfma_all(1);
     SchedPattern<MF, NR, P2, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
@@ -277,9 +291,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
     SchedPattern<MF, NR, 0, 0>::run();
     stage_sync();
     load_frags(cur ^ 1, 0, 0);
-#ifndef EFQAT_GEMM_DEBUG_NOLOAD
     issue_range(kt + 2, cur, 0, P0);
-#endif
     mfma_all(1);
     SchedPattern<MF, NR, P0, 0>::run();
     __builtin_amdgcn_sched_barrier(0);
@@ -404,12 +416,13 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 struct TileModel { int t; int bpc; double rate; double epi_dx; };
 static const TileModel kTiles[3] = {{256, 1, 2500.0, 0.75}, {192, 1, 2100.0, 0.75}, {128, 2, 1000.0, 0.6}};
 
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192) {
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192, bool allow_256) {
   GemmPlan best{};
   double best_t = 1e300;
   const int64_t ksteps = ceil_div(K, KALIGN);
   for (const TileModel& tm : kTiles) {
     if (tm.t == 192 && !allow_192) continue;
+    if (tm.t == 256 && !allow_256) continue;
     const int64_t tiles = ceil_div(M, tm.t) * ceil_div(N, tm.t);
     int64_t max_s = allow_split ? ksteps / 8 : 1;
     if (max_s < 1) max_s = 1;
@@ -458,12 +471,12 @@ void gemm_prof_end(int which, hipStream_t st, int slot) {
   if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
 }
 
-template <int BM, int BN, int EPI, bool I8>
+template <int BM, int BN, int EPI, bool I8, bool CONV = false>
 static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   using C = TileCfg<BM, BN, 2>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, EPI, I8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, EPI, I8, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             C::LDS_BYTES) != hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
@@ -472,7 +485,7 @@ static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   int slot = 0;
   constexpr int kProf = EPI == EPI_DX ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
   const bool timed = gemm_prof_begin(kProf, st, &slot);
-  hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8>), grid, dim3(256), C::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) gemm_prof_end(kProf, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
@@ -509,6 +522,31 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
                  : launch_cfg<128, 128, EPI_RAW, false>(a, split_k, stream);
     default:
       return EFQAT_ERR_BAD_SHAPE;
+  }
+}
+
+int launch_gemm_nt_conv_dx(const bf16_t* dy_tok, int64_t ldc, const bf16_t* wqT, int64_t ldb, int64_t M, int64_t N,
+                           int64_t K, const ConvDxMap& cm, const GemmPlan& plan, const GemmEpilogueDx& epi,
+                           hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (ldc % 64) || (K % 64) || (ldb % 8) || cm.H > 65535 || cm.W > 65535)
+    return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || plan.split_k != 1) return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)cm.zero_page % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  GemmArgs a{};
+  a.A = dy_tok; a.lda = ldc; a.a_rows = nullptr; a.B = wqT; a.ldb = ldb;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)(ceil_div(K, KALIGN) * KALIGN);
+  a.x_codes = epi.x_codes; a.x_clip = epi.x_clip; a.x = epi.x; a.x_dtype = epi.x_dtype;
+  a.s_x = epi.s_x; a.z_x = epi.z_x; a.dx = epi.dx; a.dx_dtype = epi.dx_dtype; a.partial = epi.partial;
+  a.epi_vec = gemm_epilogue_vec_ok(epi, N) ? 1 : 0;
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  a.cv_H = cm.H; a.cv_W = cm.W; a.cv_Ho = cm.Ho; a.cv_Wo = cm.Wo; a.cv_KW = cm.KW; a.cv_pad = cm.pad;
+  a.cv_spt = (int)(ldc / 64); a.cv_zero = cm.zero_page;
+  a.cv_m_spt = (1ull << 32) / (uint64_t)a.cv_spt + 1; a.cv_m_kw = (1ull << 32) / (uint64_t)cm.KW + 1;
+  switch (plan.tile) {
+    case 192: return launch_cfg<192, 192, EPI_DX, false, true>(a, 1, stream);
+    case 128: return launch_cfg<128, 128, EPI_DX, false, true>(a, 1, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
   }
 }
 

@@ -21,6 +21,12 @@ struct GemmArgs {
   int epi_vec;            // 8-wide vector accesses allowed in the fused epilogue
   // forward epilogue (int8 product): y = s_x * s_w[n] * (acc + (128 - round(z_x)) * wsum[n])
   const float* s_w; const int32_t* wsum; void* y; int y_dtype;
+  // implicit im2col of the A operand (dX product of a stride-1 convolution): row m is the input pixel (n, h, w),
+  // K runs over (tap, c_out) with cv_spt 64-channel stages per tap, and the operand element is
+  // dY[n][h + pad - kh][w + pad - kw][c_out] or zero outside the output image (read from cv_zero)
+  int cv_H, cv_W, cv_Ho, cv_Wo, cv_KW, cv_pad, cv_spt;
+  uint64_t cv_m_spt, cv_m_kw;   // floor(2^32 / d) + 1 for d = cv_spt, cv_KW: n / d = (n * m) >> 32 for n * d < 2^32
+  const void* cv_zero;
 };
 
 // Fused epilogue of the dX product for a 256-thread block whose wavefront (wm, wn) holds the C::WM x C::WN

@@ -35,6 +35,12 @@ struct GemmTnArgs {
   int k_per_split;                    // multiple of 64
   int tiles_m, tiles_n;
   float* out;                         // raw fp32 [split][M][N]
+  // implicit im2col of the B operand (dW product of a convolution): row t is the output pixel (n, ho, wo), the
+  // N-tile at n0 belongs to tap n0 / cv_cin = (kh, kw), and the operand is the code of input pixel
+  // (n, ho*s + kh - p, wo*s + kw - p), channel n0 % cv_cin + column.  Outside the image the term is dropped by
+  // zeroing the A row of that token in this block (a padded activation is 0 after de-quantisation, which need not
+  // be a representable code).  cv_dn / cv_dh / cv_dw: how (n, ho, wo) moves when t advances by 64.
+  int cv_H, cv_W, cv_Ho, cv_Wo, cv_KW, cv_stride, cv_pad, cv_cin, cv_dn, cv_dh, cv_dw;
 };
 
 template <int T>
@@ -70,7 +76,7 @@ __device__ __forceinline__ void dma16(const char* src, char* lds_dst) {
   asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src));
 }
 
-template <int T>
+template <int T, bool CONV = false>
 __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using C = TnCfg<T>;
@@ -126,6 +132,43 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
     b_st[j] = on ? (uint32_t)(g.ldb * 64) : 0u;
   }
   constexpr int LPS = C::A_G + C::B_G;
+  // CONV: output-pixel coordinates of every slot's token row (slots 0 .. A_G-1: A, then B), advanced by 64 tokens
+  // after each use; the block's tap; per-lane byte offset of the B column inside a pixel
+  int cv_n[CONV ? LPS : 1], cv_ho[CONV ? LPS : 1], cv_wo[CONV ? LPS : 1];
+  int cv_kh = 0, cv_kw = 0;
+  int64_t cv_bcol[CONV ? C::B_G : 1];
+  if constexpr (CONV) {
+    const int tap = n0 / g.cv_cin;
+    cv_kh = tap / g.cv_KW; cv_kw = tap - cv_kh * g.cv_KW;
+    const int hw = g.cv_Ho * g.cv_Wo;
+#pragma unroll
+    for (int t = 0; t < LPS; ++t) {
+      const int kr = t < C::A_G ? (wave + 4 * t) * RPIA + a_r0 : (wave + 4 * (t - C::A_G)) * RPIB + b_r0;
+      const int tok = k_begin + kr;
+      const int n = tok / hw, rem = tok - n * hw;
+      cv_n[t] = n; cv_ho[t] = rem / g.cv_Wo; cv_wo[t] = rem - cv_ho[t] * g.cv_Wo;
+    }
+#pragma unroll
+    for (int j = 0; j < C::B_G; ++j) {
+      const int kr = (wave + 4 * j) * RPIB + b_r0;
+      const int col = (n0 - tap * g.cv_cin) + C::swz_b(lane % C::CB, kr) * 16;
+      cv_bcol[j] = col < g.cv_cin ? (int64_t)col : -1;
+    }
+  }
+  // input pixel of slot t's token under the block's tap, or -1 when it lies outside the image; then step the token
+  auto cv_pixel = [&](int t) -> int64_t {
+    const int hi = cv_ho[t] * g.cv_stride + cv_kh - g.cv_pad, wi = cv_wo[t] * g.cv_stride + cv_kw - g.cv_pad;
+    const bool ok = (unsigned)hi < (unsigned)g.cv_H && (unsigned)wi < (unsigned)g.cv_W;
+    const int64_t pix = ((int64_t)cv_n[t] * g.cv_H + hi) * g.cv_W + wi;
+    int wo = cv_wo[t] + g.cv_dw;
+    const int c1 = wo >= g.cv_Wo ? 1 : 0;
+    wo -= c1 * g.cv_Wo;
+    int ho = cv_ho[t] + g.cv_dh + c1;
+    const int c2 = ho >= g.cv_Ho ? 1 : 0;
+    ho -= c2 * g.cv_Ho;
+    cv_wo[t] = wo; cv_ho[t] = ho; cv_n[t] += g.cv_dn + c2;
+    return ok ? pix : -1;
+  };
   using Checked = std::integral_constant<bool, true>;
   using Unchecked = std::integral_constant<bool, false>;
   // issues load slots t0 .. t1-1 of stage kt; every slot must be issued exactly once per stage, in stage order
@@ -137,6 +180,9 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
     for (int t = t0; t < t1; ++t) {
       if (t < C::A_G) {
         const char* src = a_ptr[t];
+        if constexpr (CONV) {
+          if (cv_pixel(t) < 0) src = zero;              // this token's tap falls into the padding: drop its term
+        }
         if constexpr (decltype(checked)::value) {
           if (kb + (wave + 4 * t) * RPIA + a_r0 >= span) src = zero;
         }
@@ -145,6 +191,10 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
       } else {
         const int u = t - C::A_G;
         const char* src = b_ptr[u];
+        if constexpr (CONV) {
+          const int64_t pix = cv_pixel(t);
+          src = (pix >= 0 && cv_bcol[u] >= 0) ? (const char*)g.B + pix * g.cv_cin + cv_bcol[u] : zero;
+        }
         if constexpr (decltype(checked)::value) {
           if (kb + (wave + 4 * u) * RPIB + b_r0 >= span) src = zero;
         }
@@ -661,12 +711,12 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
 #endif
 }
 
-template <int T>
+template <int T, bool CONV = false>
 static int launch_tn_cfg(const GemmTnArgs& a, int split_k, hipStream_t st) {
   using C = TnCfg<T>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_tn<T>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
+    if (hipFuncSetAttribute((const void*)k_gemm_tn<T, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
         hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
@@ -674,7 +724,7 @@ static int launch_tn_cfg(const GemmTnArgs& a, int split_k, hipStream_t st) {
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
   int slot = 0;
   const bool timed = gemm_prof_begin(1, st, &slot);
-  hipLaunchKernelGGL((k_gemm_tn<T>), grid, dim3(256), C::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((k_gemm_tn<T, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) gemm_prof_end(1, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
@@ -719,6 +769,27 @@ static int launch_dx8_cfg(const GemmDx8Args& a, hipStream_t st) {
   if (timed) gemm_prof_end(0, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
+}
+
+int launch_gemm_tn_conv(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* x_codes, const ConvDwMap& cm,
+                        const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                        float* out_partial, hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (lda % 8) || (a_cols % 8) || a_cols > lda || lda >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || plan.tile != 128 || (cm.c_in % 128) != 0)
+    return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)A % 16) || ((uintptr_t)x_codes % 16) || ((uintptr_t)zero_page % 256)) return EFQAT_ERR_ALIGNMENT;
+  GemmTnArgs a{};
+  a.A = A; a.lda = lda; a.B = x_codes; a.ldb = 0; a.a_cols = (int)a_cols; a.b_cols = INT32_MAX;
+  a.zero_page = zero_page; a.z_x = z_x;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)(ceil_div(ceil_div(K, 64), plan.split_k) * 64);
+  a.tiles_m = plan.tiles_m; a.tiles_n = plan.tiles_n;
+  a.out = out_partial;
+  a.cv_H = cm.H; a.cv_W = cm.W; a.cv_Ho = cm.Ho; a.cv_Wo = cm.Wo; a.cv_KW = cm.KW; a.cv_stride = cm.stride;
+  a.cv_pad = cm.pad; a.cv_cin = cm.c_in;
+  const int hw = cm.Ho * cm.Wo, rem = 64 % hw;
+  a.cv_dn = 64 / hw; a.cv_dh = rem / cm.Wo; a.cv_dw = rem % cm.Wo;
+  return launch_tn_cfg<128, true>(a, plan.split_k, stream);
 }
 
 int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,

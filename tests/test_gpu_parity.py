@@ -343,6 +343,18 @@ CONV_CASES = [
     (2, 6, 7, 10, 9, 2, 3, 2, 0, "f32", 4, 0.7, (1, 3), 1, False),
     (4, 14, 14, 64, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (1, 20), 0, False),   # ResNet-like, several tiles
     (4, 14, 14, 64, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (0, 1), 0, False),
+    # stride 1 and C_out a multiple of 64: the dX operand is gathered inside the tile loads (no im2col matrix)
+    (2, 9, 7, 32, 128, 3, 3, 1, 1, "bf16", 8, 0.8, (1, 4), 0, False),     # two K stages per tap
+    (2, 9, 7, 32, 64, 2, 3, 1, 0, "bf16", 4, 0.7, (1, 2), 0, True),       # no padding: output smaller than input
+    (2, 6, 10, 16, 64, 3, 3, 1, 2, "f32", 8, 0.8, (1, 4), 0, False),      # padding 2: output larger than input
+    (2, 6, 10, 16, 64, 3, 1, 1, 1, "bf16", 8, 0.8, (1, 4), 1, False),     # channel-major dY, 3 x 1 kernel
+    (5, 11, 13, 48, 192, 3, 3, 1, 1, "bf16", 8, 0.8, (1, 20), 0, False),  # several row tiles, ragged edge
+    # C_in a multiple of 128 and token-major dY: the dW operand (codes) is gathered inside the tile loads
+    (2, 7, 6, 128, 24, 3, 3, 1, 1, "bf16", 4, 0.7, (1, 4), 0, False),
+    (3, 9, 8, 128, 40, 3, 3, 2, 1, "bf16", 8, 0.8, (1, 2), 0, True),      # stride 2
+    (1, 5, 5, 256, 64, 2, 2, 1, 0, "f32", 8, 0.8, (1, 1), 0, False),      # image smaller than a 64-token stage
+    (2, 6, 10, 128, 64, 3, 1, 1, 1, "bf16", 8, 0.8, (1, 1), 0, False),    # every channel: dY itself is the A operand
+    (7, 10, 9, 128, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (1, 4), 0, False),    # 630 tokens: split-K with a ragged last stage
 ]
 
 
