@@ -200,6 +200,11 @@ int efqat_set_option(int option, int value);
  *   ds_w      out float: [k] (scatter == 0) or [c_out] with only entries idx written
  *   ds_x,dz_x out float[1] each
  *   dw / ds_w may be NULL when k == 0 (dX, dS_x, dZ_x are still produced).
+ * Alignment: dy 16 bytes; x_codes and w_codes 16 bytes when c_in is a multiple of 16 (their
+ * tiles are then copied 16 bytes at a time); everything else to its element size.  A
+ * misaligned pointer is reported as EFQAT_ERR_ALIGNMENT, never read.
+ * The workspace size depends on k in both directions (k == c_out needs no compacted copy of
+ * dY): query it for the k that is passed.
  */
 size_t efqat_linear_bwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out, int64_t k,
                                         int dy_dtype, int dy_layout);
