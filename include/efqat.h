@@ -215,6 +215,34 @@ int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int
                      int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                      float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------ backward + optimizer step
+ * efqat_linear_bwd followed, in the same pass over the k updated rows, by the optimizer step
+ * that Alg. 1 applies to unfrozen channels (SGD; frozen rows, their scales and their momentum
+ * are not touched), so that the weight gradient need not travel through memory:
+ *
+ *   g   = dW[c][:] + weight_decay * w[c][:]          c in idx
+ *   buf = momentum * mom_w[c][:] + g  (stored back)  when momentum != 0, else buf = g
+ *   w[c][:] -= lr_w * buf;   s_w[c] likewise from dS_w[c] with lr_s, mom_s and no decay.
+ *
+ * w and s_w are read (old values: dX, the clip masks and dS_w refer to them) and then
+ * updated in place; dw and ds_w become optional (NULL: not written).  Everything else as in
+ * efqat_linear_bwd, including the workspace size. */
+typedef struct efqat_sgd_step {
+  float lr_w;          /* learning rate of the weights */
+  float lr_s;          /* learning rate of the weight scales */
+  float momentum;      /* 0: plain SGD, mom_w / mom_s are ignored and may be NULL */
+  float weight_decay;  /* weights only */
+  float* mom_w;        /* device, float [c_out][c_in] (conv: [c_out][KH][KW][c_in]) */
+  float* mom_s;        /* device, float [c_out] */
+} efqat_sgd_step;
+int efqat_linear_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                         int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
+                         const void* x, int x_dtype, const float* s_x, const float* z_x,
+                         const int8_t* w_codes, const uint32_t* w_clip, float* w, float* s_w,
+                         const int32_t* idx, int64_t k, void* dx, int dx_dtype, float* dw,
+                         int scatter, float* ds_w, float* ds_x, float* dz_x,
+                         const efqat_sgd_step* step, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ conv backward
  * Same as efqat_linear_bwd for Y[n][ho][wo][co] = sum_{kh,kw,ci}
  * X_q[n][ho*stride+kh-pad][wo*stride+kw-pad][ci] * W_q[co][kh][kw][ci] (zero outside the
@@ -233,6 +261,17 @@ int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64
                    const uint32_t* w_clip, const float* w, const float* s_w, const int32_t* idx,
                    int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                    float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
+
+/* efqat_conv_bwd with the fused optimizer step of efqat_linear_bwd_sgd. */
+int efqat_conv_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                       int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride,
+                       int64_t pad, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
+                       int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
+                       const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
+                       void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
+                       float* dz_x, const efqat_sgd_step* step, void* ws, size_t ws_bytes,
+                       void* stream);
+
 
 /* ------------------------------------------------------------------ low-precision forward
  * The forward product of Sec. 3.1, Y = X_q W_q^T, computed from the 8-bit codes on the int8 matrix

@@ -155,6 +155,27 @@ def bias_grad(dY):
     return d.reshape(-1, d.shape[-1]).sum(axis=0)
 
 
+def sgd_step_rows(W, S_w, idx, dW_rows, dS_w_rows, lr_w, lr_s, momentum=0.0, weight_decay=0.0,
+                  mom_w=None, mom_s=None):
+    """Optimizer step of Alg. 1 on the unfrozen channels only (SGD with momentum and weight
+    decay; frozen rows, their scales and momentum buffers stay as they are):
+        g = dW + wd * W;  buf = mu * buf + g (if mu != 0);  W -= lr_w * buf
+    and the same for the scales with lr_s and without decay.  Returns new copies
+    (W, S_w, mom_w, mom_s) in fp64."""
+    W = np.array(W, dtype=np.float64); S = np.array(S_w, dtype=np.float64)
+    mw = None if mom_w is None else np.array(mom_w, dtype=np.float64)
+    ms = None if mom_s is None else np.array(mom_s, dtype=np.float64)
+    idx = np.asarray(idx, dtype=np.int64)
+    g = np.asarray(dW_rows, dtype=np.float64) + weight_decay * W[idx]
+    gs = np.asarray(dS_w_rows, dtype=np.float64)
+    if momentum != 0.0:
+        mw[idx] = momentum * mw[idx] + g; g = mw[idx]
+        ms[idx] = momentum * ms[idx] + gs; gs = ms[idx]
+    W[idx] = W[idx] - lr_w * g
+    S[idx] = S[idx] - lr_s * gs
+    return W, S, mw, ms
+
+
 # --------------------------------------------------------------------------
 # Quantizer-parameter gradients (derived; see module header)
 # --------------------------------------------------------------------------

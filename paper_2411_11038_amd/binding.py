@@ -19,10 +19,16 @@ EXPORTS = [
     "efqat_layer_select_workspace_bytes", "efqat_layer_select",
     "efqat_bias_grad_workspace_bytes", "efqat_bias_grad",
     "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
-    "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd",
+    "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd", "efqat_linear_bwd_sgd", "efqat_conv_bwd_sgd",
     "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
     "efqat_profile_enable", "efqat_profile_read", "efqat_set_option",
 ]
+
+
+class SgdStep(C.Structure):
+    """efqat_sgd_step of include/efqat.h."""
+    _fields_ = [("lr_w", C.c_float), ("lr_s", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
+                ("mom_w", C.c_void_p), ("mom_s", C.c_void_p)]
 
 
 class EfqatError(RuntimeError):
@@ -78,6 +84,12 @@ def lib():
     L.efqat_linear_bwd.restype = ci
     L.efqat_linear_bwd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
                                    + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_linear_bwd_sgd.restype = ci
+    L.efqat_linear_bwd_sgd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
+                                       + [vp, i64, vp, ci, vp, ci, vp, vp, vp] + [C.POINTER(SgdStep), vp, sz, vp])
+    L.efqat_conv_bwd_sgd.restype = ci
+    L.efqat_conv_bwd_sgd.argtypes = ([vp, ci, ci] + [i64] * 9 + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
+                                     + [vp, i64, vp, ci, vp, ci, vp, vp, vp] + [C.POINTER(SgdStep), vp, sz, vp])
     L.efqat_conv_bwd_workspace_bytes.restype = sz
     L.efqat_conv_bwd_workspace_bytes.argtypes = [i64] * 10 + [ci, ci]
     L.efqat_conv_bwd.restype = ci
@@ -269,10 +281,17 @@ def _bwd_outputs(x, w, k, dx_dtype, scatter):
     return dx, dw, ds_w, ds_x, dz_x
 
 
+def _sgd_struct(sgd):
+    """dict(lr_w, lr_s, momentum=0, weight_decay=0, mom_w=None, mom_s=None) -> SgdStep"""
+    return SgdStep(float(sgd["lr_w"]), float(sgd["lr_s"]), float(sgd.get("momentum", 0.0)),
+                   float(sgd.get("weight_decay", 0.0)), _p(sgd.get("mom_w")), _p(sgd.get("mom_s")))
+
+
 def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, dy_layout=DY_TOKEN_MAJOR,
-               dx_dtype=None, scatter=False, ws=None, out=None):
+               dx_dtype=None, scatter=False, ws=None, out=None, sgd=None):
     """Backward of one quantized linear layer restricted to the rows idx.  Returns
-    dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys)."""
+    dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys).
+    sgd: dict for the fused optimizer step (efqat_linear_bwd_sgd): w and s_w are then updated in place."""
     L = lib()
     T, c_in = x_codes.shape
     c_out = w_codes.shape[0]
@@ -285,11 +304,15 @@ def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, d
     need = L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, _dt(dy), dy_layout)
     if ws is None:
         ws = _ws(need, x)
-    rc = L.efqat_linear_bwd(_p(dy), _dt(dy), dy_layout, T, c_in, c_out, _p(x_codes), _p(x_clip), _p(x), _dt(x),
-                            _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
-                            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
-                            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x), _p(ws),
-                            ws.numel(), _stream())
+    args = (_p(dy), _dt(dy), dy_layout, T, c_in, c_out, _p(x_codes), _p(x_clip), _p(x), _dt(x),
+            _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
+            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
+            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x))
+    if sgd is None:
+        rc = L.efqat_linear_bwd(*args, _p(ws), ws.numel(), _stream())
+    else:
+        step = _sgd_struct(sgd)
+        rc = L.efqat_linear_bwd_sgd(*args, C.byref(step), _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_linear_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)
 
@@ -309,7 +332,7 @@ def linear_fwd(x_codes, s_x, z_x, w_codes, s_w, y_dtype=torch.bfloat16, ws=None,
 
 
 def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, stride=1, pad=0,
-             dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None):
+             dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None, sgd=None):
     """Backward of one quantized conv layer (x NHWC, w OHWI) restricted to output channels idx."""
     L = lib()
     N, H, W, c_in = x_codes.shape
@@ -323,10 +346,14 @@ def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, str
     need = L.efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, _dt(dy), dy_layout)
     if ws is None:
         ws = _ws(need, x)
-    rc = L.efqat_conv_bwd(_p(dy), _dt(dy), dy_layout, N, H, W, c_in, c_out, KH, KW, stride, pad, _p(x_codes),
-                          _p(x_clip), _p(x), _dt(x), _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
-                          _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
-                          int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x), _p(ws), ws.numel(),
-                          _stream())
+    args = (_p(dy), _dt(dy), dy_layout, N, H, W, c_in, c_out, KH, KW, stride, pad, _p(x_codes),
+            _p(x_clip), _p(x), _dt(x), _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
+            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
+            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x))
+    if sgd is None:
+        rc = L.efqat_conv_bwd(*args, _p(ws), ws.numel(), _stream())
+    else:
+        step = _sgd_struct(sgd)
+        rc = L.efqat_conv_bwd_sgd(*args, C.byref(step), _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_conv_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)

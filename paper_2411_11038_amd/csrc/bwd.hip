@@ -229,6 +229,14 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
   sum_partials_block(part, n, ds_x, dz_x);
 }
 
+// Optional optimizer step fused into the second pass (off when w == nullptr): SGD with momentum and weight decay
+// on the rows idx of the master weights and on their scales, the rule of Alg. 1's optimizer step for unfrozen
+// channels:  g = dW + wd * W;  buf = mu * buf + g;  W -= lr_w * buf   (buf is skipped when mu == 0; scales: no decay).
+struct SgdArgs {
+  float* w; float* s_w; float* mom_w; float* mom_s;
+  float lr_w, lr_s, mu, wd;
+};
+
 // Second pass of the restricted weight gradient: ordered split-K sum, S_x scaling, straight-through mask
 // of the weight quantizer and the per-row scale gradient
 //   dW[c][j] = in range ? dW_q : 0,  dS_w[c] = sum_j dW_q * (in range ? code - w/S_w : code),  c = idx[m].
@@ -239,7 +247,8 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
                                                    const float* __restrict__ s_w, const int32_t* __restrict__ idx,
                                                    float* __restrict__ dw, int scatter, float* __restrict__ ds_w,
                                                    const float* __restrict__ part_dx, int64_t n_part_dx,
-                                                   float* __restrict__ ds_x, float* __restrict__ dz_x) {
+                                                   float* __restrict__ ds_x, float* __restrict__ dz_x,
+                                                   const SgdArgs sgd) {
   if ((int64_t)blockIdx.x == k) {                     // one extra block: dS_x, dZ_x from the dX epilogue's partials
     sum_partials_block(part_dx, n_part_dx, ds_x, dz_x);
     return;
@@ -274,7 +283,22 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
         acc += dwq[t] * gs;
         o[t] = inr ? dwq[t] : 0.0f;
       }
-      *reinterpret_cast<float4*>(dw + orow * ncols + j) = make_float4(o[0], o[1], o[2], o[3]);
+      if (dw) *reinterpret_cast<float4*>(dw + orow * ncols + j) = make_float4(o[0], o[1], o[2], o[3]);
+      if (sgd.w) {
+        float gq[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) gq[t] = fmaf(sgd.wd, wf[t], o[t]);
+        if (sgd.mom_w) {
+          float4 mb = *reinterpret_cast<const float4*>(sgd.mom_w + c * ncols + j);
+          mb.x = fmaf(sgd.mu, mb.x, gq[0]); mb.y = fmaf(sgd.mu, mb.y, gq[1]);
+          mb.z = fmaf(sgd.mu, mb.z, gq[2]); mb.w = fmaf(sgd.mu, mb.w, gq[3]);
+          *reinterpret_cast<float4*>(sgd.mom_w + c * ncols + j) = mb;
+          gq[0] = mb.x; gq[1] = mb.y; gq[2] = mb.z; gq[3] = mb.w;
+        }
+        *reinterpret_cast<float4*>(sgd.w + c * ncols + j) =
+            make_float4(fmaf(-sgd.lr_w, gq[0], wf[0]), fmaf(-sgd.lr_w, gq[1], wf[1]), fmaf(-sgd.lr_w, gq[2], wf[2]),
+                        fmaf(-sgd.lr_w, gq[3], wf[3]));
+      }
     }
   } else {
     for (int64_t j = threadIdx.x; j < ncols; j += 256) {
@@ -283,16 +307,37 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
       const float dwq = sx * a;
       const bool inr = (w_clip[c * wpr + (j >> 5)] >> (j & 31)) & 1u;
       const float code = (float)w_codes[c * ncols + j];
-      const float gs = inr ? (code - w[c * ncols + j] / sw) : code;
+      const float wv = w[c * ncols + j];
+      const float gs = inr ? (code - wv / sw) : code;
       acc += dwq * gs;
-      dw[orow * ncols + j] = inr ? dwq : 0.0f;
+      const float ov = inr ? dwq : 0.0f;
+      if (dw) dw[orow * ncols + j] = ov;
+      if (sgd.w) {
+        float gq = fmaf(sgd.wd, wv, ov);
+        if (sgd.mom_w) {
+          gq = fmaf(sgd.mu, sgd.mom_w[c * ncols + j], gq);
+          sgd.mom_w[c * ncols + j] = gq;
+        }
+        sgd.w[c * ncols + j] = fmaf(-sgd.lr_w, gq, wv);
+      }
     }
   }
   acc = wave_sum(acc);
   __shared__ float red[4];
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) ds_w[orow] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (threadIdx.x == 0) {
+    const float ds = (red[0] + red[1]) + (red[2] + red[3]);
+    if (ds_w) ds_w[orow] = ds;
+    if (sgd.s_w) {
+      float gq = ds;
+      if (sgd.mom_s) {
+        gq = fmaf(sgd.mu, sgd.mom_s[c], gq);
+        sgd.mom_s[c] = gq;
+      }
+      sgd.s_w[c] = fmaf(-sgd.lr_s, gq, sw);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -389,6 +434,7 @@ struct BwdIo {
   const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype; const float* s_x; const float* z_x;
   const int8_t* w_codes; const uint32_t* w_clip; const float* w; const float* s_w; const int32_t* idx; int64_t k;
   void* dx; int dx_dtype; float* dw; int scatter; float* ds_w; float* ds_x; float* dz_x;
+  SgdArgs sgd;     // fused optimizer step (sgd.w == nullptr: none)
 };
 
 // Shared driver.  For conv, T_in = N*H*W input pixels, T_out = N*Ho*Wo output pixels; for linear both are T.
@@ -540,11 +586,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   if (rc) return rc;
   }
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
-                    ((uintptr_t)io.w_codes % 4) == 0) ? 1 : 0;
+                    ((uintptr_t)io.w_codes % 4) == 0 && ((uintptr_t)io.sgd.mom_w % 16) == 0) ? 1 : 0;
   // k blocks for the rows of dW plus one that finishes dS_x, dZ_x
   hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k + 1), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw,
                      fvec, io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w, part_dx,
-                     n_part_dx, io.ds_x, io.dz_x);
+                     n_part_dx, io.ds_x, io.dz_x, io.sgd);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -559,7 +605,8 @@ static int check_common(const BwdIo& io, int64_t c_out, const void* ws) {
   if (!io.dy || !io.x_codes || !io.x_clip || !io.x || !io.s_x || !io.z_x || !io.w_codes || !io.s_w || !io.dx ||
       !io.ds_x || !io.dz_x || !ws)
     return EFQAT_ERR_NULL_PTR;
-  if (io.k > 0 && (!io.idx || !io.dw || !io.ds_w || !io.w_clip || !io.w)) return EFQAT_ERR_NULL_PTR;
+  if (io.k > 0 && (!io.idx || !io.w_clip || !io.w)) return EFQAT_ERR_NULL_PTR;
+  if (io.k > 0 && !io.sgd.w && (!io.dw || !io.ds_w)) return EFQAT_ERR_NULL_PTR;   // gradients may stay unwritten only with the fused step
   if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
   const size_t dysz = io.dy_dtype == EFQAT_F32 ? 4 : 2;
   // the dY tile loads are 16-byte vectors when dY is used in place
@@ -603,6 +650,36 @@ extern "C" int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int
   return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
 }
 
+static int fill_sgd(const efqat_sgd_step* step, float* w, float* s_w, SgdArgs* out) {
+  if (!step || !w || !s_w) return EFQAT_ERR_NULL_PTR;
+  if (step->momentum != 0.0f && (!step->mom_w || !step->mom_s)) return EFQAT_ERR_NULL_PTR;
+  if (((uintptr_t)step->mom_w % 4) != 0 || ((uintptr_t)step->mom_s % 4) != 0) return EFQAT_ERR_ALIGNMENT;
+  out->w = w; out->s_w = s_w;
+  out->mom_w = step->momentum != 0.0f ? step->mom_w : nullptr;
+  out->mom_s = step->momentum != 0.0f ? step->mom_s : nullptr;
+  out->lr_w = step->lr_w; out->lr_s = step->lr_s; out->mu = step->momentum; out->wd = step->weight_decay;
+  return EFQAT_OK;
+}
+
+extern "C" int efqat_linear_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                                    int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
+                                    int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
+                                    const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
+                                    void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
+                                    float* dz_x, const efqat_sgd_step* step, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
+    return EFQAT_ERR_BAD_SHAPE;
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  int rc = fill_sgd(step, w, s_w, &io.sgd);
+  if (rc) return rc;
+  rc = check_common(io, c_out, ws);
+  if (rc) return rc;
+  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
+  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
+}
+
 static int conv_geom(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out, int64_t KH, int64_t KW,
                      int64_t stride, int64_t pad, ConvGeom* g) {
   if (N <= 0 || H <= 0 || W <= 0 || c_in <= 0 || c_out <= 0 || KH <= 0 || KW <= 0 || stride <= 0 || pad < 0)
@@ -641,6 +718,27 @@ extern "C" int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64
   if (rc) return rc;
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  rc = check_common(io, c_out, ws);
+  if (rc) return rc;
+  if (ws_bytes < efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout))
+    return EFQAT_ERR_WORKSPACE;
+  return run_bwd(io, (int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, &g, ws, (hipStream_t)stream);
+}
+
+extern "C" int efqat_conv_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                                  int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                                  const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                                  const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                                  float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                                  float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                                  const efqat_sgd_step* step, void* ws, size_t ws_bytes, void* stream) {
+  ConvGeom g;
+  int rc = conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g);
+  if (rc) return rc;
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  rc = fill_sgd(step, w, s_w, &io.sgd);
+  if (rc) return rc;
   rc = check_common(io, c_out, ws);
   if (rc) return rc;
   if (ws_bytes < efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout))

@@ -94,6 +94,16 @@ def test_argument_validation_needs_no_device():
     assert lin(ws=fake + 16) == -9
     assert lin(dy=fake + 2) == -9
 
+    # fused optimizer step
+    from paper_2411_11038_amd.binding import SgdStep
+    def lin_sgd(step, w=fake, dw=fake):
+        return L.efqat_linear_bwd_sgd(fake, 1, 0, 8, 8, 8, fake, fake, fake, 1, fake, fake, fake, fake, w, fake,
+                                      fake, 2, fake, 1, dw, 0, fake, fake, fake, step, fake, 64, None)
+    assert lin_sgd(None) == -1
+    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.9, 0.0, None, None))) == -1       # momentum without buffers
+    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.0, 0.0, None, None)), w=None) == -1
+    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.0, 0.0, None, None)), dw=None) == -6   # valid up to the workspace check
+
     # conv backward
     def conv(N=1, H=4, W=4, c_in=8, c_out=8, KH=3, KW=3, stride=1, pad=1, k=2, wsb=1 << 30):
         return L.efqat_conv_bwd(fake, 1, 0, N, H, W, c_in, c_out, KH, KW, stride, pad, fake, fake, fake, 1, fake,

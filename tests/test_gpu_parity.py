@@ -312,6 +312,90 @@ def test_linear_bwd_int8_weight_operand(case):
     assert_max_err(host(out["dx"]), host(out2["dx"]), 8e-3, "dX int8-operand vs bf16-operand kernel")
 
 
+@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4)])
+@pytest.mark.parametrize("shape", [(300, 208, 136), (260, 70, 43)])
+def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
+    # the fused optimizer step must equal the plain call followed by the SGD rule on the rows idx, and leave
+    # everything else untouched
+    T, c_in, c_out = shape
+    X, W, dY = synth.linear_layer(5100 + T, T, c_in, c_out, act_dtype="bf16")
+    xd, wd_t, dyd = act_tensor(X, "bf16"), dev(W), act_tensor(dY, "bf16")
+    fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=True)
+    fw = ef.fakequant_fwd(wd_t, ef.W_PER_ROW_SYM, 8, init_minmax=True)
+    k = ef.k_from_ratio(c_out, 1, 4)
+    idx, _ = ef.channel_select(wd_t, k)
+    args = (dyd, fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"], fw["codes"], fw["clip_bits"])
+    plain = ef.linear_bwd(*args, wd_t, fw["scale"], idx)
+    torch.cuda.synchronize()
+    mom_w0 = synth.normal(77, 5, (c_out, c_in), std=0.01).astype(np.float32)
+    mom_s0 = synth.normal(77, 6, (c_out,), std=0.01).astype(np.float32)
+    w2, s2 = wd_t.clone(), fw["scale"].clone()
+    mw, ms = dev(mom_w0), dev(mom_s0)
+    step = dict(lr_w=0.05, lr_s=0.01, momentum=momentum, weight_decay=wd, mom_w=mw if momentum else None,
+                mom_s=ms if momentum else None)
+    fused = ef.linear_bwd(*args, w2, s2, idx, sgd=step)
+    torch.cuda.synchronize()
+    for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
+        assert torch.equal(plain[key], fused[key]), key
+    ii = idx.cpu().numpy().astype(np.int64)
+    Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
+                                         momentum, wd, mom_w0 if momentum else None, mom_s0 if momentum else None)
+    np.testing.assert_allclose(host(w2), Wn, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(host(s2), Sn, rtol=2e-6, atol=1e-12)
+    frozen = np.setdiff1d(np.arange(c_out), ii)
+    assert np.array_equal(host(w2)[frozen], W[frozen].astype(np.float64))
+    assert np.array_equal(host(s2)[frozen], host(fw["scale"])[frozen])
+    if momentum:
+        np.testing.assert_allclose(host(mw), mwn, rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(host(ms), msn, rtol=2e-6, atol=1e-12)
+        assert np.array_equal(host(mw)[frozen], mom_w0[frozen].astype(np.float64))
+    # gradients are optional outputs of the fused call
+    w3, s3 = wd_t.clone(), fw["scale"].clone()
+    L = ef.lib()
+    ws = torch.empty(L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, 1, 0), dtype=torch.uint8, device="cuda")
+    from paper_2411_11038_amd.binding import SgdStep
+    st = SgdStep(0.05, 0.01, 0.0, wd, None, None)
+    import ctypes
+    rc = L.efqat_linear_bwd_sgd(dyd.data_ptr(), 1, 0, T, c_in, c_out, fx["codes"].data_ptr(), fx["clip_bits"].data_ptr(),
+                                xd.data_ptr(), 1, fx["scale"].data_ptr(), fx["zero_point"].data_ptr(),
+                                fw["codes"].data_ptr(), fw["clip_bits"].data_ptr(), w3.data_ptr(), s3.data_ptr(),
+                                idx.data_ptr(), k, fused["dx"].data_ptr(), 1, None, 0, None, fused["ds_x"].data_ptr(),
+                                fused["dz_x"].data_ptr(), ctypes.byref(st), ws.data_ptr(), ws.numel(), None)
+    torch.cuda.synchronize()
+    assert rc == 0
+    if not momentum:
+        assert torch.equal(w3, w2) and torch.equal(s3, s2)
+
+
+def test_conv_bwd_fused_sgd_step():
+    N, H, Wd, c_in, c_out, kh, kw = 2, 7, 6, 16, 24, 3, 3
+    X, W, dY = synth.conv_layer(5200, N, H, Wd, c_in, c_out, kh, kw, 1, 1, act_dtype="bf16")
+    xd, wd_t, dyd = act_tensor(X, "bf16"), dev(W), act_tensor(dY, "bf16")
+    fx = ef.fakequant_fwd(xd.view(-1, c_in), ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=True)
+    fw = ef.fakequant_fwd(wd_t.view(c_out, -1), ef.W_PER_ROW_SYM, 4, init_minmax=True)
+    k = ef.k_from_ratio(c_out, 1, 3)
+    idx, _ = ef.channel_select(wd_t, k)
+    xc, wc = fx["codes"].view(X.shape), fw["codes"].view(W.shape)
+    args = (dyd, xc, fx["clip_bits"], xd, fx["scale"], fx["zero_point"], wc, fw["clip_bits"])
+    plain = ef.conv_bwd(*args, wd_t, fw["scale"], idx, stride=1, pad=1)
+    w2, s2 = wd_t.clone(), fw["scale"].clone()
+    mom_w0 = synth.normal(78, 5, W.shape, std=0.01).astype(np.float32)
+    mom_s0 = synth.normal(78, 6, (c_out,), std=0.01).astype(np.float32)
+    mw, ms = dev(mom_w0), dev(mom_s0)
+    fused = ef.conv_bwd(*args, w2, s2, idx, stride=1, pad=1,
+                        sgd=dict(lr_w=0.05, lr_s=0.01, momentum=0.9, weight_decay=1e-3, mom_w=mw, mom_s=ms))
+    torch.cuda.synchronize()
+    for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
+        assert torch.equal(plain[key], fused[key]), key
+    ii = idx.cpu().numpy().astype(np.int64)
+    Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
+                                         0.9, 1e-3, mom_w0, mom_s0)
+    np.testing.assert_allclose(host(w2), Wn, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(host(s2), Sn, rtol=2e-6, atol=1e-12)
+    np.testing.assert_allclose(host(mw), mwn, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(host(ms), msn, rtol=2e-6, atol=1e-12)
+
+
 def test_linear_bwd_dx_independent_of_fraction_and_fp32_dx():
     X, W, dY = synth.linear_layer(77, 260, 136, 200, act_dtype="bf16")
     outs = []

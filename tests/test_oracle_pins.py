@@ -190,6 +190,33 @@ def test_bias_grad_is_gradient_of_bias():
     np.testing.assert_allclose(orc.bias_grad(d4), d4.sum(axis=(0, 1, 2)), rtol=1e-13)
 
 
+@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 0.0), (0.9, 5e-4), (0.0, 1e-2)])
+def test_sgd_step_rows_matches_torch_sgd_on_the_unfrozen_rows(momentum, wd):
+    # torch.optim.SGD over parameters that hold only the unfrozen rows (two steps, so the momentum buffer is used);
+    # frozen rows must come back untouched
+    rng = np.random.default_rng(11)
+    W = rng.normal(size=(9, 5)); S = rng.uniform(0.5, 1.5, size=9)
+    idx = np.array([1, 4, 7])
+    pw = torch.tensor(W[idx], dtype=torch.float64, requires_grad=True)
+    ps = torch.tensor(S[idx], dtype=torch.float64, requires_grad=True)
+    opt_w = torch.optim.SGD([pw], lr=0.1, momentum=momentum, weight_decay=wd)
+    opt_s = torch.optim.SGD([ps], lr=0.01, momentum=momentum)
+    mw = np.zeros_like(W) if momentum else None
+    ms = np.zeros_like(S) if momentum else None
+    Wc, Sc = W.copy(), S.copy()
+    for step in range(2):
+        dW = rng.normal(size=(3, 5)); dS = rng.normal(size=3)
+        pw.grad = torch.tensor(dW); ps.grad = torch.tensor(dS)
+        opt_w.step(); opt_s.step()
+        Wc, Sc, mw, ms = orc.sgd_step_rows(Wc, Sc, idx, dW, dS, 0.1, 0.01, momentum, wd, mw, ms)
+    np.testing.assert_allclose(Wc[idx], pw.detach().numpy(), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(Sc[idx], ps.detach().numpy(), rtol=1e-13, atol=1e-15)
+    frozen = np.setdiff1d(np.arange(9), idx)
+    assert np.array_equal(Wc[frozen], W[frozen]) and np.array_equal(Sc[frozen], S[frozen])
+    if momentum:
+        assert not mw[frozen].any() and not ms[frozen].any()
+
+
 def test_ops_model_golden():
     rows = _rows("ops_bound.txt")
     for r in rows:
