@@ -381,6 +381,8 @@ struct BwdPlan {
   bool need_sel;   // gathered dY^T rows materialised (token-major dY, or fp32 / unaligned channel-major)
   bool tn;         // dW product straight from token-major dY columns and the uint8 codes (no transposed copies)
   bool tn_direct;  // ... with dY itself as the A operand (all channels selected)
+  bool cmx;        // channel-major dY: dX product straight from dY [C_out][T] and the int8 weight codes
+  bool rdw;        // channel-major dY: dW product from the selected rows of dY and the uint8 codes, nothing staged
   bool cdw;        // convolution dW product with the im2col gather of the codes inside the tile loads
   bool cdx;        // convolution dX product with the im2col gather inside the tile loads (no im2col matrix)
   bool dx8;        // dX product with the weight operand read from the int8 codes (no bf16 W_q^T copy)
@@ -402,6 +404,9 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.cdw = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && im2col && cg && (c_in % 128) == 0;
   p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && ((!im2col && (c_in % 16) == 0) || p.cdw);
   p.tn_direct = p.tn && direct_tok && k == c_out;
+  p.rdw = k > 0 && direct_rows && !im2col && (c_in % 16) == 0;
+  p.cmx = direct_rows && !im2col && taps == 1 && (c_in % 16) == 0;
+  if (p.cmx) p.need_dyn = false;
   p.kp = round_up(k, 8);
   p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
   // stride-1 convolutions whose channel pitch is a multiple of the 64-element K stage gather dY in the tile loads
@@ -410,20 +415,23 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.dx8 = false; p.dx8_tile = 0;
   // Large products (the planner's 256 x 256 case) with a bf16 token-major dY read the weight operand straight
   // from the int8 codes: same speed as the bf16 kernel on these shapes, and no transposed bf16 copy of W_q.
-  if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16 &&
+  if (p.cmx) {
+    p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, false);
+    p.dx8 = true; p.dx8_tile = p.plan_dx.tile;
+  } else if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16 &&
       (p.plan_dx.tile == 256 || g_opt_dx_kernel == EFQAT_DX_KERNEL_INT8)) {
     p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
     p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
   }
-  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !p.tn, !p.cdw) : GemmPlan{128, 1, 0, 0};
+  p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !(p.tn || p.rdw), !p.cdw) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
   p.b_colA = (im2col && !p.cdx) ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
   p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
-  p.b_xcT = (k > 0 && !p.tn) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
+  p.b_xcT = (k > 0 && !p.tn && !p.rdw) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
-  p.b_zero = (p.tn || p.dx8 || p.cdx) ? 256 : 0; cv.take(p.b_zero);
+  p.b_zero = (p.tn || p.dx8 || p.cdx || p.rdw) ? 256 : 0; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -463,7 +471,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     TransposeExtra ex{};
     ex.z_in = c_in; ex.z_out = p.ldc;                 // one launch for all taps
     rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
-                                   p.Kx, 0, p.ldc, st, (p.tn || p.cdx) ? (uint32_t*)zero_page : nullptr, taps, &ex);
+                                   p.Kx, 0, p.ldc, st, (p.tn || p.cdx || p.rdw) ? (uint32_t*)zero_page : nullptr, taps, &ex);
     if (rc) return rc;
   }
 
@@ -503,7 +511,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
   if (p.dx8) {
     if (((uintptr_t)io.w_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
-    rc = launch_gemm_dx8(dy_tok, c_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out, p.dx8_tile, epi, st);
+    if (p.cmx)
+      rc = launch_gemm_dx8_cm((const bf16_t*)io.dy, T_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out,
+                              p.dx8_tile, epi, st);
+    else
+      rc = launch_gemm_dx8(dy_tok, c_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out, p.dx8_tile, epi, st);
   } else if (p.cdx) {
     const ConvDxMap cm{cg->H, cg->W, cg->Ho, cg->Wo, cg->KW, cg->pad, zero_page};
     rc = launch_gemm_nt_conv_dx(dy_tok, p.ldc, wqT, p.Kx, p.Mx, c_in, p.Kx, cm, p.plan_dx, epi, st);
@@ -543,6 +555,12 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
       rc = launch_gemm_tn(At, ldat, acols, io.x_codes, c_in, c_in, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
                           part_dw, st);
     }
+    if (rc) return rc;
+  } else if (p.rdw) {
+    // ---- channel-major dY: the selected rows are gathered by the tile loads, the codes are read as they lie
+    if (((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
+    rc = launch_gemm_dw_rows((const bf16_t*)io.dy, T_out, io.idx, io.x_codes, c_in, zero_page, io.z_x, io.k, p.Nw,
+                             T_out, p.plan_dw, part_dw, st);
     if (rc) return rc;
   } else {
   // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16

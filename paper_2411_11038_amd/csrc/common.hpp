@@ -143,6 +143,17 @@ int launch_gemm_nt_conv_dx(const bf16_t* dy_tok, int64_t ldc, const bf16_t* wqT,
 int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
                     const void* zero_page, int64_t M, int64_t N, int64_t K, int tile, const GemmEpilogueDx& epi,
                     hipStream_t stream);
+// The same product for a channel-major dY [C_out][lda] (lda >= M = T, T % 8 == 0): both operands have the contraction
+// index C_out as their row and are transposed by the LDS reads; no copy of dY or W_q is made.
+int launch_gemm_dx8_cm(const bf16_t* dy_cm, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
+                       const void* zero_page, int64_t M, int64_t N, int64_t K, int tile, const GemmEpilogueDx& epi,
+                       hipStream_t stream);
+// dW product for a channel-major bf16 dY [C_out][lda] (lda >= K = T, K % 8 == 0): row m of the A operand is row
+// idx[m] of dY, read through the index list in the tile loads; B = the uint8 codes [K][ldb] as they lie.
+//   out[s][m][n] = sum over the K-slice s of dY[idx[m]][t] * (codes[t][n] - round(z_x)),  plan.tile 256 or 128.
+int launch_gemm_dw_rows(const bf16_t* dy_cm, int64_t lda, const int32_t* idx, const uint8_t* x_codes, int64_t ldb,
+                        const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                        float* out_partial, hipStream_t stream);
 // event timing hooks shared by the product kernels (which: 0 dX, 1 dW, 2 forward)
 bool gemm_prof_begin(int which, hipStream_t st, int* slot);
 void gemm_prof_end(int which, hipStream_t st, int slot);

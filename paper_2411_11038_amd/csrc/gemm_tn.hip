@@ -413,7 +413,14 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
 // weight operand costs half the bytes in L2, L1 and LDS (a 256 x 256 stage is 48 KB instead of 64 KB), and the
 // transposed bf16 matrix is never written.  Same wavefront grid (1 x 4), pipeline and load discipline as k_gemm_tn;
 // the epilogue is the fused straight-through / dS_x / dZ_x epilogue shared with the K-contiguous kernel.
-template <int T>
+//
+// The same kernel in DW mode is the weight-gradient product for a channel-major dY [C_out][T] (Eq. 5 right,
+// restricted):  dW_q[m][i] = sum_t dY[idx[m]][t] * (code[t][i] - Z_x).  The A rows are the selected channels, read
+// through the index list in the tile loads (frozen channels are never touched), B = the uint8 activation codes as
+// they lie ([T][C_in]; the contraction index is the row), converted as in k_gemm_tn; split-K, raw fp32 partial tiles.
+// ATN: the A operand has the contraction index as its row ([K][lda], K-major like B) and is read with
+// ds_read_b64_tr_b16 as in k_gemm_tn; otherwise it is K-contiguous ([M][lda]).
+template <int T, bool ATN = false>
 struct Dx8Cfg {
   static constexpr int BM = T, BN = T;
   static constexpr int WGM = 1, WGN = 4;
@@ -421,6 +428,7 @@ struct Dx8Cfg {
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int RB = BN;                              // bytes per LDS row of B (one channel c)
   static constexpr int CB = RB / 16;
+  static constexpr int RA = 2 * BM, CA = RA / 16;            // ATN: bytes / chunks per LDS row of A (one K index)
   static constexpr int A_G = BM / 8 / 4, B_G = 64 * RB / 1024 / 4;   // 1-KiB loads per wave and stage
   static constexpr int LDS_A = BM * 128, LDS_B = 64 * RB, LDS_S = 4 * 256;   // scales: one copy per wavefront
   static constexpr int LDS_STAGE = LDS_A + LDS_B + LDS_S;
@@ -429,6 +437,7 @@ struct Dx8Cfg {
   static constexpr int LDS_BYTES = LDS_LOOP > LDS_EPI ? LDS_LOOP : LDS_EPI;
   static constexpr int KSH = RB == 256 ? 0 : 1;
   __device__ static __forceinline__ int swz_a(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+  __device__ static __forceinline__ int swz_atn(int c, int k) { return c ^ (4 * (k & 3)); }
   __device__ static __forceinline__ int swz_b(int c, int k) { return c ^ (2 * ((k >> KSH) & (CB / 2 - 1))); }
 };
 
@@ -440,15 +449,17 @@ __device__ __forceinline__ void dma4(const char* src, char* lds_dst) {
 }
 
 struct GemmDx8Args {
-  GemmArgs g;              // A = dY, B = weight codes, M = T, N = C_in, K = C_out, fused dX epilogue fields
+  int a_cols;              // ATN: readable width of A (multiple of 8)
+  GemmArgs g;              // dX: A = dY, B = weight codes, M = T, N = C_in, K = C_out, fused dX epilogue fields
+                           // dW: A = dY channel-major with a_rows = idx, B = activation codes, M = k, N = C_in, K = T
   int b_cols;              // readable width of B (multiple of 16)
   const void* zero_page;   // >= 256 zero bytes
 };
 
-template <int T>
+template <int T, bool DW = false, bool ATN = false>
 __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  using C = Dx8Cfg<T>;
+  using C = Dx8Cfg<T, ATN>;
   const GemmArgs& g = ga.g;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -467,7 +478,10 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   const int tn = (pid % per_group) / gsize;
   const int m0 = tm * C::BM, n0 = tn * C::BN;
 
-  const int K = g.K;
+  // K range of this block: everything for dX, one split-K slice for dW (K below is the length of the slice)
+  const int k_begin = DW ? blockIdx.y * g.k_per_split : 0;
+  const int k_end_ = DW ? ((k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K) : g.K;
+  const int K = k_end_ > k_begin ? k_end_ - k_begin : 0;
   const int nk = (K + 63) / 64;
   const int nfull = K / 64;
   const char* zero = (const char*)ga.zero_page;
@@ -482,22 +496,36 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   const char* a_ptr[C::A_G];
   const char* b_ptr[C::B_G];
   uint32_t b_st[C::B_G];
+  uint32_t a_st[C::A_G];                                // per-stage pointer step of the A slots
+  constexpr int RPIA = 1024 / C::RA;                    // ATN: K rows per 1-KiB load
+  const int atn_r0 = lane / C::CA;
 #pragma unroll
   for (int j = 0; j < C::A_G; ++j) {
-    int gm = m0 + (wave + 4 * j) * 8 + a_lrow;
-    gm = gm < g.M ? gm : g.M - 1;                       // rows past the edge re-read a valid row (outputs discarded)
-    a_ptr[j] = (const char*)g.A + ((int64_t)gm * g.lda) * 2 + a_lch * 16;
+    if constexpr (ATN) {
+      // slot j covers the K rows (wave + 4 j) * RPIA .. of a stage; lane l lands in row l / CA, physical chunk l % CA
+      const int kr = (wave + 4 * j) * RPIA + atn_r0;
+      const int col = m0 + C::swz_atn(lane % C::CA, kr) * 8;
+      const bool on = col < ga.a_cols;
+      a_ptr[j] = on ? (const char*)g.A + ((int64_t)(k_begin + kr) * g.lda + col) * 2 : zero;
+      a_st[j] = on ? (uint32_t)(g.lda * 128) : 0u;
+    } else {
+      int gm = m0 + (wave + 4 * j) * 8 + a_lrow;
+      gm = gm < g.M ? gm : g.M - 1;                     // rows past the edge re-read a valid row (outputs discarded)
+      const int64_t src_row = (DW && g.a_rows) ? (int64_t)g.a_rows[gm] : (int64_t)gm;
+      a_ptr[j] = (const char*)g.A + (src_row * g.lda + k_begin) * 2 + a_lch * 16;
+      a_st[j] = 128u;
+    }
   }
 #pragma unroll
   for (int j = 0; j < C::B_G; ++j) {
     const int kr = (wave + 4 * j) * RPIB + b_r0;
     const int col = n0 + C::swz_b(lane % C::CB, kr) * 16;
     const bool on = col < ga.b_cols;
-    b_ptr[j] = on ? (const char*)g.B + (int64_t)kr * g.ldb + col : zero;
+    b_ptr[j] = on ? (const char*)g.B + (int64_t)(k_begin + kr) * g.ldb + col : zero;
     b_st[j] = on ? (uint32_t)(g.ldb * 64) : 0u;
   }
-  const char* s_ptr = (const char*)g.s_w + lane * 4;   // the scale of channel kt * 64 + lane
-  constexpr int LPS = C::A_G + C::B_G + 1;
+  const char* s_ptr = DW ? zero : (const char*)g.s_w + lane * 4;   // dX: the scale of channel kt * 64 + lane
+  constexpr int LPS = C::A_G + C::B_G + (DW ? 0 : 1);
   using Checked = std::integral_constant<bool, true>;
   using Unchecked = std::integral_constant<bool, false>;
   auto issue_range = [&](auto checked, int kt, int buf, int t0, int t1) {
@@ -510,10 +538,14 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
       if (t < C::A_G) {
         const char* src = a_ptr[t];
         if constexpr (decltype(checked)::value) {
-          if (kb + a_lch * 8 >= K) src = zero;          // K is a multiple of 8: a chunk is all in or all out
+          if constexpr (ATN) {
+            if (kb + (wave + 4 * t) * RPIA + atn_r0 >= K) src = zero;
+          } else {
+            if (kb + a_lch * 8 >= K) src = zero;        // K is a multiple of 8: a chunk is all in or all out
+          }
         }
         dma16(src, sa + (wave + 4 * t) * 1024);
-        a_ptr[t] += 128;
+        a_ptr[t] += a_st[t];
       } else if (t < C::A_G + C::B_G) {
         const int u = t - C::A_G;
         const char* src = b_ptr[u];
@@ -558,27 +590,47 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   }
   typedef int intx4_t __attribute__((ext_vector_type(4)));
   intx4_t af[2][C::TM];
+  // ATN: four base addresses per LDS buffer for the transpose reads of A (see k_gemm_tn)
+  int atn_base[2][4];
+  if constexpr (ATN) {
+    const int h = q >> 1;
+    const int k = 8 * h + (s16 >> 2), kk = (s16 >> 2) & 3;
+    const int c0 = (mb >> 3) + ((s16 & 3) >> 1);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      atn_base[0][u] = k * C::RA + ((4 * (u ^ kk) + c0) << 4) + 8 * (s16 & 1);
+      atn_base[1][u] = atn_base[0][u] + C::LDS_STAGE;
+    }
+  }
   intx2_t braw[2][C::TN];
   float scf[2][8], mvf[2][8];                       // the 8 scales of a lane's K positions, and -128 * scale
   uint32_t bw[2][C::TN][4];                         // converted B fragments: 4 words of two bf16 each
   // LDS read number r of a sub-step: B codes, the scales, then the A fragments
-  constexpr int NRD = C::TN + 2 + C::TM;
+  constexpr int NSC = DW ? 0 : 2;                   // LDS reads of scales per sub-step
+  constexpr int NRD = C::TN + NSC + (ATN ? 2 : 1) * C::TM;
   auto lds_read = [&](auto bufc, int sub, int rb, int r) {
     constexpr int buf = decltype(bufc)::value;
     const char* st = smem + buf * C::LDS_STAGE;
     if (r < C::TN) {
       braw[rb][r] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
           (__attribute__((address_space(3))) intx2_t*)(smem + b_base[buf][r] + sub * 16 * C::RB));
-    } else if (r < C::TN + 2) {
+    } else if (r < C::TN + NSC) {
       const int hlf = r - C::TN;
       const float4 v = *reinterpret_cast<const float4*>(st + C::LDS_A + C::LDS_B + wave * 256 +
                                                         (16 * sub + 8 * fh + 4 * hlf) * 4);
       scf[rb][4 * hlf] = v.x; scf[rb][4 * hlf + 1] = v.y; scf[rb][4 * hlf + 2] = v.z; scf[rb][4 * hlf + 3] = v.w;
+    } else if constexpr (ATN) {
+      const int i = (r - C::TN - NSC) >> 1, hh = (r - C::TN - NSC) & 1;
+      const shortx4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4_t*)(
+          smem + atn_base[buf][i & 3] + (i >> 2) * 256 + hh * 4 * C::RA + sub * 16 * C::RA));
+      const intx2_t v2 = __builtin_bit_cast(intx2_t, v);
+      af[rb][i][2 * hh] = v2[0]; af[rb][i][2 * hh + 1] = v2[1];
     } else {
-      const int i = r - C::TN - 2;
+      const int i = r - C::TN - NSC;
       af[rb][i] = *reinterpret_cast<const intx4_t*>(st + C::swz_a(32 * i + fr, 2 * sub + fh));
     }
   };
+  const float zq = DW ? rintf(g.z_x[0]) : 0.0f;
   auto load_frags = [&](auto bufc, int sub, int rb) {
 #pragma unroll
     for (int r = 0; r < NRD; ++r) lds_read(bufc, sub, rb, r);
@@ -587,16 +639,23 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   // rounded once like the product itself.  Piece p of fragment j makes elements 2p and 2p + 1 (5 VALU operations).
   constexpr int NPIECE = 4 * C::TN;
   auto conv_offsets = [&](int rb) {
+    if constexpr (!DW) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) mvf[rb][t] = -128.0f * scf[rb][t];
+      for (int t = 0; t < 8; ++t) mvf[rb][t] = -128.0f * scf[rb][t];
+    }
   };
   auto conv_piece = [&](int rb, int piece) {
     const int j = piece >> 2, pp = piece & 3;
-    const uint32_t w = (uint32_t)braw[rb][j][pp >> 1] ^ 0x80808080u;
     const int sh = 16 * (pp & 1);
-    const float f0 = fmaf((float)((w >> sh) & 0xFFu), scf[rb][2 * pp], mvf[rb][2 * pp]);
-    const float f1 = fmaf((float)((w >> (sh + 8)) & 0xFFu), scf[rb][2 * pp + 1], mvf[rb][2 * pp + 1]);
-    bw[rb][j][pp] = pack_bf16x2(f0, f1);
+    if constexpr (DW) {                                // activation codes: (code - Z_x), exact in bf16
+      const uint32_t w = (uint32_t)braw[rb][j][pp >> 1];
+      bw[rb][j][pp] = pack_bf16x2((float)((w >> sh) & 0xFFu) - zq, (float)((w >> (sh + 8)) & 0xFFu) - zq);
+    } else {
+      const uint32_t w = (uint32_t)braw[rb][j][pp >> 1] ^ 0x80808080u;
+      const float f0 = fmaf((float)((w >> sh) & 0xFFu), scf[rb][2 * pp], mvf[rb][2 * pp]);
+      const float f1 = fmaf((float)((w >> (sh + 8)) & 0xFFu), scf[rb][2 * pp + 1], mvf[rb][2 * pp + 1]);
+      bw[rb][j][pp] = pack_bf16x2(f0, f1);
+    }
   };
   auto convert = [&](int rb) {
     conv_offsets(rb);
@@ -707,7 +766,22 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   }
   __syncthreads();
 
-  epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
+  if constexpr (DW) {
+    float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j) {
+        const int col = n0 + wn * C::WN + j * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * C::WM + i * 32 + 8 * (r >> 2) + 4 * fh + (r & 3);
+          if (row < g.M && col < g.N) out[(int64_t)row * g.N + col] = acc[i][j][r];
+        }
+      }
+  } else {
+    epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
+  }
 #endif
 }
 
@@ -752,23 +826,68 @@ int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* 
 }
 
 
-template <int T>
-static int launch_dx8_cfg(const GemmDx8Args& a, hipStream_t st) {
-  using C = Dx8Cfg<T>;
+template <int T, bool DW = false, bool ATN = false>
+static int launch_dx8_cfg(const GemmDx8Args& a, int split_k, hipStream_t st) {
+  using C = Dx8Cfg<T, ATN>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
-        hipSuccess)
+    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T, DW, ATN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            C::LDS_BYTES) != hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
   }
-  dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n));
+  dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
   int slot = 0;
-  const bool timed = gemm_prof_begin(0, st, &slot);
-  hipLaunchKernelGGL((k_gemm_dx8<T>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) gemm_prof_end(0, st, slot);
+  const bool timed = gemm_prof_begin(DW ? 1 : 0, st, &slot);
+  hipLaunchKernelGGL((k_gemm_dx8<T, DW, ATN>), grid, dim3(256), C::LDS_BYTES, st, a);
+  if (timed) gemm_prof_end(DW ? 1 : 0, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
+}
+
+int launch_gemm_dx8_cm(const bf16_t* dy_cm, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
+                       const void* zero_page, int64_t M, int64_t N, int64_t K, int tile, const GemmEpilogueDx& epi,
+                       hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (M % 8) || (lda % 8) || (ldb % 16) || (N % 16)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldb >= (1 << 24) || lda >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)dy_cm % 16) || ((uintptr_t)w_codes % 16) || ((uintptr_t)s_w % 4) || ((uintptr_t)zero_page % 256))
+    return EFQAT_ERR_ALIGNMENT;
+  GemmDx8Args a{};
+  a.g.A = dy_cm; a.g.lda = lda; a.g.B = w_codes; a.g.ldb = ldb;
+  a.g.M = (int)M; a.g.N = (int)N; a.g.K = (int)K;
+  a.g.s_w = s_w;
+  a.g.x_codes = epi.x_codes; a.g.x_clip = epi.x_clip; a.g.x = epi.x; a.g.x_dtype = epi.x_dtype;
+  a.g.s_x = epi.s_x; a.g.z_x = epi.z_x; a.g.dx = epi.dx; a.g.dx_dtype = epi.dx_dtype; a.g.partial = epi.partial;
+  a.g.epi_vec = gemm_epilogue_vec_ok(epi, N) ? 1 : 0;
+  a.g.tiles_m = (int)ceil_div(M, tile); a.g.tiles_n = (int)ceil_div(N, tile);
+  a.a_cols = (int)M; a.b_cols = (int)N;
+  a.zero_page = zero_page;
+  switch (tile) {
+    case 256: return launch_dx8_cfg<256, false, true>(a, 1, stream);
+    case 128: return launch_dx8_cfg<128, false, true>(a, 1, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
+  }
+}
+
+int launch_gemm_dw_rows(const bf16_t* dy_cm, int64_t lda, const int32_t* idx, const uint8_t* x_codes, int64_t ldb,
+                        const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
+                        float* out_partial, hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || (K % 8) || (lda % 8) || (ldb % 16) || (N % 16)) return EFQAT_ERR_BAD_SHAPE;
+  if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldb >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;
+  if (((uintptr_t)dy_cm % 16) || ((uintptr_t)x_codes % 16) || ((uintptr_t)zero_page % 256)) return EFQAT_ERR_ALIGNMENT;
+  GemmDx8Args a{};
+  a.g.A = dy_cm; a.g.lda = lda; a.g.a_rows = idx; a.g.B = x_codes; a.g.ldb = ldb;
+  a.g.M = (int)M; a.g.N = (int)N; a.g.K = (int)K;
+  a.g.k_per_split = (int)(ceil_div(ceil_div(K, 64), plan.split_k) * 64);
+  a.g.z_x = z_x; a.g.out = out_partial;
+  a.g.tiles_m = plan.tiles_m; a.g.tiles_n = plan.tiles_n;
+  a.b_cols = (int)N;
+  a.zero_page = zero_page;
+  switch (plan.tile) {
+    case 256: return launch_dx8_cfg<256, true>(a, plan.split_k, stream);
+    case 128: return launch_dx8_cfg<128, true>(a, plan.split_k, stream);
+    default: return EFQAT_ERR_BAD_SHAPE;
+  }
 }
 
 int launch_gemm_tn_conv(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* x_codes, const ConvDwMap& cm,
@@ -810,8 +929,8 @@ int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_
   a.b_cols = (int)N;
   a.zero_page = zero_page;
   switch (tile) {
-    case 256: return launch_dx8_cfg<256>(a, stream);
-    case 128: return launch_dx8_cfg<128>(a, stream);
+    case 256: return launch_dx8_cfg<256>(a, 1, stream);
+    case 128: return launch_dx8_cfg<128>(a, 1, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }

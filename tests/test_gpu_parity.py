@@ -261,6 +261,13 @@ LIN_CASES = [
     (333, 272, 200, "f32", 8, 8, 0.7, (1, 1), 0, True),
     (70, 16, 24, "bf16", 8, 8, 1.0, (1, 3), 0, False),
     (2048, 512, 640, "bf16", 8, 8, 0.8, (1, 1), 0, False),        # several 256-wide tiles, split-K
+    # channel-major bf16 dY, T % 8 == 0, c_in % 16 == 0: rows idx of dY gathered by the dW kernel's tile loads,
+    # activation operand read from the uint8 codes as they lie
+    (304, 208, 136, "bf16", 8, 4, 0.7, (1, 4), 1, False),         # tails in M (k = 34), N and K (304 = 4 * 64 + 48)
+    (304, 208, 136, "bf16", 8, 8, 0.8, (1, 2), 1, True),
+    (72, 16, 24, "bf16", 8, 8, 1.0, (1, 3), 1, False),
+    (2048, 512, 640, "bf16", 8, 8, 0.8, (1, 1), 1, False),        # every channel; several tiles; split-K
+    (1000, 768, 1096, "bf16", 8, 8, 0.8, (1, 20), 1, False),      # k = 54 of 1096
 ]
 
 
