@@ -217,7 +217,7 @@ def main():
     roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=achieved / PEAK_BF16_TFLOPS,
                     traffic=DX_KERNEL_TRAFFIC_BYTES.get((args.workload, args.dy_layout)),
-                    kernel="k_gemm_nt<dX epilogue>", algorithmic_flops_per_launch=dx_flops,
+                    kernel="dX product with fused epilogue (k_gemm_kk / k_gemm_nt / k_gemm_dx8 by shape)", algorithmic_flops_per_launch=dx_flops,
                     avg_kernel_ms=dx_avg_s * 1e3, launches=int(dx_n),
                     dw_kernel_avg_ms=(dw_ms / dw_n) if dw_n else None)
 

@@ -164,12 +164,16 @@ int efqat_bias_grad(const void* dy, int dy_dtype, int dy_layout, int64_t T, int6
  * the library's only state).  EFQAT_OPT_DX_KERNEL chooses the kernel of the dX product
  * (Eq. 5 left) of efqat_linear_bwd where both apply (bf16 token-major dY, C_out % 8 == 0,
  * C_in % 16 == 0): AUTO picks by problem size, BF16 always stages a bf16 copy of W_q^T, INT8
- * always reads the weight operand from the int8 codes.  All choices give identical results.
- * Changes the workspace size: query it after setting the option. */
+ * always reads the weight operand from the int8 codes.  BF16_PINNED (any linear layer, and
+ * convolutions whose dX product runs on a staged im2col matrix) stages the bf16 copy and always
+ * uses the 192 x 192 kernel with the hand-pinned instruction order, which AUTO and BF16 take
+ * only where the planner picks that tile.  All choices give the same results up to the order
+ * of the fp32 sums.  Changes the workspace size: query it after setting the option. */
 #define EFQAT_OPT_DX_KERNEL 1
 #define EFQAT_DX_KERNEL_AUTO 0
 #define EFQAT_DX_KERNEL_BF16 1
 #define EFQAT_DX_KERNEL_INT8 2
+#define EFQAT_DX_KERNEL_BF16_PINNED 3
 int efqat_set_option(int option, int value);
 
 /* ------------------------------------------------------------------ linear backward

@@ -226,7 +226,7 @@ def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, 
     return idx, kpl
 
 
-OPT_DX_KERNEL, DX_KERNEL_AUTO, DX_KERNEL_BF16, DX_KERNEL_INT8 = 1, 0, 1, 2
+OPT_DX_KERNEL, DX_KERNEL_AUTO, DX_KERNEL_BF16, DX_KERNEL_INT8, DX_KERNEL_BF16_PINNED = 1, 0, 1, 2, 3
 
 
 def set_option(option: int, value: int):

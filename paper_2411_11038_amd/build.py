@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libefqat.so")
-SOURCES = ["api.hip", "fakequant.hip", "select.hip", "gemm.hip", "gemm_tn.hip", "bwd.hip", "fwd.hip", "bias.hip"]
+SOURCES = ["api.hip", "fakequant.hip", "select.hip", "gemm.hip", "gemm_tn.hip", "gemm_kk.hip", "bwd.hip", "fwd.hip", "bias.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

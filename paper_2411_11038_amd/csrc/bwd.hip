@@ -386,6 +386,7 @@ struct BwdPlan {
   bool cdw;        // convolution dW product with the im2col gather of the codes inside the tile loads
   bool cdx;        // convolution dX product with the im2col gather inside the tile loads (no im2col matrix)
   bool dx8;        // dX product with the weight operand read from the int8 codes (no bf16 W_q^T copy)
+  bool kk;         // dX product from the bf16 copies by the 192 x 192 kernel with the pinned instruction order
   int dx8_tile;
   int64_t kp;      // k rounded up to 8 (pitch of the compacted dY columns)
   GemmPlan plan_dx, plan_dw;
@@ -405,7 +406,7 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && ((!im2col && (c_in % 16) == 0) || p.cdw);
   p.tn_direct = p.tn && direct_tok && k == c_out;
   p.rdw = k > 0 && direct_rows && !im2col && (c_in % 16) == 0;
-  p.cmx = direct_rows && !im2col && taps == 1 && (c_in % 16) == 0;
+  p.cmx = direct_rows && !im2col && taps == 1 && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16_PINNED;
   if (p.cmx) p.need_dyn = false;
   p.kp = round_up(k, 8);
   p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
@@ -418,11 +419,17 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   if (p.cmx) {
     p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, false);
     p.dx8 = true; p.dx8_tile = p.plan_dx.tile;
+  } else if (g_opt_dx_kernel == EFQAT_DX_KERNEL_BF16_PINNED) {
+    if (!p.cdx) {
+      p.plan_dx.tile = 192; p.plan_dx.split_k = 1;
+      p.plan_dx.tiles_m = (int)ceil_div(p.Mx, 192); p.plan_dx.tiles_n = (int)ceil_div(c_in, 192);
+    }
   } else if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16 &&
       (p.plan_dx.tile == 256 || g_opt_dx_kernel == EFQAT_DX_KERNEL_INT8)) {
     p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
     p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
   }
+  p.kk = !p.dx8 && !p.cdx && p.plan_dx.tile == 192;
   p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !(p.tn || p.rdw), !p.cdw) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
@@ -431,7 +438,7 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
   p.b_xcT = (k > 0 && !p.tn && !p.rdw) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
-  p.b_zero = (p.tn || p.dx8 || p.cdx || p.rdw) ? 256 : 0; cv.take(p.b_zero);
+  p.b_zero = (p.tn || p.dx8 || p.cdx || p.rdw || p.kk) ? 256 : 0; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -471,7 +478,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     TransposeExtra ex{};
     ex.z_in = c_in; ex.z_out = p.ldc;                 // one launch for all taps
     rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
-                                   p.Kx, 0, p.ldc, st, (p.tn || p.cdx || p.rdw) ? (uint32_t*)zero_page : nullptr, taps, &ex);
+                                   p.Kx, 0, p.ldc, st, p.b_zero ? (uint32_t*)zero_page : nullptr, taps, &ex);
     if (rc) return rc;
   }
 
@@ -519,6 +526,8 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   } else if (p.cdx) {
     const ConvDxMap cm{cg->H, cg->W, cg->Ho, cg->Wo, cg->KW, cg->pad, zero_page};
     rc = launch_gemm_nt_conv_dx(dy_tok, p.ldc, wqT, p.Kx, p.Mx, c_in, p.Kx, cm, p.plan_dx, epi, st);
+  } else if (p.kk) {
+    rc = launch_gemm_kk(A, lda, wqT, p.Kx, zero_page, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
   } else {
     rc = launch_gemm_nt(A, lda, nullptr, wqT, p.Kx, p.Mx, c_in, p.Kx, p.plan_dx, nullptr, &epi, st);
   }
@@ -640,8 +649,7 @@ using namespace efqat;
 
 extern "C" int efqat_set_option(int option, int value) {
   if (option != EFQAT_OPT_DX_KERNEL) return EFQAT_ERR_BAD_LAYOUT;
-  if (value != EFQAT_DX_KERNEL_AUTO && value != EFQAT_DX_KERNEL_BF16 && value != EFQAT_DX_KERNEL_INT8)
-    return EFQAT_ERR_BAD_LAYOUT;
+  if (value < EFQAT_DX_KERNEL_AUTO || value > EFQAT_DX_KERNEL_BF16_PINNED) return EFQAT_ERR_BAD_LAYOUT;
   g_opt_dx_kernel = value;
   return EFQAT_OK;
 }

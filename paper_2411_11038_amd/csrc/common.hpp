@@ -115,6 +115,12 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
                    int64_t M, int64_t N, int64_t K, const GemmPlan& plan, float* out_partial,
                    const GemmEpilogueDx* epi, hipStream_t stream);
 
+// The same product as launch_gemm_nt (no row gather) by the kernel with a hand-pinned instruction order:
+// plan.tile 256 or 192; A, B and zero_page (>= 256 zero bytes) 16-byte aligned.
+int launch_gemm_kk(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, const void* zero_page, int64_t M,
+                   int64_t N, int64_t K, const GemmPlan& plan, float* out_partial, const GemmEpilogueDx* epi,
+                   hipStream_t stream);
+
 // Weight-gradient product from token-major operands (no transposed copies):
 //   out[s][m][n] = sum over the K-slice s of A[t][m] * (B[t][n] - round(z_x)),  A bf16 [K][lda], B uint8 [K][ldb].
 // Columns >= a_cols / b_cols and rows >= K are taken as zero (read from zero_page: 256 zero bytes, 256-byte

@@ -17,13 +17,9 @@
 #include <type_traits>
 
 #include "gemm_epilogue.hpp"
+#include "lds_copy.hpp"
 
 namespace efqat {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef short shortx4_t __attribute__((ext_vector_type(4)));
-typedef int intx2_t __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 struct GemmTnArgs {
   const bf16_t* A; int64_t lda;       // [K][lda], lda multiple of 8; columns >= a_cols are not read
@@ -63,18 +59,6 @@ struct TnCfg {
   __device__ static __forceinline__ int swz_a(int c, int k) { return c ^ (4 * (k & 3)); }
   __device__ static __forceinline__ int swz_b(int c, int k) { return c ^ (2 * ((k >> KSH) & (CB / 2 - 1))); }
 };
-
-// One wave-wide global -> LDS copy: lane l moves 16 bytes from its own src to lds_dst + 16 l.  Written as inline
-// assembly on purpose: the compiler models the LDS transpose-read builtins as possible LDS writes and would make
-// every one of them wait for all copies in flight (s_waitcnt vmcnt(0)), which serialises the pipeline.  The
-// kernel orders copies against reads itself (s_waitcnt vmcnt(0) + barrier once per stage).  M0 holds the LDS
-// destination; nothing else in this kernel uses M0, and volatile statements keep their order, so the copy always
-// sees the M0 value written just before it (s_nop: one wait state between an M0 write and its use).
-__device__ __forceinline__ void dma16(const char* src, char* lds_dst) {
-  const uint32_t m = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
-  asm volatile("s_mov_b32 m0, %0" ::"s"(m) : "m0");
-  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src));
-}
 
 template <int T, bool CONV = false>
 __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
@@ -440,13 +424,6 @@ struct Dx8Cfg {
   __device__ static __forceinline__ int swz_atn(int c, int k) { return c ^ (4 * (k & 3)); }
   __device__ static __forceinline__ int swz_b(int c, int k) { return c ^ (2 * ((k >> KSH) & (CB / 2 - 1))); }
 };
-
-// one wave-wide global -> LDS copy of 4 bytes per lane (the 64 scales of a stage)
-__device__ __forceinline__ void dma4(const char* src, char* lds_dst) {
-  const uint32_t m = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
-  asm volatile("s_mov_b32 m0, %0" ::"s"(m) : "m0");
-  asm volatile("s_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(src));
-}
 
 struct GemmDx8Args {
   int a_cols;              // ATN: readable width of A (multiple of 8)

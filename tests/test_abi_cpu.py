@@ -71,7 +71,8 @@ def test_argument_validation_needs_no_device():
     assert L.efqat_layer_select(fake, fake, 4, 2, None, fake, fake, fake, 8, None) == -6
     # options
     assert L.efqat_set_option(1, 2) == 0 and L.efqat_set_option(1, 0) == 0
-    assert L.efqat_set_option(1, 3) == -5 and L.efqat_set_option(9, 0) == -5
+    assert L.efqat_set_option(1, 3) == 0 and L.efqat_set_option(1, 0) == 0
+    assert L.efqat_set_option(1, 4) == -5 and L.efqat_set_option(1, -1) == -5 and L.efqat_set_option(9, 0) == -5
     # bias gradient
     assert L.efqat_bias_grad(None, 1, 0, 8, 8, fake, fake, 1 << 20, None) == -1
     assert L.efqat_bias_grad(fake, 1, 0, 0, 8, fake, fake, 1 << 20, None) == -2

@@ -319,6 +319,41 @@ def test_linear_bwd_int8_weight_operand(case):
     assert_max_err(host(out["dx"]), host(out2["dx"]), 8e-3, "dX int8-operand vs bf16-operand kernel")
 
 
+# dX product by the 192 x 192 kernel with the pinned instruction order and the three-stage LDS ring, forced through
+# the option hook (the planner takes it only for large products): ragged edges in every dimension, K from a single
+# 8-wide chunk to many stages, so that the pipelined loop, its drain and the zero-page tail all run
+PINNED_CASES = [
+    # T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter
+    (300, 208, 136, "bf16", 8, 4, 0.7, (1, 4), 0, False),     # 2 full stages + 8: drain only, tails in M and N
+    (70, 16, 8, "bf16", 8, 8, 1.0, (1, 2), 0, False),         # one chunk of K
+    (129, 144, 64, "bf16", 8, 8, 0.7, (0, 1), 0, False),      # exactly one stage, r = 0
+    (192, 192, 192, "bf16", 8, 8, 0.8, (1, 4), 0, False),     # one exact tile, three stages
+    (260, 200, 448, "bf16", 8, 8, 0.8, (1, 20), 0, False),    # seven stages: one trip of the pinned loop + drain
+    (517, 392, 1096, "bf16", 8, 8, 0.8, (1, 8), 0, True),     # 17 stages + tail of 8; several tiles
+    (400, 70, 645, "f32", 8, 4, 0.7, (1, 3), 0, False),       # nothing a multiple of 8: staged dY, scalar epilogue
+    (520, 208, 840, "bf16", 8, 8, 0.8, (1, 4), 1, False),     # channel-major dY: transposed copy, then this kernel
+]
+
+
+@pytest.mark.parametrize("case", PINNED_CASES, ids=lambda c: "T%d_%dx%d_%s_r%d-%d_L%d" % (
+    c[0], c[1], c[2], c[3], c[7][0], c[7][1], c[8]))
+def test_linear_bwd_pinned_dx_kernel(case):
+    T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter = case
+    X, W, dY = synth.linear_layer(7000 + T + c_out, T, c_in, c_out, act_dtype=kind)
+    try:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16_PINNED)
+        out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout,
+                                                         scatter)
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16)
+        out2, *_ = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter)
+    finally:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
+    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+    # same operands, same bf16 rounding, fp32 accumulation in the same K order: only the epilogue's output rounding
+    # can differ, and not even that - the two kernels must agree exactly
+    assert np.array_equal(host(out["dx"]), host(out2["dx"]))
+
+
 @pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4)])
 @pytest.mark.parametrize("shape", [(300, 208, 136), (260, 70, 43)])
 def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
