@@ -487,6 +487,24 @@ CONV_CASES = [
 @pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "N%d_%dx%d_%d-%d_k%dx%d_s%dp%d_%s_L%d" % (
     c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8], c[9], c[13]))
 def test_conv_bwd_matches_oracle(case):
+    _conv_case(case)
+
+
+# strided convolutions stage an im2col matrix of dY; with the option set, that matrix is the A operand of the
+# 192 x 192 pinned-order kernel
+@pytest.mark.parametrize("case", [CONV_CASES[2], CONV_CASES[4], CONV_CASES[5], CONV_CASES[14]],
+                         ids=lambda c: "N%d_%dx%d_%d-%d_k%dx%d_s%dp%d_%s_L%d" % (
+                             c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8], c[9], c[13]))
+def test_conv_bwd_pinned_dx_kernel_on_im2col_matrix(case):
+    assert case[7] == 2
+    try:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16_PINNED)
+        _conv_case(case)
+    finally:
+        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
+
+
+def _conv_case(case):
     N, H, Wd, c_in, c_out, kh, kw, stride, pad, kind, w_bits, shrink, (num, den), layout, scatter = case
     X, W, dY = synth.conv_layer(4000 + H + c_in, N, H, Wd, c_in, c_out, kh, kw, stride, pad, act_dtype=kind)
     xd, wd = act_tensor(X, kind), dev(W)
