@@ -265,7 +265,15 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
     for (int64_t j = (int64_t)threadIdx.x * 4; j < ncols; j += 1024) {
       const float* p = part + m * ncols + j;
       float4 a = *reinterpret_cast<const float4*>(p);
-      for (int s = 1; s < S; ++s) {
+      int s = 1;
+      for (; s + 3 < S; s += 4) {                     // four slices in flight; summed in slice order as below
+        float4 b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const float4*>(p + (int64_t)(s + u) * slice);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { a.x += b[u].x; a.y += b[u].y; a.z += b[u].z; a.w += b[u].w; }
+      }
+      for (; s < S; ++s) {
         const float4 b = *reinterpret_cast<const float4*>(p + (int64_t)s * slice);
         a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
       }

@@ -2,6 +2,8 @@
 // All kernels are HBM-bound streaming passes built on 64-wide wavefront reductions.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace efqat {
 
 // ----------------------------------------------------------------------------------------------
@@ -86,6 +88,19 @@ __global__ __launch_bounds__(256) void k_act_qparams(const float* __restrict__ p
 }
 
 // ----------------------------------------------------------------------------------------------
+// round(x / s) as the round-to-nearest-even integer of the correctly rounded quotient.  x * (1/s) is within
+// 1.5 ulp of it, so the two round to the same integer unless x/s sits that close to a half-way point; only
+// then is the exact (slow) division needed (always for huge quotients, where the tolerance exceeds one half,
+// and for a scale so small that its reciprocal overflows).
+__device__ __forceinline__ float round_quotient(float x, float s, float inv_s) {
+  const float qf = x * inv_s;
+  float r = rintf(qf);
+  const float tol = 2.5e-7f * fabsf(qf);
+  if (!(0.5f - fabsf(qf - r) > tol) || !(inv_s < 3.0e38f)) r = rintf(__fdiv_rn(x, s));
+  return r;
+}
+
+// ----------------------------------------------------------------------------------------------
 // Eq. 1 / Eq. 3: codes + clip-mask bits (+ optional de-quantised bf16 values).
 // One wavefront handles one 512-element segment of one row per iteration; a lane owns 8
 // consecutive elements, four neighbouring lanes assemble one 32-bit mask word.
@@ -155,15 +170,7 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
     float dq[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      // The code is defined on the correctly rounded quotient x/s.  x * (1/s) is within 1.5 ulp of it, so the
-      // two round to the same integer unless x/s sits that close to a half-way point; only then is the exact
-      // (slow) division needed (always for huge quotients, where the tolerance exceeds one half, and for a
-      // scale so small that its reciprocal overflows).
-      const float qf = v[j] * inv_s;
-      float r = rintf(qf);
-      const float tol = 2.5e-7f * fabsf(qf);
-      if (!(0.5f - fabsf(qf - r) > tol) || !(inv_s < 3.0e38f)) r = rintf(__fdiv_rn(v[j], s));
-      const float c = r + z;                       // un-clamped code
+      const float c = round_quotient(v[j], s, inv_s) + z;   // un-clamped code
       const float cc = __builtin_amdgcn_fmed3f(c, lo, hi);
       const bool inr = (c == cc);                  // closed interval: a code on the bound is not clipped
       if (inr && (col0 + j < cols)) bits8 |= (1u << j);
@@ -198,6 +205,124 @@ __global__ __launch_bounds__(256) void k_quantize(const T* __restrict__ x, int64
   }
 }
 
+// Eq. 1 for a per-tensor quantizer whose rows are a whole number of 32-element mask words (cols % 32 == 0, aligned
+// pointers): the tensor is one flat run of 8-element chunks, codes and mask words are flat as well, so no lane idles
+// on a ragged segment and nothing is divided.  Each lane handles two chunks a grid-stride apart per iteration, both
+// loads issued before either is used.
+template <typename T>
+__global__ __launch_bounds__(256) void k_quantize_act_flat(const T* __restrict__ x, int64_t nchunks, int bits,
+                                                           const float* __restrict__ scale,
+                                                           const float* __restrict__ zp, uint8_t* __restrict__ codes,
+                                                           uint32_t* __restrict__ clip, bf16_t* __restrict__ xq) {
+  const int lane = threadIdx.x & 63;
+  const float hi = (float)((1 << bits) - 1);
+  const float s = scale[0];
+  const float z = rintf(zp[0]);
+  const float inv_s = __fdiv_rn(1.0f, s);
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  auto finish = [&](int64_t c, const float (&v)[8]) {
+    uint32_t bits8 = 0;
+    uint32_t cw[2] = {0u, 0u};
+    float dq[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float cu = round_quotient(v[j], s, inv_s) + z;
+      const float cc = __builtin_amdgcn_fmed3f(cu, 0.0f, hi);
+      if (cu == cc) bits8 |= (1u << j);
+      cw[j >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(cc, j & 3, cw[j >> 2]);
+      dq[j] = s * (cc - z);
+    }
+    *reinterpret_cast<uint2*>(codes + c * 8) = make_uint2(cw[0], cw[1]);
+    if (xq)
+      *reinterpret_cast<uint4*>(xq + c * 8) = make_uint4(pack_bf16x2(dq[0], dq[1]), pack_bf16x2(dq[2], dq[3]),
+                                                         pack_bf16x2(dq[4], dq[5]), pack_bf16x2(dq[6], dq[7]));
+    // chunks c .. c+3 of lanes 4m .. 4m+3 make one mask word (c of lane 4m is a multiple of 4: see the launch)
+    uint32_t word = bits8 << (8 * (lane & 3));
+    word |= __shfl_xor(word, 1, kWave);
+    word |= __shfl_xor(word, 2, kWave);
+    if ((lane & 3) == 0) clip[c >> 2] = word;
+  };
+  // the grid covers whole groups of four chunks: nchunks % 4 == 0 and the stride is a multiple of 4, so the four
+  // lanes of a mask word are in range together
+  int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; c + stride < nchunks; c += 2 * stride) {
+    float v0[8], v1[8];
+    load8<T>(x + c * 8, v0);
+    load8<T>(x + (c + stride) * 8, v1);
+    finish(c, v0);
+    finish(c + stride, v1);
+  }
+  if (c < nchunks) {
+    float v0[8];
+    load8<T>(x + c * 8, v0);
+    finish(c, v0);
+  }
+}
+
+// Eq. 4 + Eq. 3 with the row held in registers (weights, min/max initialisation, cols <= 8 * 64 * WPR * NIT,
+// cols % 32 == 0, aligned pointers): WPR wavefronts per row (1, or the 4 of a block when there are few rows) issue all
+// loads of the row at once, take the abs-max, write S_w[c] and quantize from the registers, so the row is read once
+// and the reads are not a chain of dependent round trips.
+template <int NIT, int WPR>
+__global__ __launch_bounds__(256) void k_quantize_w_row_init(const float* __restrict__ w, int64_t rows, int64_t cols,
+                                                             int bits, float* __restrict__ scale,
+                                                             int8_t* __restrict__ codes, uint32_t* __restrict__ clip) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = WPR == 4 ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
+  const int part = WPR == 4 ? wave : 0;               // which quarter of the row's chunks (interleaved by 64)
+  const bool on = row < rows;                         // WPR == 1: whole wavefronts beyond the last row idle
+  const float hi = (float)((1 << (bits - 1)) - 1), lo = -hi;
+  const int n8 = on ? (int)(cols >> 3) : 0;
+  const float* p = w + (on ? row : 0) * cols;
+  float v[NIT][8];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * WPR + part) * 64 + lane;
+    if (i < n8) load8<float>(p + (int64_t)i * 8, v[it]);
+  }
+  float m = 0.0f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    if ((it * WPR + part) * 64 + lane < n8) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(v[it][j]));
+    }
+  }
+  m = wave_max(m);
+  if (WPR == 4) {
+    __shared__ float s_m[4];
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+  }
+  float s = __fdiv_rn(m, hi);
+  if (!(s > 0.0f)) s = 1.0f;                          // all-zero row
+  if (on && lane == 0 && part == 0) scale[row] = s;
+  const float inv_s = __fdiv_rn(1.0f, s);
+  const int64_t wpr = cols >> 5;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int i = (it * WPR + part) * 64 + lane;
+    // n8 % 4 == 0: the four lanes of a mask word are in range together
+    if (i < n8) {
+      uint32_t bits8 = 0;
+      uint32_t cw[2] = {0u, 0u};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float cu = round_quotient(v[it][j], s, inv_s);
+        const float cc = __builtin_amdgcn_fmed3f(cu, lo, hi);
+        if (cu == cc) bits8 |= (1u << j);
+        cw[j >> 2] |= ((uint32_t)((int)cc & 0xFF)) << (8 * (j & 3));
+      }
+      *reinterpret_cast<uint2*>(codes + row * cols + (int64_t)i * 8) = make_uint2(cw[0], cw[1]);
+      uint32_t word = bits8 << (8 * (lane & 3));
+      word |= __shfl_xor(word, 1, kWave);
+      word |= __shfl_xor(word, 2, kWave);
+      if ((lane & 3) == 0) clip[row * wpr + (i >> 2)] = word;
+    }
+  }
+}
+
 // ----------------------------------------------------------------------------------------------
 static inline bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -221,10 +346,31 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
   const int64_t items = row_items ? rows : rows * ceil_div(cols, 512);
   int64_t blocks = ceil_div(items, 4);
   if (blocks > 256 * 32) blocks = 256 * 32;
-  if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
+  if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM && vec_row && (cols % 32) == 0) {
+    const int64_t nchunks = n / 8;
+    int64_t fb = ceil_div(nchunks, 512);             // two chunks per lane and iteration
+    if (fb > 256 * 16) fb = 256 * 16;
+    hipLaunchKernelGGL((k_quantize_act_flat<T>), dim3((unsigned)fb), dim3(256), 0, st, x, nchunks, bits, scale, zp,
+                       (uint8_t*)codes, clip, xq);
+  } else if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM, false>), dim3((unsigned)blocks), dim3(256), 0,
                        st, x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
-  else if (init_minmax)
+  else if (init_minmax && std::is_same<T, float>::value && vec_row && (cols % 32) == 0 && cols <= 8 * 64 * 8 && !xq) {
+    // few rows: a block per row, so that the chip still holds enough wavefronts to cover the memory latency
+    const bool wide = rows < 4096 && cols > 8 * 64;
+    const float* wf = (const float*)x;
+    int8_t* cd = (int8_t*)codes;
+    const int per_wave = (int)ceil_div(cols, 8 * 64 * (wide ? 4 : 1));     // 8-element chunks per lane
+    const dim3 grid((unsigned)(wide ? rows : ceil_div(rows, 4)));
+#define EFQAT_ROW_INIT(NIT, WPR) \
+  hipLaunchKernelGGL((k_quantize_w_row_init<NIT, WPR>), grid, dim3(256), 0, st, wf, rows, cols, bits, scale, cd, clip)
+    if (wide) {
+      if (per_wave <= 1) EFQAT_ROW_INIT(1, 4); else EFQAT_ROW_INIT(2, 4);
+    } else {
+      if (per_wave <= 2) EFQAT_ROW_INIT(2, 1); else if (per_wave <= 4) EFQAT_ROW_INIT(4, 1); else EFQAT_ROW_INIT(8, 1);
+    }
+#undef EFQAT_ROW_INIT
+  } else if (init_minmax)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, true>), dim3((unsigned)blocks), dim3(256), 0, st, x,
                        rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
   else
