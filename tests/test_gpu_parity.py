@@ -77,6 +77,24 @@ def test_fakequant_weight(rows, cols, bits, shrink):
         assert (~mask).any()
 
 
+# min/max initialisation of fp32 weights whose rows are whole mask words and at most 4096 long runs on the kernels that
+# hold the row in registers: one case per variant (chunks per lane x wavefronts per row), ragged row counts, a zero row
+@pytest.mark.parametrize("rows,cols", [(256, 256), (4097, 512), (5, 1024), (3, 2080), (7, 4096), (4100, 1056),
+                                       (4098, 2080), (4099, 4096), (2, 32)])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_fakequant_weight_minmax_rows_in_registers(rows, cols, bits):
+    W = synth.normal(31 + rows + cols, 1, (rows, cols), std=0.02).astype(np.float32)
+    W[rows // 2] = 0.0                                        # degenerate row
+    W[0, cols - 1] = 3.0 * np.abs(W[0]).max()                 # the row's maximum sits in its last element
+    sw = orc.weight_scale_minmax(W, bits)
+    codes, mask, _ = orc.fakequant_weight(W, sw, bits)
+    out = ef.fakequant_fwd(dev(W), ef.W_PER_ROW_SYM, bits, init_minmax=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["scale"].cpu().numpy(), sw)
+    assert np.array_equal(out["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(out["clip_bits"]), pack_mask(mask))
+
+
 def test_fakequant_conv_weight_ohwi():
     W = synth.normal(3, 1, (24, 3, 3, 16), std=0.05).astype(np.float32)
     sw = orc.weight_scale_minmax(W, 4)
