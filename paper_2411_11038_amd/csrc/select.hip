@@ -26,9 +26,9 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
 }
 
 // Exact Top-K by radix select, one 1024-thread block.  Scores are non-negative doubles, so their bit
-// patterns order like the values.  Eight passes over the bytes of the 64-bit key (most significant first)
-// find the key T of the k-th largest score and `need`, the number of scores equal to T that still belong to
-// the selection; then one ordered sweep writes every index whose score is > T, plus the first `need` indices
+// patterns order like the values.  Passes over 8-bit digits of the 64-bit key, from the highest bit on which
+// two keys differ downwards, find the key T of the k-th largest score and `need`, the number of scores equal
+// to T that still belong to the selection (as soon as at most 64 candidates remain they are ranked directly); then one ordered sweep writes every index whose score is > T, plus the first `need` indices
 // (ascending) whose score equals T: ties go to the lower index, output is ascending.  Integer counting only,
 // so the result does not depend on thread scheduling.
 __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
@@ -42,12 +42,14 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   __shared__ unsigned long long cand_key[64];
   __shared__ int cand_idx[64];
   __shared__ int s_bin_count, s_ncand;
+  __shared__ int scan_gt[12 * 16], scan_eq[12 * 16];   // KPT x wavefronts (cached case)
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   // Up to KPT keys per thread stay in registers for all passes (n <= 12288); longer inputs are re-read.
   constexpr int KPT = 12;
+  static_assert(KPT * 16 == 3 * 64, "the ordered output scans KPT x 16 counts with three per lane");
   unsigned long long keys[KPT];
   const bool cached = n <= (int64_t)KPT * 1024;
-  // Bytes on which all keys agree need no pass: find them from the OR and AND of all keys.
+  // Leading bits on which all keys agree need no pass: find them from the OR and AND of all keys.
   unsigned long long vor = 0ull, vand = ~0ull;
   if (cached) {
 #pragma unroll
@@ -75,30 +77,36 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   vor = 0ull; vand = ~0ull;
   for (int i = 0; i < 16; ++i) { vor |= s_or[i]; vand &= s_and[i]; }
   const unsigned long long diff = vor ^ vand;          // bits that differ between some two keys
-  int first_pass = 7;
-  while (first_pass > 0 && (diff >> (8 * first_pass)) == 0ull) --first_pass;
+  // The first 8-bit digit window ends at the highest bit on which two keys differ, so the first pass already
+  // spreads the keys over the bins; below it the windows follow each other down to bit 0 (the last one may be
+  // narrower).  `top` = first bit above the current window; the bits from `top` upwards are the prefix.
+  const int hb = diff ? 63 - __clzll((long long)diff) : 7;
+  int top = (hb >= 7 ? hb : 7) + 1;
   if (tid == 0) {
-    s_prefix = first_pass == 7 ? 0ull : (vor >> (8 * (first_pass + 1)));   // the shared high bytes
+    s_prefix = top >= 64 ? 0ull : (vor >> top);         // shared by all keys
     s_need = k;
     s_bin_count = 1 << 30;
   }
   for (int b = tid; b < 16 * 256; b += 1024) (&hist[0][0])[b] = 0u;
   __syncthreads();
-  for (int pass = first_pass; pass >= 0; --pass) {
+  while (top > 0) {
+    const int width = top < 8 ? top : 8;
+    const int shift = top - width;                      // the window is bits [shift, top)
+    const unsigned long long dmask = (1ull << width) - 1ull;
     const unsigned long long prefix = s_prefix;
     if (cached) {
 #pragma unroll
       for (int q = 0; q < KPT; ++q) {
         const int64_t i = (int64_t)q * 1024 + tid;
         const unsigned long long key = keys[q];
-        const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
-        if (i < n && match) atomicAdd(&hist[wv][(key >> (8 * pass)) & 255ull], 1u);
+        const bool match = (top >= 64) || ((key >> top) == prefix);
+        if (i < n && match) atomicAdd(&hist[wv][(key >> shift) & dmask], 1u);
       }
     } else {
       for (int64_t i = tid; i < n; i += 1024) {
         const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
-        const bool match = (pass == 7) || ((key >> (8 * (pass + 1))) == prefix);
-        if (match) atomicAdd(&hist[wv][(key >> (8 * pass)) & 255ull], 1u);
+        const bool match = (top >= 64) || ((key >> top) == prefix);
+        if (match) atomicAdd(&hist[wv][(key >> shift) & dmask], 1u);
       }
     }
     __syncthreads();
@@ -125,8 +133,8 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
         int d;
         if (a + h3 >= need) d = 3;
         else { a += h3; if (a + h2 >= need) d = 2; else { a += h2; if (a + h1 >= need) d = 1; else { a += h1; d = 0; } } }
-        s_need = need - a;                              // still to take among keys whose byte equals d
-        s_prefix = (prefix << 8) | (unsigned long long)(4 * lane + d);
+        s_need = need - a;                              // still to take among keys whose digit equals d
+        s_prefix = (prefix << width) | (unsigned long long)(4 * lane + d);
         s_bin_count = d == 3 ? h3 : d == 2 ? h2 : d == 1 ? h1 : h0;
       }
       if (lane == 0) s_ncand = 0;
@@ -134,13 +142,14 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
     __syncthreads();
     // Few keys left under the chosen prefix: finish at once instead of one pass per remaining byte.  The
     // candidates are gathered (in any order) and ranked by one wavefront under (key descending, index ascending).
-    if (pass > 0 && s_bin_count <= 64) {
+    top = shift;                                        // the prefix now reaches down to `shift`
+    if (top > 0 && s_bin_count <= 64) {
       const unsigned long long np = s_prefix;
       if (cached) {
 #pragma unroll
         for (int q = 0; q < KPT; ++q) {
           const int64_t i = (int64_t)q * 1024 + tid;
-          if (i < n && (keys[q] >> (8 * pass)) == np) {
+          if (i < n && (keys[q] >> top) == np) {
             const int slot = atomicAdd(&s_ncand, 1);
             cand_key[slot] = keys[q]; cand_idx[slot] = (int)i;
           }
@@ -148,7 +157,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
       } else {
         for (int64_t i = tid; i < n; i += 1024) {
           const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
-          if ((key >> (8 * pass)) == np) {
+          if ((key >> top) == np) {
             const int slot = atomicAdd(&s_ncand, 1);
             cand_key[slot] = key; cand_idx[slot] = (int)i;
           }
@@ -180,6 +189,48 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   }
   const unsigned long long T = s_prefix;
   const long long need = s_need;
+  if (cached) {
+    // Ordered output from the keys still in registers: key q of thread t sits at index 1024 q + t.  Every wavefront
+    // counts its "greater" and "equal" flags per chunk q, one wavefront turns the KPT x 16 counts into exclusive
+    // prefixes in index order, then every selected key knows its output position.  Two barriers, no global re-read.
+    const unsigned long long below = (1ull << lane) - 1ull;
+    unsigned long long bg[KPT], be[KPT];
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int64_t c = (int64_t)q * 1024 + tid;
+      bg[q] = __ballot(c < n && keys[q] > T);
+      be[q] = __ballot(c < n && keys[q] == T);
+      if (lane == 0) { scan_gt[q * 16 + wv] = __popcll(bg[q]); scan_eq[q * 16 + wv] = __popcll(be[q]); }
+    }
+    __syncthreads();
+    if (wv == 0) {
+      // exclusive scan of KPT * 16 = 192 counts (3 consecutive entries per lane), gt and eq
+      int g0 = scan_gt[3 * lane], g1 = scan_gt[3 * lane + 1], g2 = scan_gt[3 * lane + 2];
+      int e0 = scan_eq[3 * lane], e1 = scan_eq[3 * lane + 1], e2 = scan_eq[3 * lane + 2];
+      int gi = g0 + g1 + g2, ei = e0 + e1 + e2;        // inclusive prefix over lanes <= l
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int tg = __shfl_up(gi, o, kWave), te = __shfl_up(ei, o, kWave);
+        if (lane >= o) { gi += tg; ei += te; }
+      }
+      const int gx = gi - (g0 + g1 + g2), ex = ei - (e0 + e1 + e2);
+      scan_gt[3 * lane] = gx; scan_gt[3 * lane + 1] = gx + g0; scan_gt[3 * lane + 2] = gx + g0 + g1;
+      scan_eq[3 * lane] = ex; scan_eq[3 * lane + 1] = ex + e0; scan_eq[3 * lane + 2] = ex + e0 + e1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int64_t c = (int64_t)q * 1024 + tid;
+      const bool gt = (bg[q] >> lane) & 1ull, eq = (be[q] >> lane) & 1ull;
+      const long long gt_before = scan_gt[q * 16 + wv] + __popcll(bg[q] & below);
+      const long long eq_before = scan_eq[q * 16 + wv] + __popcll(be[q] & below);
+      if (gt || (eq && eq_before < need)) {
+        const long long pos = gt_before + (eq_before < need ? eq_before : need);
+        if (pos < k) idx[pos] = (int32_t)c;
+      }
+    }
+    return;
+  }
   if (tid == 0) { s_base_gt = 0; s_base_eq = 0; }
   __syncthreads();
   for (int64_t c0 = 0; c0 < n; c0 += 1024) {
