@@ -146,6 +146,24 @@ def test_network_select_cwpn():
         assert idx.cpu().numpy().tolist() == np.concatenate(ref).astype(np.int64).tolist() if k_total else True
 
 
+@pytest.mark.parametrize("n,spread_bits,k", [(1000, 9, 137), (3072, 3, 768), (5000, 20, 1), (14000, 13, 9000),
+                                             (700, 0, 50)])
+def test_topk_on_scores_that_differ_only_in_their_low_bits(n, spread_bits, k):
+    # keys whose highest differing bit is low: the first digit window is clamped to bits 0..7 or is followed by a
+    # narrower last window; many exact ties (every value occurs several times), which must go to the lower index.
+    # 14000 scores do not fit the registers of the block and take the re-reading path.
+    base = np.float64(0.8171).view(np.uint64)
+    r = synth.normal(900 + n, 0, (n,))
+    low = (np.abs(r) * 1e6).astype(np.uint64) % np.uint64(1 << spread_bits) if spread_bits else np.zeros(n, np.uint64)
+    scores = (base + low).view(np.float64)
+    flat = dev(scores); off_d = dev(np.array([0, n], dtype=np.int64))
+    idx, kpl = ef.network_select(flat, off_d, k)
+    torch.cuda.synchronize()
+    ref = orc.top_k_channels(scores, k)
+    assert kpl.cpu().numpy().tolist() == [k]
+    assert idx.cpu().numpy().tolist() == ref.astype(np.int64).tolist()
+
+
 def test_layer_select_lwpn():
     shapes = [(64, 32), (48, 100), (200, 8), (16, 16), (16, 16), (33, 7)]
     ws, scores, offs = [], [], [0]
