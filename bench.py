@@ -165,7 +165,7 @@ def cpu_baseline(layers, num, den, a_bits, w_bits):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by tokens; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the path would shard by tokens, one all-reduce of dW[idx] per layer); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
