@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_flat(const T* __restrict__
   }
 }
 
-// Eq. 4 + Eq. 3 with the row held in registers (weights, min/max initialisation, cols <= 8 * 64 * WPR * NIT,
+// Eq. 4 + Eq. 3 with the row held in registers (weights, min/max initialisation, cols <= 8 * 64 * WPR * NIT <= 16384,
 // cols % 32 == 0, aligned pointers): WPR wavefronts per row (1, or the 4 of a block when there are few rows) issue all
 // loads of the row at once, take the abs-max, write S_w[c] and quantize from the registers, so the row is read once
 // and the reads are not a chain of dependent round trips.
@@ -355,9 +355,10 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
   } else if (mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_ACT_PER_TENSOR_ASYM, false>), dim3((unsigned)blocks), dim3(256), 0,
                        st, x, rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
-  else if (init_minmax && std::is_same<T, float>::value && vec_row && (cols % 32) == 0 && cols <= 8 * 64 * 8 && !xq) {
-    // few rows: a block per row, so that the chip still holds enough wavefronts to cover the memory latency
-    const bool wide = rows < 4096 && cols > 8 * 64;
+  else if (init_minmax && std::is_same<T, float>::value && vec_row && (cols % 32) == 0 && cols <= 8 * 64 * 4 * 8 && !xq) {
+    // few rows or long rows: a block per row, so that the chip still holds enough wavefronts to cover the memory
+    // latency and a lane holds at most 64 values
+    const bool wide = (rows < 4096 && cols > 8 * 64) || cols > 8 * 64 * 8;
     const float* wf = (const float*)x;
     int8_t* cd = (int8_t*)codes;
     const int per_wave = (int)ceil_div(cols, 8 * 64 * (wide ? 4 : 1));     // 8-element chunks per lane
@@ -365,7 +366,8 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
 #define EFQAT_ROW_INIT(NIT, WPR) \
   hipLaunchKernelGGL((k_quantize_w_row_init<NIT, WPR>), grid, dim3(256), 0, st, wf, rows, cols, bits, scale, cd, clip)
     if (wide) {
-      if (per_wave <= 1) EFQAT_ROW_INIT(1, 4); else EFQAT_ROW_INIT(2, 4);
+      if (per_wave <= 1) EFQAT_ROW_INIT(1, 4); else if (per_wave <= 2) EFQAT_ROW_INIT(2, 4);
+      else if (per_wave <= 4) EFQAT_ROW_INIT(4, 4); else if (per_wave <= 6) EFQAT_ROW_INIT(6, 4); else EFQAT_ROW_INIT(8, 4);
     } else {
       if (per_wave <= 2) EFQAT_ROW_INIT(2, 1); else if (per_wave <= 4) EFQAT_ROW_INIT(4, 1); else EFQAT_ROW_INIT(8, 1);
     }

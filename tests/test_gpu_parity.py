@@ -80,7 +80,8 @@ def test_fakequant_weight(rows, cols, bits, shrink):
 # min/max initialisation of fp32 weights whose rows are whole mask words and at most 4096 long runs on the kernels that
 # hold the row in registers: one case per variant (chunks per lane x wavefronts per row), ragged row counts, a zero row
 @pytest.mark.parametrize("rows,cols", [(256, 256), (4097, 512), (5, 1024), (3, 2080), (7, 4096), (4100, 1056),
-                                       (4098, 2080), (4099, 4096), (2, 32)])
+                                       (4098, 2080), (4099, 4096), (2, 32), (5, 4128), (3, 8192),
+                                       (300, 11008), (4100, 16384), (9, 16416)])
 @pytest.mark.parametrize("bits", [8, 4])
 def test_fakequant_weight_minmax_rows_in_registers(rows, cols, bits):
     W = synth.normal(31 + rows + cols, 1, (rows, cols), std=0.02).astype(np.float32)
