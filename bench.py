@@ -29,8 +29,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dX product kernel, mean of the two layers of config 2 with token-major dY: from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_bert_ffn_r25_kernel_stats.md
-# (FFN1 143.3 MB read + 18.9 MB written, FFN2 245.6 MB + 75.6 MB).  Not measurable live; other workloads: null.
-DX_KERNEL_TRAFFIC_BYTES = {("cfg2", 0): 0.5 * (143.3e6 + 18.9e6 + 246.3e6 + 75.6e6)}
+# (k_gemm_kk, both layers: 189.7 MB read + 47.3 MB written per launch on average).  Not measurable live; other
+# workloads: null.
+DX_KERNEL_TRAFFIC_BYTES = {("cfg2", 0): 189.7e6 + 47.3e6}
 
 
 def parse_args():

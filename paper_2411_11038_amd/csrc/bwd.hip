@@ -401,8 +401,11 @@ struct BwdPlan {
   size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, b_zero, total;
 };
 
+// io_bf16: x and dX are both bf16 (known at the call, not at the workspace query: nothing it changes may change
+// a workspace size).
 static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, int taps, int64_t k,
-                         int dy_dtype, int dy_layout, bool im2col, const ConvGeom* cg = nullptr) {
+                         int dy_dtype, int dy_layout, bool im2col, const ConvGeom* cg = nullptr,
+                         bool io_bf16 = false) {
   BwdPlan p{};
   p.Mx = T_in; p.Tw = T_out; p.Nw = (int64_t)taps * c_in;
   p.ldc = round_up(c_out, 8); p.ldt = round_up(T_out, 8);
@@ -437,16 +440,24 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
     p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
     p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
   }
+  // bf16 in and out, whole 192 x 192 tiles: the pinned kernel with its straight-line epilogue changes the ranking of
+  // the tiles below 256 (the workspace slices do not depend on the outcome)
+  if (!p.dx8 && !p.cdx && io_bf16 && p.plan_dx.tile != 256 && (p.Mx % 192) == 0 && (c_in % 192) == 0 &&
+      p.Mx * c_in <= (int64_t)INT32_MAX && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16_PINNED)
+    p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, true, false, true);
   p.kk = !p.dx8 && !p.cdx && p.plan_dx.tile == 192;
   p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !(p.tn || p.rdw), !p.cdw) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);
   p.b_dyn = p.need_dyn ? (size_t)T_out * p.ldc * 2 : 0; cv.take(p.b_dyn);
   p.b_colA = (im2col && !p.cdx) ? (size_t)T_in * p.Kx * 2 : 0; cv.take(p.b_colA);
-  p.b_part_dx = (size_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n * 2 * sizeof(float); cv.take(p.b_part_dx);
+  // one (dS_x, dZ_x) pair per tile: sized for the smallest tile, whichever kernel runs
+  p.b_part_dx = (size_t)std::max<int64_t>(ceil_div(p.Mx, 128) * ceil_div(c_in, 128),
+                                          (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n) * 2 * sizeof(float);
+  cv.take(p.b_part_dx);
   p.b_xcT = (k > 0 && !p.tn && !p.rdw) ? (size_t)p.Nw * p.ldt * 2 : 0; cv.take(p.b_xcT);
   p.b_sel = p.need_sel ? (p.tn ? (size_t)T_out * p.kp * 2 : (size_t)k * p.ldt * 2) : 0; cv.take(p.b_sel);
-  p.b_zero = (p.tn || p.dx8 || p.cdx || p.rdw || p.kk) ? 256 : 0; cv.take(p.b_zero);
+  p.b_zero = 256; cv.take(p.b_zero);
   p.b_part_dw = k > 0 ? (size_t)p.plan_dw.split_k * k * p.Nw * sizeof(float) : 0; cv.take(p.b_part_dw);
   p.total = cv.off;
   return p;
@@ -466,7 +477,8 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   const int taps = cg ? cg->KH * cg->KW : 1;
   // a 1x1 / stride 1 / no-padding convolution is a linear layer over pixels: no im2col needed
   const bool im2col = cg != nullptr && !(taps == 1 && cg->stride == 1 && cg->pad == 0);
-  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col, cg);
+  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col, cg,
+                              io.x_dtype == EFQAT_BF16 && io.dx_dtype == EFQAT_BF16);
   WsCarver cv(ws);
   bf16_t* wqT = (bf16_t*)cv.take(p.b_wqT);
   bf16_t* dyn = (bf16_t*)cv.take(p.b_dyn);

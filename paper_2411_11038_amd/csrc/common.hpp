@@ -104,7 +104,8 @@ struct GemmPlan {
 };
 // Pure host function of the problem size (so the workspace query and the call agree).  allow_split = false
 // for the product with the fused dX epilogue.
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192 = true, bool allow_256 = true);
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192 = true, bool allow_256 = true,
+                   bool fast192 = false);   // fast192: price the 192 tile as k_gemm_kk with its straight-line epilogue
 
 // C[M][N] = sum_k A[row(m)][k] * B[n][k]; both operands bf16 with K contiguous.
 //   a_rows: optional gather, row(m) = a_rows[m]; lda/ldb in elements (multiples of 8), K multiple of 8.

@@ -415,12 +415,15 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 //   - blocks run in rounds of 256 CUs x blocks-per-CU;  split-K adds its fp32 partial tiles, written and read once.
 struct TileModel { int t; int bpc; double rate; double epi_dx; };
 static const TileModel kTiles[3] = {{256, 1, 2500.0, 0.75}, {192, 1, 2100.0, 0.75}, {128, 2, 1000.0, 0.6}};
+// the 192 x 192 kernel with the three-stage ring and the straight-line epilogue (k_gemm_kk, EPI_DXF)
+static const TileModel kTileFast192 = {192, 1, 2545.0, 0.45};
 
-GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192, bool allow_256) {
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K, bool allow_split, bool allow_192, bool allow_256, bool fast192) {
   GemmPlan best{};
   double best_t = 1e300;
   const int64_t ksteps = ceil_div(K, KALIGN);
-  for (const TileModel& tm : kTiles) {
+  for (const TileModel& tm0 : kTiles) {
+    const TileModel& tm = (tm0.t == 192 && fast192) ? kTileFast192 : tm0;
     if (tm.t == 192 && !allow_192) continue;
     if (tm.t == 256 && !allow_256) continue;
     const int64_t tiles = ceil_div(M, tm.t) * ceil_div(N, tm.t);

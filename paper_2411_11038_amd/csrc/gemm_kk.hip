@@ -266,6 +266,8 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 
   if constexpr (EPI == EPI_DX) {
     epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
+  } else if constexpr (EPI == EPI_DXF) {
+    epilogue_dx_fast<C>(g, acc, smem, m0, n0, wm, wn);
   } else {
     float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
 #pragma unroll
@@ -295,7 +297,7 @@ static int launch_kk_cfg(const GemmKkArgs& a, int split_k, hipStream_t st) {
   }
   dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
   int slot = 0;
-  constexpr int kProf = EPI == EPI_DX ? 0 : 1;
+  constexpr int kProf = EPI == EPI_RAW ? 1 : 0;
   const bool timed = gemm_prof_begin(kProf, st, &slot);
   hipLaunchKernelGGL((k_gemm_kk<T, WGM, WGN, EPI>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) gemm_prof_end(kProf, st, slot);
@@ -327,8 +329,13 @@ int launch_gemm_kk(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, c
   a.tiles_m = plan.tiles_m;
   a.tiles_n = plan.tiles_n;
   switch (plan.tile) {
-    case 192:
-      return epi ? launch_kk_cfg<192, 2, 2, EPI_DX>(ka, 1, stream) : launch_kk_cfg<192, 2, 2, EPI_RAW>(ka, split_k, stream);
+    case 192: {
+      if (!epi) return launch_kk_cfg<192, 2, 2, EPI_RAW>(ka, split_k, stream);
+      // nothing to decide at run time: the straight-line epilogue
+      const bool fast = a.epi_vec && epi->x_dtype == EFQAT_BF16 && epi->dx_dtype == EFQAT_BF16 && (M % 192) == 0 &&
+                        (N % 192) == 0 && M * N <= (int64_t)INT32_MAX;
+      return fast ? launch_kk_cfg<192, 2, 2, EPI_DXF>(ka, 1, stream) : launch_kk_cfg<192, 2, 2, EPI_DX>(ka, 1, stream);
+    }
     default:
       return EFQAT_ERR_BAD_SHAPE;
   }

@@ -369,6 +369,10 @@ PINNED_CASES = [
     (517, 392, 1096, "bf16", 8, 8, 0.8, (1, 8), 0, True),     # 17 stages + tail of 8; several tiles
     (400, 70, 645, "f32", 8, 4, 0.7, (1, 3), 0, False),       # nothing a multiple of 8: staged dY, scalar epilogue
     (520, 208, 840, "bf16", 8, 8, 0.8, (1, 4), 1, False),     # channel-major dY: transposed copy, then this kernel
+    # bf16 in and out, T and C_in multiples of 192: the straight-line epilogue (several tiles, clipped activations)
+    (384, 576, 264, "bf16", 8, 8, 0.6, (1, 4), 0, False),
+    (576, 192, 1096, "bf16", 8, 4, 0.7, (1, 8), 0, True),
+    (192, 384, 72, "bf16", 4, 8, 0.6, (1, 2), 0, False),      # 4-bit activations: many clipped elements
 ]
 
 
