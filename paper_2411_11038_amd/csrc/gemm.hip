@@ -336,6 +336,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
       }
   } else if constexpr (EPI == EPI_DX) {
     epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
+  } else if constexpr (EPI == EPI_DXF) {
+    epilogue_dx_fast<C>(g, acc, smem, m0, n0, wm, wn);
   } else {
     // Forward epilogue: the int32 sums are over (code - 128) * w, so
     //   y[m][n] = S_x * S_w[n] * (acc + (128 - round(Z_x)) * sum_k w[n][k]).
@@ -486,12 +488,18 @@ static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   }
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
   int slot = 0;
-  constexpr int kProf = EPI == EPI_DX ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
+  constexpr int kProf = (EPI == EPI_DX || EPI == EPI_DXF) ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
   const bool timed = gemm_prof_begin(kProf, st, &slot);
   hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) gemm_prof_end(kProf, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
+}
+
+// nothing left to decide in the dX epilogue: bf16 in and out, whole tiles, 32-bit element offsets, aligned pointers
+static bool nt_epilogue_fast(const GemmArgs& g, const GemmEpilogueDx& epi, int tile) {
+  return g.epi_vec && epi.x_dtype == EFQAT_BF16 && epi.dx_dtype == EFQAT_BF16 && (g.M % tile) == 0 &&
+         (g.N % tile) == 0 && (int64_t)g.M * g.N <= (int64_t)INT32_MAX;
 }
 
 int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf16_t* B, int64_t ldb, int64_t M,
@@ -521,6 +529,7 @@ int launch_gemm_nt(const bf16_t* A, int64_t lda, const int32_t* a_rows, const bf
       return epi ? launch_cfg<192, 192, EPI_DX, false>(a, 1, stream)
                  : launch_cfg<192, 192, EPI_RAW, false>(a, split_k, stream);
     case 128:
+      if (epi && nt_epilogue_fast(a, *epi, 128)) return launch_cfg<128, 128, EPI_DXF, false>(a, 1, stream);
       return epi ? launch_cfg<128, 128, EPI_DX, false>(a, 1, stream)
                  : launch_cfg<128, 128, EPI_RAW, false>(a, split_k, stream);
     default:
@@ -547,8 +556,10 @@ int launch_gemm_nt_conv_dx(const bf16_t* dy_tok, int64_t ldc, const bf16_t* wqT,
   a.cv_spt = (int)(ldc / 64); a.cv_zero = cm.zero_page;
   a.cv_m_spt = (1ull << 32) / (uint64_t)a.cv_spt + 1; a.cv_m_kw = (1ull << 32) / (uint64_t)cm.KW + 1;
   switch (plan.tile) {
-    case 192: return launch_cfg<192, 192, EPI_DX, false, true>(a, 1, stream);
-    case 128: return launch_cfg<128, 128, EPI_DX, false, true>(a, 1, stream);
+    case 192: return nt_epilogue_fast(a, epi, 192) ? launch_cfg<192, 192, EPI_DXF, false, true>(a, 1, stream)
+                                                   : launch_cfg<192, 192, EPI_DX, false, true>(a, 1, stream);
+    case 128: return nt_epilogue_fast(a, epi, 128) ? launch_cfg<128, 128, EPI_DXF, false, true>(a, 1, stream)
+                                                   : launch_cfg<128, 128, EPI_DX, false, true>(a, 1, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }

@@ -433,7 +433,8 @@ struct GemmDx8Args {
   const void* zero_page;   // >= 256 zero bytes
 };
 
-template <int T, bool DW = false, bool ATN = false>
+// FAST (dX only): the straight-line epilogue for bf16 x / dX and whole tiles (epilogue_dx_fast).
+template <int T, bool DW = false, bool ATN = false, bool FAST = false>
 __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using C = Dx8Cfg<T, ATN>;
@@ -756,6 +757,8 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
           if (row < g.M && col < g.N) out[(int64_t)row * g.N + col] = acc[i][j][r];
         }
       }
+  } else if constexpr (FAST) {
+    epilogue_dx_fast<C>(g, acc, smem, m0, n0, wm, wn);
   } else {
     epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
   }
@@ -803,12 +806,12 @@ int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* 
 }
 
 
-template <int T, bool DW = false, bool ATN = false>
+template <int T, bool DW = false, bool ATN = false, bool FAST = false>
 static int launch_dx8_cfg(const GemmDx8Args& a, int split_k, hipStream_t st) {
   using C = Dx8Cfg<T, ATN>;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T, DW, ATN>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T, DW, ATN, FAST>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             C::LDS_BYTES) != hipSuccess)
       return EFQAT_ERR_HIP;
     attr_done = true;
@@ -816,10 +819,16 @@ static int launch_dx8_cfg(const GemmDx8Args& a, int split_k, hipStream_t st) {
   dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
   int slot = 0;
   const bool timed = gemm_prof_begin(DW ? 1 : 0, st, &slot);
-  hipLaunchKernelGGL((k_gemm_dx8<T, DW, ATN>), grid, dim3(256), C::LDS_BYTES, st, a);
+  hipLaunchKernelGGL((k_gemm_dx8<T, DW, ATN, FAST>), grid, dim3(256), C::LDS_BYTES, st, a);
   if (timed) gemm_prof_end(DW ? 1 : 0, st, slot);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
+}
+
+// nothing left to decide in the epilogue: bf16 in and out, whole tiles, 32-bit element offsets, aligned pointers
+static bool dx8_epilogue_fast(const GemmArgs& g, const GemmEpilogueDx& epi, int tile) {
+  return g.epi_vec && epi.x_dtype == EFQAT_BF16 && epi.dx_dtype == EFQAT_BF16 && (g.M % tile) == 0 &&
+         (g.N % tile) == 0 && (int64_t)g.M * g.N <= (int64_t)INT32_MAX;
 }
 
 int launch_gemm_dx8_cm(const bf16_t* dy_cm, int64_t lda, const int8_t* w_codes, int64_t ldb, const float* s_w,
@@ -840,8 +849,10 @@ int launch_gemm_dx8_cm(const bf16_t* dy_cm, int64_t lda, const int8_t* w_codes, 
   a.a_cols = (int)M; a.b_cols = (int)N;
   a.zero_page = zero_page;
   switch (tile) {
-    case 256: return launch_dx8_cfg<256, false, true>(a, 1, stream);
-    case 128: return launch_dx8_cfg<128, false, true>(a, 1, stream);
+    case 256: return dx8_epilogue_fast(a.g, epi, 256) ? launch_dx8_cfg<256, false, true, true>(a, 1, stream)
+                                                      : launch_dx8_cfg<256, false, true>(a, 1, stream);
+    case 128: return dx8_epilogue_fast(a.g, epi, 128) ? launch_dx8_cfg<128, false, true, true>(a, 1, stream)
+                                                      : launch_dx8_cfg<128, false, true>(a, 1, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }
@@ -906,8 +917,10 @@ int launch_gemm_dx8(const bf16_t* dy, int64_t lda, const int8_t* w_codes, int64_
   a.b_cols = (int)N;
   a.zero_page = zero_page;
   switch (tile) {
-    case 256: return launch_dx8_cfg<256>(a, 1, stream);
-    case 128: return launch_dx8_cfg<128>(a, 1, stream);
+    case 256: return dx8_epilogue_fast(a.g, epi, 256) ? launch_dx8_cfg<256, false, false, true>(a, 1, stream)
+                                                      : launch_dx8_cfg<256>(a, 1, stream);
+    case 128: return dx8_epilogue_fast(a.g, epi, 128) ? launch_dx8_cfg<128, false, false, true>(a, 1, stream)
+                                                      : launch_dx8_cfg<128>(a, 1, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }

@@ -305,6 +305,9 @@ LIN_CASES = [
     (72, 16, 24, "bf16", 8, 8, 1.0, (1, 3), 1, False),
     (2048, 512, 640, "bf16", 8, 8, 0.8, (1, 1), 1, False),        # every channel; several tiles; split-K
     (1000, 768, 1096, "bf16", 8, 8, 0.8, (1, 20), 1, False),      # k = 54 of 1096
+    (384, 256, 136, "bf16", 8, 8, 0.6, (1, 4), 1, False),         # whole 128 tiles: straight-line dX epilogue
+    (256, 128, 136, "bf16", 8, 8, 0.6, (1, 4), 0, False),         # ... of the bf16-operand 128 x 128 kernel
+    (256, 136, 128, "bf16", 4, 8, 0.6, (1, 4), 0, False),         # (C_in = 136: general epilogue, same kernel family)
 ]
 
 
@@ -335,6 +338,8 @@ DX8_CASES = [
     (2048, 512, 640, 8, 8, 0.8, (1, 1), False),     # 256 tile, everything a multiple of the tile
     (1100, 528, 200, 8, 4, 0.7, (1, 4), False),     # 256 tile with tails in M, N and K
     (1030, 768, 1096, 8, 8, 0.8, (1, 20), False),   # 256 tile, 17 full stages + tail
+    (384, 256, 136, 8, 8, 0.6, (1, 4), False),      # whole 128 tiles: straight-line epilogue, clipped activations
+    (1024, 512, 200, 4, 8, 0.6, (1, 4), True),      # whole 256 tiles, 4-bit activations (many clipped)
 ]
 
 
@@ -522,6 +527,9 @@ CONV_CASES = [
     (1, 5, 5, 256, 64, 2, 2, 1, 0, "f32", 8, 0.8, (1, 1), 0, False),      # image smaller than a 64-token stage
     (2, 6, 10, 128, 64, 3, 1, 1, 1, "bf16", 8, 0.8, (1, 1), 0, False),    # every channel: dY itself is the A operand
     (7, 10, 9, 128, 64, 3, 3, 1, 1, "bf16", 4, 0.8, (1, 4), 0, False),    # 630 tokens: split-K with a ragged last stage
+    # 128 input pixels x 128 channels: whole tiles, the straight-line dX epilogue behind the implicit-im2col loop
+    (2, 8, 8, 128, 64, 3, 3, 1, 1, "bf16", 8, 0.6, (1, 4), 0, False),
+    (3, 8, 16, 256, 128, 3, 3, 1, 1, "bf16", 8, 0.6, (1, 2), 0, True),
 ]
 
 
