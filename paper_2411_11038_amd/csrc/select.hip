@@ -25,36 +25,38 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
   if (lane == 0) scores[row] = acc / (double)n;
 }
 
-// Exact Top-K by radix select, one 1024-thread block.  Scores are non-negative doubles, so their bit
+// Exact Top-K by radix select, one block of NTH threads.  Scores are non-negative doubles, so their bit
 // patterns order like the values.  Passes over 8-bit digits of the 64-bit key, from the highest bit on which
 // two keys differ downwards, find the key T of the k-th largest score and `need`, the number of scores equal
 // to T that still belong to the selection (as soon as at most 64 candidates remain they are ranked directly); then one ordered sweep writes every index whose score is > T, plus the first `need` indices
 // (ascending) whose score equals T: ties go to the lower index, output is ascending.  Integer counting only,
 // so the result does not depend on thread scheduling.
-__global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
+template <int NTH>
+__global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
                                                      int32_t* __restrict__ idx) {
-  __shared__ unsigned int hist[16][256];              // one histogram per wavefront: 16x less atomic contention
+  constexpr int NW = NTH / 64;                        // wavefronts
+  __shared__ unsigned int hist[NW][256];              // one histogram per wavefront: less atomic contention
   __shared__ unsigned int total[256];
-  __shared__ unsigned long long s_prefix, s_or[16], s_and[16];
+  __shared__ unsigned long long s_prefix, s_or[NW], s_and[NW];
   __shared__ long long s_need;
-  __shared__ int wsum_gt[16], wsum_eq[16];
+  __shared__ int wsum_gt[NW], wsum_eq[NW];
   __shared__ long long s_base_gt, s_base_eq;
   __shared__ unsigned long long cand_key[64];
   __shared__ int cand_idx[64];
   __shared__ int s_bin_count, s_ncand;
-  __shared__ int scan_gt[12 * 16], scan_eq[12 * 16];   // KPT x wavefronts (cached case)
+  __shared__ int scan_gt[12 * NW + 64], scan_eq[12 * NW + 64];   // KPT x wavefronts (cached case), padded to whole lanes
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   // Up to KPT keys per thread stay in registers for all passes (n <= 12288); longer inputs are re-read.
   constexpr int KPT = 12;
-  static_assert(KPT * 16 == 3 * 64, "the ordered output scans KPT x 16 counts with three per lane");
+  constexpr int EPL = (KPT * NW + 63) / 64;           // scan entries per lane of the ordered output
   unsigned long long keys[KPT];
-  const bool cached = n <= (int64_t)KPT * 1024;
+  const bool cached = n <= (int64_t)KPT * NTH;
   // Leading bits on which all keys agree need no pass: find them from the OR and AND of all keys.
   unsigned long long vor = 0ull, vand = ~0ull;
   if (cached) {
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
-      const int64_t i = (int64_t)q * 1024 + tid;
+      const int64_t i = (int64_t)q * NTH + tid;
       keys[q] = 0ull;
       if (i < n) {
         keys[q] = (unsigned long long)__double_as_longlong(scores[i]);
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
       }
     }
   } else {
-    for (int64_t i = tid; i < n; i += 1024) {
+    for (int64_t i = tid; i < n; i += NTH) {
       const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
       vor |= key; vand &= key;
     }
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   if (lane == 0) { s_or[wv] = vor; s_and[wv] = vand; }
   __syncthreads();
   vor = 0ull; vand = ~0ull;
-  for (int i = 0; i < 16; ++i) { vor |= s_or[i]; vand &= s_and[i]; }
+  for (int i = 0; i < NW; ++i) { vor |= s_or[i]; vand &= s_and[i]; }
   const unsigned long long diff = vor ^ vand;          // bits that differ between some two keys
   // The first 8-bit digit window ends at the highest bit on which two keys differ, so the first pass already
   // spreads the keys over the bins; below it the windows follow each other down to bit 0 (the last one may be
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
     s_need = k;
     s_bin_count = 1 << 30;
   }
-  for (int b = tid; b < 16 * 256; b += 1024) (&hist[0][0])[b] = 0u;
+  for (int b = tid; b < NW * 256; b += NTH) (&hist[0][0])[b] = 0u;
   __syncthreads();
   while (top > 0) {
     const int width = top < 8 ? top : 8;
@@ -97,22 +99,22 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
     if (cached) {
 #pragma unroll
       for (int q = 0; q < KPT; ++q) {
-        const int64_t i = (int64_t)q * 1024 + tid;
+        const int64_t i = (int64_t)q * NTH + tid;
         const unsigned long long key = keys[q];
         const bool match = (top >= 64) || ((key >> top) == prefix);
         if (i < n && match) atomicAdd(&hist[wv][(key >> shift) & dmask], 1u);
       }
     } else {
-      for (int64_t i = tid; i < n; i += 1024) {
+      for (int64_t i = tid; i < n; i += NTH) {
         const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
         const bool match = (top >= 64) || ((key >> top) == prefix);
         if (match) atomicAdd(&hist[wv][(key >> shift) & dmask], 1u);
       }
     }
     __syncthreads();
-    if (tid < 256) {                                    // fold the 16 per-wave histograms, clear them for the next pass
+    if (tid < 256) {                                    // fold the per-wave histograms, clear them for the next pass
       unsigned int t = 0;
-      for (int w = 0; w < 16; ++w) { t += hist[w][tid]; hist[w][tid] = 0u; }
+      for (int w = 0; w < NW; ++w) { t += hist[w][tid]; hist[w][tid] = 0u; }
       total[tid] = t;
     }
     __syncthreads();
@@ -148,14 +150,14 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
       if (cached) {
 #pragma unroll
         for (int q = 0; q < KPT; ++q) {
-          const int64_t i = (int64_t)q * 1024 + tid;
+          const int64_t i = (int64_t)q * NTH + tid;
           if (i < n && (keys[q] >> top) == np) {
             const int slot = atomicAdd(&s_ncand, 1);
             cand_key[slot] = keys[q]; cand_idx[slot] = (int)i;
           }
         }
       } else {
-        for (int64_t i = tid; i < n; i += 1024) {
+        for (int64_t i = tid; i < n; i += NTH) {
           const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
           if ((key >> top) == np) {
             const int slot = atomicAdd(&s_ncand, 1);
@@ -190,40 +192,49 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   const unsigned long long T = s_prefix;
   const long long need = s_need;
   if (cached) {
-    // Ordered output from the keys still in registers: key q of thread t sits at index 1024 q + t.  Every wavefront
-    // counts its "greater" and "equal" flags per chunk q, one wavefront turns the KPT x 16 counts into exclusive
+    // Ordered output from the keys still in registers: key q of thread t sits at index NTH q + t.  Every wavefront
+    // counts its "greater" and "equal" flags per chunk q, one wavefront turns the KPT x NW counts into exclusive
     // prefixes in index order, then every selected key knows its output position.  Two barriers, no global re-read.
     const unsigned long long below = (1ull << lane) - 1ull;
     unsigned long long bg[KPT], be[KPT];
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
-      const int64_t c = (int64_t)q * 1024 + tid;
+      const int64_t c = (int64_t)q * NTH + tid;
       bg[q] = __ballot(c < n && keys[q] > T);
       be[q] = __ballot(c < n && keys[q] == T);
-      if (lane == 0) { scan_gt[q * 16 + wv] = __popcll(bg[q]); scan_eq[q * 16 + wv] = __popcll(be[q]); }
+      if (lane == 0) { scan_gt[q * NW + wv] = __popcll(bg[q]); scan_eq[q * NW + wv] = __popcll(be[q]); }
     }
     __syncthreads();
     if (wv == 0) {
-      // exclusive scan of KPT * 16 = 192 counts (3 consecutive entries per lane), gt and eq
-      int g0 = scan_gt[3 * lane], g1 = scan_gt[3 * lane + 1], g2 = scan_gt[3 * lane + 2];
-      int e0 = scan_eq[3 * lane], e1 = scan_eq[3 * lane + 1], e2 = scan_eq[3 * lane + 2];
-      int gi = g0 + g1 + g2, ei = e0 + e1 + e2;        // inclusive prefix over lanes <= l
+      // exclusive scan of the KPT * NW counts (EPL consecutive entries per lane; entries beyond the end are zero)
+      int g[EPL], e[EPL];
+      int gs = 0, es = 0;
+#pragma unroll
+      for (int u = 0; u < EPL; ++u) {
+        const bool in = EPL * lane + u < KPT * NW;
+        g[u] = in ? scan_gt[EPL * lane + u] : 0; e[u] = in ? scan_eq[EPL * lane + u] : 0;
+        gs += g[u]; es += e[u];
+      }
+      int gi = gs, ei = es;                             // inclusive prefix over lanes <= l
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int tg = __shfl_up(gi, o, kWave), te = __shfl_up(ei, o, kWave);
         if (lane >= o) { gi += tg; ei += te; }
       }
-      const int gx = gi - (g0 + g1 + g2), ex = ei - (e0 + e1 + e2);
-      scan_gt[3 * lane] = gx; scan_gt[3 * lane + 1] = gx + g0; scan_gt[3 * lane + 2] = gx + g0 + g1;
-      scan_eq[3 * lane] = ex; scan_eq[3 * lane + 1] = ex + e0; scan_eq[3 * lane + 2] = ex + e0 + e1;
+      int gx = gi - gs, ex = ei - es;
+#pragma unroll
+      for (int u = 0; u < EPL; ++u) {
+        scan_gt[EPL * lane + u] = gx; scan_eq[EPL * lane + u] = ex;
+        gx += g[u]; ex += e[u];
+      }
     }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
-      const int64_t c = (int64_t)q * 1024 + tid;
+      const int64_t c = (int64_t)q * NTH + tid;
       const bool gt = (bg[q] >> lane) & 1ull, eq = (be[q] >> lane) & 1ull;
-      const long long gt_before = scan_gt[q * 16 + wv] + __popcll(bg[q] & below);
-      const long long eq_before = scan_eq[q * 16 + wv] + __popcll(be[q] & below);
+      const long long gt_before = scan_gt[q * NW + wv] + __popcll(bg[q] & below);
+      const long long eq_before = scan_eq[q * NW + wv] + __popcll(be[q] & below);
       if (gt || (eq && eq_before < need)) {
         const long long pos = gt_before + (eq_before < need ? eq_before : need);
         if (pos < k) idx[pos] = (int32_t)c;
@@ -233,7 +244,7 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
   }
   if (tid == 0) { s_base_gt = 0; s_base_eq = 0; }
   __syncthreads();
-  for (int64_t c0 = 0; c0 < n; c0 += 1024) {
+  for (int64_t c0 = 0; c0 < n; c0 += NTH) {
     const int64_t c = c0 + tid;
     unsigned long long key = 0ull;
     if (c < n) key = (unsigned long long)__double_as_longlong(scores[c]);
@@ -254,11 +265,17 @@ __global__ __launch_bounds__(1024) void k_topk_radix(const double* __restrict__ 
     __syncthreads();
     if (tid == 0) {
       long long a = 0, e = 0;
-      for (int i = 0; i < 16; ++i) { a += wsum_gt[i]; e += wsum_eq[i]; }
+      for (int i = 0; i < NW; ++i) { a += wsum_gt[i]; e += wsum_eq[i]; }
       s_base_gt += a; s_base_eq += e;
     }
     __syncthreads();
   }
+}
+
+// short inputs (BERT / ResNet channel counts) fit the registers of four wavefronts, whose barriers are cheaper
+static void launch_topk(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st) {
+  if (n <= 12 * 256) hipLaunchKernelGGL(k_topk_radix<256>, dim3(1), dim3(256), 0, st, scores, n, k, idx);
+  else hipLaunchKernelGGL(k_topk_radix<1024>, dim3(1), dim3(1024), 0, st, scores, n, k, idx);
 }
 
 // CWPN helpers: per-layer counts of selected channels, and global -> per-layer local indices.
@@ -321,7 +338,7 @@ extern "C" int efqat_channel_select(const float* w, int64_t c_out, int64_t block
                      sc_out);
   EFQAT_LAUNCH_CHECK();
   if (k == 0) return EFQAT_OK;
-  hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, sc_out, c_out, k, idx);
+  launch_topk(sc_out, c_out, k, idx, st);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -342,7 +359,7 @@ extern "C" int efqat_network_select(const double* scores, const int64_t* layer_o
   hipStream_t st = (hipStream_t)stream;
   // k_per_layer is derived from idx; with k_total == 0 every count is 0 and idx is never read
   if (k_total > 0) {
-    hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, scores, total, k_total, idx);
+    launch_topk(scores, total, k_total, idx, st);
     EFQAT_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_layer_counts, dim3((unsigned)ceil_div(n_layers, 256)), dim3(256), 0, st, layer_off, n_layers,
@@ -414,7 +431,7 @@ extern "C" int efqat_layer_select(const double* scores, const int64_t* layer_off
   hipLaunchKernelGGL(k_layer_means, dim3((unsigned)n_layers), dim3(256), 0, st, scores, layer_off, ls);
   EFQAT_LAUNCH_CHECK();
   if (k_layers > 0) {
-    hipLaunchKernelGGL(k_topk_radix, dim3(1), dim3(1024), 0, st, ls, n_layers, k_layers, layer_idx);
+    launch_topk(ls, n_layers, k_layers, layer_idx, st);
     EFQAT_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_layer_flags, dim3((unsigned)ceil_div(n_layers, 256)), dim3(256), 0, st, layer_off, n_layers,
