@@ -207,93 +207,113 @@ __device__ __forceinline__ void epilogue_dx(const GemmArgs& g, floatx16_t (&acc)
 // Per lane: s1 = sum a (code - Z), s3 = sum o x, sd = sum (a - o) with o = in range ? a : 0; then
 // sum a gs = s1 - s3 / S (the reduction epilogue_dx forms term by term).
 template <class C>
-__device__ __forceinline__ void epilogue_dx_fast(const GemmArgs& g, floatx16_t (&acc)[C::TM][C::TN], char* smem,
-                                                 int m0, int n0, int wm, int wn) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int fr = lane & 31, fh = lane >> 5;
-  constexpr int PITCH = C::WN + 8;                   // floats; 4*PITCH = 32 (mod 64) banks
-  constexpr int CPR = C::WN / 8;                     // 8-column chunks per row
-  constexpr int LPR = (CPR % 8 == 0) ? 8 : 4;
+struct EpiDxFast {
+  static constexpr int PITCH = C::WN + 8;            // floats; 4*PITCH = 32 (mod 64) banks
+  static constexpr int CPR = C::WN / 8;              // 8-column chunks per row
+  static constexpr int LPR = (CPR % 8 == 0) ? 8 : 4;
   static_assert(CPR % LPR == 0, "chunks per row");
-  constexpr int KC = CPR / LPR, RP = 64 / LPR, HP = 32 / RP, NP = HP * KC;
-  float* stage = reinterpret_cast<float*>(smem) + wave * 32 * PITCH;
-  const float s = g.s_x[0];
-  const float z = rintf(g.z_x[0]);
-  const float ninv_s = -1.0f / s;
-  const uint32_t un = (uint32_t)g.N, uwpr = (uint32_t)((g.N + 31) >> 5);
-  const uint32_t lr = (uint32_t)lane / LPR, lq = (uint32_t)lane % LPR;
-  const uint32_t row_b = (uint32_t)(m0 + wm * C::WM) + lr, col_b = (uint32_t)(n0 + wn * C::WN) + lq * 8u;
-  const float* st_b = stage + lr * PITCH + lq * 8;
-  const uint8_t* codes = g.x_codes;
-  const bf16_t* xp = (const bf16_t*)g.x;
-  bf16_t* dxp = (bf16_t*)g.dx;
+  static constexpr int KC = CPR / LPR, RP = 64 / LPR, HP = 32 / RP, NP = HP * KC;
   struct Inputs { uint2 cw; uint4 xa; uint32_t mb; };
   Inputs in[NP];
+  uint32_t un, uwpr, row_b, col_b;
+  const uint8_t* codes; const uint32_t* clip; const bf16_t* xp; bf16_t* dxp;
+
   // element offset of pass p = (h, k) of slab i
-  auto elem = [&](int i, int p) -> uint32_t {
+  __device__ __forceinline__ uint32_t elem(int i, int p) const {
     return (row_b + (uint32_t)(32 * i + RP * (p / KC))) * un + col_b + (uint32_t)(8 * LPR * (p % KC));
-  };
-  auto fetch = [&](int i, int p) {
+  }
+  __device__ __forceinline__ void fetch(int i, int p) {
     const uint32_t row = row_b + (uint32_t)(32 * i + RP * (p / KC));
     const uint32_t col = col_b + (uint32_t)(8 * LPR * (p % KC));
     const uint32_t e = row * un + col;
-    in[p].mb = g.x_clip[row * uwpr + (col >> 5)] >> (col & 31u);
+    in[p].mb = clip[row * uwpr + (col >> 5)];        // shifted at use: no arithmetic on a value still in flight
     in[p].cw = *reinterpret_cast<const uint2*>(codes + e);
     in[p].xa = *reinterpret_cast<const uint4*>(xp + e);
-  };
-  auto lds_chunk = [&](int p, float4& a0, float4& a1) {
-    a0 = *reinterpret_cast<const float4*>(st_b + RP * (p / KC) * PITCH + 8 * LPR * (p % KC));
-    a1 = *reinterpret_cast<const float4*>(st_b + RP * (p / KC) * PITCH + 8 * LPR * (p % KC) + 4);
-  };
-  float s1 = 0.0f, s3 = 0.0f, sd = 0.0f;
+  }
+  // Addresses of this wavefront's sub-tile, and the requests for the inputs of its first slab.  A kernel may call
+  // this before its main loop has ended, provided none of its own global -> LDS copies is still outstanding or
+  // issued later (a wavefront's loads complete in order).
+  __device__ __forceinline__ void prefetch(const GemmArgs& g, int m0, int n0, int wm, int wn) {
+    const int lane = threadIdx.x & 63;
+    un = (uint32_t)g.N; uwpr = (uint32_t)((g.N + 31) >> 5);
+    row_b = (uint32_t)(m0 + wm * C::WM) + (uint32_t)lane / LPR;
+    col_b = (uint32_t)(n0 + wn * C::WN) + ((uint32_t)lane % LPR) * 8u;
+    codes = g.x_codes; clip = g.x_clip; xp = (const bf16_t*)g.x; dxp = (bf16_t*)g.dx;
 #pragma unroll
-  for (int p = 0; p < NP; ++p) fetch(0, p);
+    for (int p = 0; p < NP; ++p) fetch(0, p);
+  }
+  // The epilogue proper; prefetch() has been called.  smem: at least 4 * 32 * (C::WN + 8) floats, no longer used by
+  // the main loop (the caller has synchronised).  part_idx: the tile's slot in g.partial.
+  __device__ __forceinline__ void run(const GemmArgs& g, floatx16_t (&acc)[C::TM][C::TN], char* smem, int part_idx) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fr = lane & 31, fh = lane >> 5;
+    float* stage = reinterpret_cast<float*>(smem) + wave * 32 * PITCH;
+    const float s = g.s_x[0];
+    const float z = rintf(g.z_x[0]);
+    const float ninv_s = -1.0f / s;
+    const float* st_b = stage + ((uint32_t)lane / LPR) * PITCH + ((uint32_t)lane % LPR) * 8;
+    auto lds_chunk = [&](int p, float4& a0, float4& a1) {
+      a0 = *reinterpret_cast<const float4*>(st_b + RP * (p / KC) * PITCH + 8 * LPR * (p % KC));
+      a1 = *reinterpret_cast<const float4*>(st_b + RP * (p / KC) * PITCH + 8 * LPR * (p % KC) + 4);
+    };
+    const uint32_t msh = col_b & 31u;                 // a pass moves by a multiple of 32 columns
+    static_assert((8 * LPR) % 32 == 0, "mask bit offset is the same in every pass");
+    float s1 = 0.0f, s3 = 0.0f, sd = 0.0f;
 #pragma unroll
-  for (int i = 0; i < C::TM; ++i) {
-    if (i > 0) lds_barrier();
+    for (int i = 0; i < C::TM; ++i) {
+      if (i > 0) lds_barrier();
 #pragma unroll
-    for (int j = 0; j < C::TN; ++j)
+      for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
-    lds_barrier();
-    float4 n0v, n1v;
-    lds_chunk(0, n0v, n1v);
+        for (int r = 0; r < 16; ++r)
+          stage[(8 * (r >> 2) + 4 * fh + (r & 3)) * PITCH + j * 32 + fr] = acc[i][j][r];
+      lds_barrier();
+      float4 n0v, n1v;
+      lds_chunk(0, n0v, n1v);
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      const float a[8] = {n0v.x, n0v.y, n0v.z, n0v.w, n1v.x, n1v.y, n1v.z, n1v.w};
-      if (p + 1 < NP) lds_chunk(p + 1, n0v, n1v);
-      const Inputs q8 = in[p];
-      if (i + 1 < C::TM) fetch(i + 1, p);
-      const uint32_t xw[4] = {q8.xa.x, q8.xa.y, q8.xa.z, q8.xa.w};
-      float o[8];
+      for (int p = 0; p < NP; ++p) {
+        const float a[8] = {n0v.x, n0v.y, n0v.z, n0v.w, n1v.x, n1v.y, n1v.z, n1v.w};
+        if (p + 1 < NP) lds_chunk(p + 1, n0v, n1v);
+        const Inputs q8 = in[p];
+        if (i + 1 < C::TM) fetch(i + 1, p);
+        const uint32_t xw[4] = {q8.xa.x, q8.xa.y, q8.xa.z, q8.xa.w};
+        float o[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const float xv = (t & 1) ? __uint_as_float(xw[t >> 1] & 0xFFFF0000u) : __uint_as_float(xw[t >> 1] << 16);
-        const uint32_t byte = ((t < 4 ? q8.cw.x : q8.cw.y) >> (8 * (t & 3))) & 0xFFu;
-        const bool inr = (q8.mb >> t) & 1u;
-        s1 = fmaf(a[t], (float)byte - z, s1);
-        o[t] = inr ? a[t] : 0.0f;
-        s3 = fmaf(o[t], xv, s3);
-        sd += a[t] - o[t];
+        for (int t = 0; t < 8; ++t) {
+          const float xv = (t & 1) ? __uint_as_float(xw[t >> 1] & 0xFFFF0000u) : __uint_as_float(xw[t >> 1] << 16);
+          const uint32_t byte = ((t < 4 ? q8.cw.x : q8.cw.y) >> (8 * (t & 3))) & 0xFFu;
+          const bool inr = (q8.mb >> (msh + t)) & 1u;
+          s1 = fmaf(a[t], (float)byte - z, s1);
+          o[t] = inr ? a[t] : 0.0f;
+          s3 = fmaf(o[t], xv, s3);
+          sd += a[t] - o[t];
+        }
+        *reinterpret_cast<uint4*>(dxp + elem(i, p)) =
+            make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
+                       pack_bf16x2(o[6], o[7]));
+        __builtin_amdgcn_sched_barrier(0);            // keeps the passes from piling up in registers
       }
-      *reinterpret_cast<uint4*>(dxp + elem(i, p)) =
-          make_uint4(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]),
-                     pack_bf16x2(o[6], o[7]));
-      __builtin_amdgcn_sched_barrier(0);              // keeps the passes from piling up in registers
+    }
+    const float ps = wave_sum(fmaf(s3, ninv_s, s1));
+    const float pz = wave_sum(sd);
+    lds_barrier();                                   // staging area is dead: reuse for the block sum
+    float* red = reinterpret_cast<float*>(smem);
+    if (lane == 0) { red[2 * wave] = ps; red[2 * wave + 1] = pz; }
+    lds_barrier();
+    if (tid == 0) {
+      g.partial[2 * part_idx] = (red[0] + red[2]) + (red[4] + red[6]);
+      g.partial[2 * part_idx + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
     }
   }
-  float ps = wave_sum(fmaf(s3, ninv_s, s1));
-  float pz = wave_sum(sd);
-  lds_barrier();                                     // staging area is dead: reuse for the block sum
-  float* red = reinterpret_cast<float*>(smem);
-  if (lane == 0) { red[2 * wave] = ps; red[2 * wave + 1] = pz; }
-  lds_barrier();
-  if (tid == 0) {
-    g.partial[2 * blockIdx.x] = (red[0] + red[2]) + (red[4] + red[6]);
-    g.partial[2 * blockIdx.x + 1] = -s * ((red[1] + red[3]) + (red[5] + red[7]));
-  }
+};
+
+template <class C>
+__device__ __forceinline__ void epilogue_dx_fast(const GemmArgs& g, floatx16_t (&acc)[C::TM][C::TN], char* smem,
+                                                 int m0, int n0, int wm, int wn) {
+  EpiDxFast<C> e;
+  e.prefetch(g, m0, n0, wm, wn);
+  e.run(g, acc, smem, blockIdx.x);
 }
 
 }  // namespace efqat

@@ -174,11 +174,14 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   constexpr int P0 = LPS / 4, P1 = (LPS - P0 + 2) / 3, P2 = (LPS - P0 - P1 + 1) / 2, P3 = LPS - P0 - P1 - P2;
   // end of a stage: the copies of the next stage have landed (the LPS copies issued after them, which belong to
   // the stage after next, may still be in flight), every wavefront is done reading this stage's buffer
-  auto stage_sync = [&](auto steadyc) {
+  // `tail`: one of the last two stages - every copy landed before it began and none is issued any more
+  auto stage_sync = [&](auto steadyc, bool tail) {
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (decltype(steadyc)::value) {
       static_assert(LPS == 12, "the wait count below is LPS");
       asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+    } else if (tail) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
@@ -205,6 +208,9 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
     }
   };
 
+  EpiDxFast<C> epi;                                   // used by EPI_DXF only
+  const int kt_epi = nk >= 2 ? nk - 2 : 0;            // the first of the last two stages
+
   // ---- main loop.  Stage kt lives in buffer kt % 3.  On entry to stage kt the first P0 copies of stage kt + 2 have
   // been issued if and only if that stage is a full one (kt + 2 < nfull); both variants keep this true for kt + 1.
   auto stage = [&](auto bufc, auto steadyc, int kt) {
@@ -217,12 +223,18 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
       substep(bufc, 1, 0, kt + 2, nn, P0, P0 + P1);
       substep(bufc, 2, 1, kt + 2, nn, P0 + P1, P0 + P1 + P2);
       substep(bufc, 3, 0, kt + 2, nn, P0 + P1 + P2, LPS);
-      stage_sync(steadyc);
+      stage_sync(steadyc, false);
       substep(Next{}, 0, 1, kt + 3, cur, 0, P0);
     } else {
       const bool more1 = kt + 1 < nk;
+      // the last two stages: the preceding barrier was passed with every copy landed (all drain stages before
+      // them wait for vmcnt(0)), and nothing more is issued - the moment to request the epilogue's first inputs
+      const bool tail = kt + 2 >= nk;
       if (kt + 2 < nfull) issue_range(Unchecked{}, kt + 2, nn, P0, LPS);
       else if (kt + 2 < nk) issue_range(Checked{}, kt + 2, nn, 0, LPS);
+      if constexpr (EPI == EPI_DXF) {
+        if (kt == kt_epi) epi.prefetch(g, m0, n0, wm, wn);
+      }
       __builtin_amdgcn_sched_barrier(0);
       load_frags(bufc, 1, 1);
       mfma_all(0);
@@ -232,7 +244,7 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
       __builtin_amdgcn_sched_barrier(0);
       load_frags(bufc, 3, 1);
       mfma_all(0);
-      stage_sync(steadyc);
+      stage_sync(steadyc, tail);
       if (more1) load_frags(Next{}, 0, 0);
       if (kt + 3 < nfull) issue_range(Unchecked{}, kt + 3, cur, 0, P0);
       mfma_all(1);
@@ -267,7 +279,7 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   if constexpr (EPI == EPI_DX) {
     epilogue_dx<C>(g, acc, smem, m0, n0, wm, wn);
   } else if constexpr (EPI == EPI_DXF) {
-    epilogue_dx_fast<C>(g, acc, smem, m0, n0, wm, wn);
+    epi.run(g, acc, smem, blockIdx.x);
   } else {
     float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
 #pragma unroll
