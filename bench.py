@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
+                    help="2: the weight-side calls of each layer run on a second stream, joined before its backward; "
+                         "1: one stream; 0: two streams except for the small convolution workload, whose kernels are "
+                         "shorter than the cross-stream joins cost")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -95,18 +99,27 @@ class Layer:
         need = max(bwd_ws + [L.efqat_fakequant_fwd_workspace_bytes(self.T_in, c_in, 0),
                              L.efqat_channel_select_workspace_bytes(c_out)])
         self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        # the weight-side calls (quantize W, select) get a workspace of their own: they may run on a second stream
+        need_w = max(L.efqat_fakequant_fwd_workspace_bytes(c_out, block, 1), L.efqat_channel_select_workspace_bytes(c_out))
+        self.ws_w = torch.empty(max(need_w, 256), dtype=torch.uint8, device=dev)
+
+    def quant_x(self, ef):
+        x2 = self.x.view(self.T_in, self.c_in)
+        fx2 = dict(self.fx, codes=self.fx["codes"].view(self.T_in, self.c_in))
+        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=fx2)
+
+    def quant_w(self, ef):
+        w2 = self.w.view(self.c_out, -1)
+        fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
+        ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws_w, out=fw2)
 
     def forward_quant(self, ef):
-        x2 = self.x.view(self.T_in, self.c_in)
-        w2 = self.w.view(self.c_out, -1)
-        fx2 = dict(self.fx, codes=self.fx["codes"].view(self.T_in, self.c_in))
-        fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
-        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=fx2)
-        ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws, out=fw2)
+        self.quant_x(ef)
+        self.quant_w(ef)
 
     def select(self, ef, k):
         idx = self.idx_full[:k]
-        ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws, out=dict(scores=self.scores, idx=idx))
+        ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws_w, out=dict(scores=self.scores, idx=idx))
         return idx
 
     def backward(self, ef, idx):
@@ -200,11 +213,33 @@ def main():
                   for i, n in enumerate(("conv", "conv1x1"))]
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
+    # The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
+    # do not depend on its activations, so the step issues them on a second stream of the same (default) priority and
+    # joins them before the layer's backward.  ev_bwd keeps the next step from rewriting a layer's weight codes and
+    # idx while this step's backward still reads them.  --streams 1 issues everything on one stream.
+    if args.streams == 0:
+        args.streams = 1 if args.workload == "cfg4" else 2
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream() if args.streams == 2 else None
+    ev_w = [torch.cuda.Event() for _ in layers]
+    ev_bwd = [torch.cuda.Event() for _ in layers]
+
     def step():
-        for l, k in zip(layers, ks):
-            l.forward_quant(ef)
-            idx = l.select(ef, k)
+        for i, (l, k) in enumerate(zip(layers, ks)):
+            if side_stream is None:
+                l.forward_quant(ef)
+                idx = l.select(ef, k)
+            else:
+                side_stream.wait_event(ev_bwd[i])
+                with torch.cuda.stream(side_stream):
+                    l.quant_w(ef)
+                    idx = l.select(ef, k)
+                    ev_w[i].record(side_stream)
+                l.quant_x(ef)
+                main_stream.wait_event(ev_w[i])
             l.backward(ef, idx)
+            if side_stream is not None:
+                ev_bwd[i].record(main_stream)
 
     for _ in range(args.warmup):
         step()
@@ -313,7 +348,7 @@ def main():
                config=dict(workload="%s: %s, r=%d/%d, W%dA%d, dY %s-major" % (
                    args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
                    num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
-                   k=ks, step="fakequant(X,W) + select + restricted backward, every layer"),
+                   k=ks, step="fakequant(X,W) + select + restricted backward, every layer", streams=args.streams),
                roofline=roofline, sweep=sweep, forward_int8=fwd, bias_grad=bias,
                paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
     if args.calibrate_copy:
