@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
 // to T that still belong to the selection (as soon as at most 64 candidates remain they are ranked directly); then one ordered sweep writes every index whose score is > T, plus the first `need` indices
 // (ascending) whose score equals T: ties go to the lower index, output is ascending.  Integer counting only,
 // so the result does not depend on thread scheduling.
-template <int NTH>
+template <int NTH, int KPT>
 __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
                                                      int32_t* __restrict__ idx) {
   constexpr int NW = NTH / 64;                        // wavefronts
@@ -44,10 +44,9 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
   __shared__ unsigned long long cand_key[64];
   __shared__ int cand_idx[64];
   __shared__ int s_bin_count, s_ncand;
-  __shared__ int scan_gt[12 * NW + 64], scan_eq[12 * NW + 64];   // KPT x wavefronts (cached case), padded to whole lanes
+  __shared__ int scan_gt[KPT * NW + 64], scan_eq[KPT * NW + 64]; // KPT x wavefronts (cached case), padded to whole lanes
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  // Up to KPT keys per thread stay in registers for all passes (n <= 12288); longer inputs are re-read.
-  constexpr int KPT = 12;
+  // Up to KPT keys per thread stay in registers for all passes (n <= KPT * NTH); longer inputs are re-read.
   constexpr int EPL = (KPT * NW + 63) / 64;           // scan entries per lane of the ordered output
   unsigned long long keys[KPT];
   const bool cached = n <= (int64_t)KPT * NTH;
@@ -272,10 +271,13 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
   }
 }
 
-// short inputs (BERT / ResNet channel counts) fit the registers of four wavefronts, whose barriers are cheaper
+// Short inputs (BERT / ResNet channel counts) fit the registers of four wavefronts, whose barriers are cheaper; the
+// number of keys per thread is a template argument so that a short input does not walk through empty slots.
 static void launch_topk(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st) {
-  if (n <= 12 * 256) hipLaunchKernelGGL(k_topk_radix<256>, dim3(1), dim3(256), 0, st, scores, n, k, idx);
-  else hipLaunchKernelGGL(k_topk_radix<1024>, dim3(1), dim3(1024), 0, st, scores, n, k, idx);
+  if (n <= 256) hipLaunchKernelGGL((k_topk_radix<256, 1>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
+  else if (n <= 4 * 256) hipLaunchKernelGGL((k_topk_radix<256, 4>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
+  else if (n <= 12 * 256) hipLaunchKernelGGL((k_topk_radix<256, 12>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
+  else hipLaunchKernelGGL((k_topk_radix<1024, 12>), dim3(1), dim3(1024), 0, st, scores, n, k, idx);
 }
 
 // CWPN helpers: per-layer counts of selected channels, and global -> per-layer local indices.
