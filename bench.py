@@ -57,14 +57,14 @@ class Layer:
     """Device buffers of one layer, all allocated up front (nothing is allocated in a timed region)."""
 
     def __init__(self, ef, torch, name, seed, T, c_in, c_out, act_dtype, a_bits, w_bits, layout, synth, fracs,
-                 conv=None):
+                 conv=None, row_sigma=0.0):
         self.name, self.c_in, self.c_out, self.conv = name, c_in, c_out, conv
         self.a_bits, self.w_bits, self.layout = a_bits, w_bits, layout
         L = ef.lib()
         dyd = 1 if act_dtype == "bf16" else 0
         ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
         if conv is None:
-            X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype)
+            X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype, row_scale_sigma=row_sigma)
             self.T, self.T_in, self.taps = T, T, 1
             bwd_ws = [L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k_, dyd, layout) for k_ in ks]
         else:
@@ -116,6 +116,21 @@ class Layer:
     def forward_quant(self, ef):
         self.quant_x(ef)
         self.quant_w(ef)
+
+    def requant_given(self, ef):
+        """Quantise X and W again with the scales / zero point the buffers hold (no min/max initialisation)."""
+        x2 = self.x.view(self.T_in, self.c_in)
+        w2 = self.w.view(self.c_out, -1)
+        fx2 = dict(self.fx, codes=self.fx["codes"].view(self.T_in, self.c_in))
+        fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
+        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, False, ws=self.ws, out=fx2)
+        ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, False, ws=self.ws_w, out=fw2)
+
+    def clipped_fraction(self, torch):
+        """Share of the activation elements whose clip-mask bit is 0 (columns are a multiple of 32 in every workload)."""
+        table = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=self.x.device)
+        ones = int(table[self.fx["clip_bits"].view(torch.uint8).long()].sum().item())
+        return 1.0 - ones / float(self.T_in * self.c_in)
 
     def select(self, ef, k):
         idx = self.idx_full[:k]
@@ -299,6 +314,43 @@ def main():
         for row, key in zip(sweep, fr):
             row["speedup_vs_full"] = full / times[key]
 
+    # The backward call at the headline fraction on inputs of different structure (not part of `value`): a contiguous
+    # block of channels (the best case for the compaction of dY columns; the selected set of i.i.d. rows is scattered,
+    # the worst case), scales shrunk to 0.7x after the min/max initialisation (a few per cent of the elements fall
+    # outside the range, so the clip masks and dZ_x do real work), and weight rows with log-normal factors (a few
+    # dominant channels, as in trained networks; linear workloads only).
+    variants = None
+    if not args.no_sweep:
+        def time_bwd(lays, idxs):
+            def bwd():
+                for l, idx in zip(lays, idxs):
+                    l.backward(ef, idx)
+            for _ in range(20):                          # host-side set-up precedes every variant: let the clocks settle
+                bwd()
+            return time_region(torch, bwd, max(3, args.steps)) * 1e3
+        for l in layers:
+            l.forward_quant(ef)
+        idx_sel = [l.select(ef, k) for l, k in zip(layers, ks)]
+        variants = dict(r="%d/%d" % (num, den), selected_idx_ms=time_bwd(layers, idx_sel))
+        idx_blk = [torch.arange(k, dtype=torch.int32, device="cuda") for k in ks]
+        variants["contiguous_idx_ms"] = time_bwd(layers, idx_blk)
+        for l in layers:
+            l.fx["scale"].mul_(0.7)
+            l.fw["scale"].mul_(0.7)
+            l.requant_given(ef)
+        variants["scales_x0p7_ms"] = time_bwd(layers, idx_sel)
+        variants["scales_x0p7_clipped_activation_share"] = [round(l.clipped_fraction(torch), 5) for l in layers]
+        for l in layers:
+            l.forward_quant(ef)                          # back to the min/max scales
+        if "layers" in cfg and args.workload != "cfg5":
+            lo = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
+                        args.dy_layout, synth, fracs, row_sigma=0.5) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
+            for l in lo:
+                l.forward_quant(ef)
+            idx_o = [l.select(ef, k) for l, k in zip(lo, ks)]
+            variants["lognormal_rows_sigma0p5_ms"] = time_bwd(lo, idx_o)
+            del lo, idx_o
+
     # low-precision forward (int8 matrix cores), not part of the step or of `value`: the paper leaves the forward
     # pass out of its timings
     fwd = None
@@ -349,7 +401,7 @@ def main():
                    args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
                    num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
                    k=ks, step="fakequant(X,W) + select + restricted backward, every layer", streams=args.streams),
-               roofline=roofline, sweep=sweep, forward_int8=fwd, bias_grad=bias,
+               roofline=roofline, sweep=sweep, variants=variants, forward_int8=fwd, bias_grad=bias,
                paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
