@@ -307,9 +307,26 @@ def main():
             ef.profile_enable(False)
             times[(n_, d_)] = t
             fl = sum(l.flops(k) for l, k in zip(layers, kk))
+            # the same call layer by layer: total, the dX product, the dW product, and the rest (operand preparation,
+            # compaction of the selected dY columns, second pass with the masks, scatter and dS_w)
+            per_layer = []
+            for l, idx, k_ in zip(layers, idxs, kk):
+                one = lambda: l.backward(ef, idx)
+                for _ in range(3):
+                    one()
+                tl = time_region(torch, one, max(3, args.steps // 2))
+                ef.profile_enable(True)
+                time_region(torch, one, max(3, args.steps // 4))
+                ldx, lndx = ef.profile_read(0)
+                ldw, lndw = ef.profile_read(1)
+                ef.profile_enable(False)
+                a_dx = ldx / max(lndx, 1)
+                a_dw = (ldw / lndw) if lndw else 0.0
+                per_layer.append(dict(name=l.name, k=k_, ms=tl * 1e3, tflops=l.flops(k_) / tl / 1e12, dx_kernel_ms=a_dx,
+                                      dw_kernel_ms=a_dw, other_ms=max(tl * 1e3 - a_dx - a_dw, 0.0)))
             sweep.append(dict(r="%d/%d" % (n_, d_), k=kk, ms=t * 1e3, tflops=fl / t / 1e12,
                               dx_kernel_ms=pdx / max(ndx, 1) * len(layers),
-                              dw_kernel_ms=(pdw / ndw * len(layers)) if ndw else 0.0))
+                              dw_kernel_ms=(pdw / ndw * len(layers)) if ndw else 0.0, layers=per_layer))
         full = times[(1, 1)]
         for row, key in zip(sweep, fr):
             row["speedup_vs_full"] = full / times[key]
