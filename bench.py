@@ -155,6 +155,37 @@ class Layer:
         return 2.0 * self.T * self.c_in * self.taps * (self.c_out + k)
 
 
+def make_step(torch, ef, layers, ks, streams):
+    """One step over `layers` with ks[i] selected channels each: quantize X and W, select, restricted backward.
+
+    The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
+    do not depend on its activations, so with streams == 2 they are issued on a second stream of the same (default)
+    priority and joined before the layer's backward; ev_bwd keeps the next step from rewriting a layer's weight
+    codes and idx while this step's backward still reads them.  streams == 1 issues everything on one stream."""
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream() if streams == 2 else None
+    ev_w = [torch.cuda.Event() for _ in layers]
+    ev_bwd = [torch.cuda.Event() for _ in layers]
+
+    def step():
+        for i, (l, k) in enumerate(zip(layers, ks)):
+            if side_stream is None:
+                l.forward_quant(ef)
+                idx = l.select(ef, k)
+            else:
+                side_stream.wait_event(ev_bwd[i])
+                with torch.cuda.stream(side_stream):
+                    l.quant_w(ef)
+                    idx = l.select(ef, k)
+                    ev_w[i].record(side_stream)
+                l.quant_x(ef)
+                main_stream.wait_event(ev_w[i])
+            l.backward(ef, idx)
+            if side_stream is not None:
+                ev_bwd[i].record(main_stream)
+    return step
+
+
 def time_region(torch, fn, steps):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -228,33 +259,9 @@ def main():
                   for i, n in enumerate(("conv", "conv1x1"))]
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
-    # The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
-    # do not depend on its activations, so the step issues them on a second stream of the same (default) priority and
-    # joins them before the layer's backward.  ev_bwd keeps the next step from rewriting a layer's weight codes and
-    # idx while this step's backward still reads them.  --streams 1 issues everything on one stream.
     if args.streams == 0:
         args.streams = 1 if args.workload == "cfg4" else 2
-    main_stream = torch.cuda.current_stream()
-    side_stream = torch.cuda.Stream() if args.streams == 2 else None
-    ev_w = [torch.cuda.Event() for _ in layers]
-    ev_bwd = [torch.cuda.Event() for _ in layers]
-
-    def step():
-        for i, (l, k) in enumerate(zip(layers, ks)):
-            if side_stream is None:
-                l.forward_quant(ef)
-                idx = l.select(ef, k)
-            else:
-                side_stream.wait_event(ev_bwd[i])
-                with torch.cuda.stream(side_stream):
-                    l.quant_w(ef)
-                    idx = l.select(ef, k)
-                    ev_w[i].record(side_stream)
-                l.quant_x(ef)
-                main_stream.wait_event(ev_w[i])
-            l.backward(ef, idx)
-            if side_stream is not None:
-                ev_bwd[i].record(main_stream)
+    step = make_step(torch, ef, layers, ks, args.streams)
 
     for _ in range(args.warmup):
         step()
