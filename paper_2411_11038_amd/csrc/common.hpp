@@ -42,6 +42,15 @@ __device__ __forceinline__ float load_as_f32<float>(const float* p, int64_t i) {
 template <>
 __device__ __forceinline__ float load_as_f32<bf16_t>(const bf16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
 
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin in dispatch order (x fastest, then
+// y).  This maps the dispatch-order id to a logical index under which every XCD owns one contiguous range of
+// [0, total): blocks with neighbouring logical indices - the tiles of one split-K slice, which share operand
+// tiles - run on the same XCD at the same time, so an operand tile is fetched into one L2 instead of into all.
+__device__ __forceinline__ int xcd_contiguous_index(int linear, int total) {
+  const int q8 = total >> 3, r8 = total & 7, x = linear & 7, j = linear >> 3;
+  return x * q8 + (x < r8 ? x : r8) + j;
+}
+
 // ---- wave-level reductions in a fixed butterfly order (deterministic)
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

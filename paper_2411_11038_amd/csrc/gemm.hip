@@ -94,9 +94,10 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
 
   // ---- block -> tile: spread contiguous tile ranges over the 8 XCDs (one L2 each), then walk the
   // range in groups of 8 row-tiles so that concurrently resident blocks share operand panels.
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int ntile = gridDim.x;
+  const int logical = xcd_contiguous_index(blockIdx.y * ntile + blockIdx.x, ntile * gridDim.y);
+  const int split = logical / ntile;                   // split-K slice (0 when there is one)
+  const int pid = logical - split * ntile;
   const int GM = EFQAT_GEMM_GM;
   const int per_group = GM * g.tiles_n;
   const int group = pid / per_group;
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   const int m0 = tm * BM, n0 = tn * BN;
   const int lm0 = m0, ln0 = n0;
 
-  const int k_begin = blockIdx.y * g.k_per_split;
+  const int k_begin = split * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
 
   // ---- operand staging.  One wave instruction of the direct global->LDS load (global_load_lds_dwordx4)
@@ -322,7 +323,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const GemmArgs g) {
   // ---- epilogue.  MFMA 32x32 accumulator layout: lane holds column (lane & 31) and rows
   // 8*(r/4) + 4*(lane >> 5) + (r % 4), r = 0..15.
   if constexpr (EPI == EPI_RAW) {
-    float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+    float* out = g.out + (int64_t)split * g.M * g.N;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll

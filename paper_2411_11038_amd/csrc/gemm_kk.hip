@@ -58,9 +58,10 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 
   // consecutive block ids land on different XCDs: give each XCD a contiguous range of tiles, then walk the tiles
   // in groups of GM tile rows so that the blocks running together share operand rows in L2
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int ntile = gridDim.x;
+  const int logical = xcd_contiguous_index(blockIdx.y * ntile + blockIdx.x, ntile * gridDim.y);
+  const int split = logical / ntile;                   // split-K slice (0 when there is one)
+  const int pid = logical - split * ntile;
   const int GM = 8;
   const int per_group = GM * g.tiles_n;
   const int group = pid / per_group;
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   const int tn = (pid % per_group) / gsize;
   const int m0 = tm * C::BM, n0 = tn * C::BN;
 
-  const int k_begin = blockIdx.y * g.k_per_split;
+  const int k_begin = split * g.k_per_split;
   const int k_end_ = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
   const int K = k_end_ > k_begin ? k_end_ - k_begin : 0;
   const int nk = (K + 63) / 64;
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   } else if constexpr (EPI == EPI_DXF) {
     epi.run(g, acc, smem, blockIdx.x);
   } else {
-    float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+    float* out = g.out + (int64_t)split * g.M * g.N;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll

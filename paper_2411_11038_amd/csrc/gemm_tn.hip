@@ -69,9 +69,11 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / C::WGN, wn = wave % C::WGN;
 
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  // (tile, split-K slice) of this block: slice-major logical order, one contiguous range per XCD
+  const int ntile = gridDim.x;
+  const int logical = xcd_contiguous_index(blockIdx.y * ntile + blockIdx.x, ntile * gridDim.y);
+  const int split = logical / ntile;
+  const int pid = logical - split * ntile;
   const int GM = 8;
   const int per_group = GM * g.tiles_n;
   const int group = pid / per_group;
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
   const int tn = (pid % per_group) / gsize;
   const int m0 = tm * C::BM, n0 = tn * C::BN;
 
-  const int k_begin = blockIdx.y * g.k_per_split;
+  const int k_begin = split * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K;
   const int span = k_end - k_begin;
   const int nk = span > 0 ? (span + 63) / 64 : 0;
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(const GemmTnArgs g) {
 
   // ---- raw fp32 partial tile.  Accumulator layout of the 32x32 MFMA: column lane & 31, rows 8 (r/4) + 4 (lane/32) + r%4.
   const int fr = lane & 31, fh = lane >> 5;
-  float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+  float* out = g.out + (int64_t)split * g.M * g.N;
 #pragma unroll
   for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -444,9 +446,10 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = 0, wn = wave;
 
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int ntile = gridDim.x;
+  const int logical = xcd_contiguous_index(blockIdx.y * ntile + blockIdx.x, ntile * gridDim.y);
+  const int split = logical / ntile;                   // split-K slice (0 when there is one)
+  const int pid = logical - split * ntile;
   const int GM = 8;
   const int per_group = GM * g.tiles_n;
   const int group = pid / per_group;
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   const int m0 = tm * C::BM, n0 = tn * C::BN;
 
   // K range of this block: everything for dX, one split-K slice for dW (K below is the length of the slice)
-  const int k_begin = DW ? blockIdx.y * g.k_per_split : 0;
+  const int k_begin = DW ? split * g.k_per_split : 0;
   const int k_end_ = DW ? ((k_begin + g.k_per_split) < g.K ? (k_begin + g.k_per_split) : g.K) : g.K;
   const int K = k_end_ > k_begin ? k_end_ - k_begin : 0;
   const int nk = (K + 63) / 64;
@@ -745,7 +748,7 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
   __syncthreads();
 
   if constexpr (DW) {
-    float* out = g.out + (int64_t)blockIdx.y * g.M * g.N;
+    float* out = g.out + (int64_t)split * g.M * g.N;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
