@@ -326,6 +326,32 @@ def test_linear_bwd_matches_oracle(case):
     _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
 
 
+def _random_case(seed):
+    """A seeded small layer with nothing aligned on purpose: shapes, dtypes, layout, fraction, scatter, bit widths."""
+    rng = np.random.default_rng(9000 + seed)
+    T = int(rng.integers(1, 420)); c_in = int(rng.integers(1, 330)); c_out = int(rng.integers(1, 330))
+    if seed % 4 == 0:                                    # some whole-tile shapes as well
+        T = 192 * int(rng.integers(1, 3)); c_in = 64 * int(rng.integers(1, 5))
+    kind = "bf16" if rng.integers(0, 3) else "f32"
+    layout = int(rng.integers(0, 2))
+    num, den = [(0, 1), (1, 7), (1, 3), (1, 1), (1, 20)][int(rng.integers(0, 5))]
+    return (T, c_in, c_out, kind, [8, 4][int(rng.integers(0, 2))], [8, 4][int(rng.integers(0, 2))],
+            [1.0, 0.7, 0.5][int(rng.integers(0, 3))], (num, den), layout, bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_linear_bwd_random_shapes_match_oracle(seed):
+    T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter = _random_case(seed)
+    X, W, dY = synth.linear_layer(5000 + seed, T, c_in, c_out, act_dtype=kind)
+    out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout,
+                                                     scatter)
+    assert np.array_equal(fx["codes"].cpu().numpy().astype(np.int64), ref["x_codes"])
+    assert np.array_equal(fw["codes"].cpu().numpy().astype(np.int64), ref["w_codes"])
+    assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"]))
+    assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"]))
+    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+
+
 # dX product with the weight operand read from the int8 codes (bf16 token-major dY, C_out % 8 == 0, C_in % 16 == 0):
 # forced through the option hook so that both tile sizes meet ragged edges in every dimension
 DX8_CASES = [
@@ -551,6 +577,26 @@ def test_conv_bwd_pinned_dx_kernel_on_im2col_matrix(case):
         _conv_case(case)
     finally:
         ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
+
+
+def _random_conv_case(seed):
+    """A seeded small convolution: image, channels, kernel, stride, padding, dtype, layout and fraction all drawn."""
+    rng = np.random.default_rng(9500 + seed)
+    kh, kw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, 3))
+    H, Wd = int(rng.integers(kh, 13)), int(rng.integers(kw, 13))
+    N = int(rng.integers(1, 5))
+    c_in = [int(rng.integers(1, 90)), 128, 64][int(rng.integers(0, 3))]
+    c_out = [int(rng.integers(1, 90)), 64, 128][int(rng.integers(0, 3))]
+    kind = "bf16" if rng.integers(0, 3) else "f32"
+    num, den = [(0, 1), (1, 7), (1, 3), (1, 1)][int(rng.integers(0, 4))]
+    return (N, H, Wd, c_in, c_out, kh, kw, stride, pad, kind, [8, 4][int(rng.integers(0, 2))],
+            [1.0, 0.7][int(rng.integers(0, 2))], (num, den), int(rng.integers(0, 2)), bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_conv_bwd_random_shapes_match_oracle(seed):
+    _conv_case(_random_conv_case(seed))
 
 
 def _conv_case(case):
