@@ -210,23 +210,31 @@ __global__ __launch_bounds__(256) void k_im2col_dy(const bf16_t* __restrict__ dy
 
 // ------------------------------------------------------------------------------------------------
 // dS_x, dZ_x: ordered sum of the per-block partials written by the dX epilogue.
+template <int NTH>
 __device__ __forceinline__ void sum_partials_block(const float* __restrict__ part, int64_t n,
                                                    float* __restrict__ ds_x, float* __restrict__ dz_x) {
+  constexpr int NW = NTH / 64;
   double a = 0.0, b = 0.0;
-  for (int64_t i = threadIdx.x; i < n; i += 256) { a += (double)part[2 * i]; b += (double)part[2 * i + 1]; }
+  for (int64_t i = threadIdx.x; i < n; i += NTH) { a += (double)part[2 * i]; b += (double)part[2 * i + 1]; }
   a = wave_sum(a); b = wave_sum(b);
-  __shared__ double sa[4], sb[4];
+  __shared__ double sa[NW], sb[NW];
   if ((threadIdx.x & 63) == 0) { sa[threadIdx.x >> 6] = a; sb[threadIdx.x >> 6] = b; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    ds_x[0] = (float)((sa[0] + sa[1]) + (sa[2] + sa[3]));
-    dz_x[0] = (float)((sb[0] + sb[1]) + (sb[2] + sb[3]));
+    double ta = 0.0, tb = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; w += 4) {                  // fixed order
+      ta += (sa[w] + sa[w + 1]) + (sa[w + 2] + sa[w + 3]);
+      tb += (sb[w] + sb[w + 1]) + (sb[w + 2] + sb[w + 3]);
+    }
+    ds_x[0] = (float)ta;
+    dz_x[0] = (float)tb;
   }
 }
 
 __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, int64_t n,
                                                       float* __restrict__ ds_x, float* __restrict__ dz_x) {
-  sum_partials_block(part, n, ds_x, dz_x);
+  sum_partials_block<256>(part, n, ds_x, dz_x);
 }
 
 // Optional optimizer step fused into the second pass (off when w == nullptr): SGD with momentum and weight decay
@@ -240,7 +248,9 @@ struct SgdArgs {
 // Second pass of the restricted weight gradient: ordered split-K sum, S_x scaling, straight-through mask
 // of the weight quantizer and the per-row scale gradient
 //   dW[c][j] = in range ? dW_q : 0,  dS_w[c] = sum_j dW_q * (in range ? code - w/S_w : code),  c = idx[m].
-__global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ part, int S, int64_t k, int64_t ncols,
+// One block of NTH threads per row: 256, or 1024 for long rows, so that a row is one trip through the loop.
+template <int NTH>
+__global__ __launch_bounds__(NTH) void k_dw_finish(const float* __restrict__ part, int S, int64_t k, int64_t ncols,
                                                    int vec, const float* __restrict__ s_x,
                                                    const int8_t* __restrict__ w_codes,
                                                    const uint32_t* __restrict__ w_clip, const float* __restrict__ w,
@@ -250,7 +260,7 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
                                                    float* __restrict__ ds_x, float* __restrict__ dz_x,
                                                    const SgdArgs sgd) {
   if ((int64_t)blockIdx.x == k) {                     // one extra block: dS_x, dZ_x from the dX epilogue's partials
-    sum_partials_block(part_dx, n_part_dx, ds_x, dz_x);
+    sum_partials_block<NTH>(part_dx, n_part_dx, ds_x, dz_x);
     return;
   }
   const int64_t m = blockIdx.x;
@@ -262,7 +272,7 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
   const int64_t slice = k * ncols;
   float acc = 0.0f;
   if (vec) {                                          // ncols % 4 == 0 and 16-byte aligned rows
-    for (int64_t j = (int64_t)threadIdx.x * 4; j < ncols; j += 1024) {
+    for (int64_t j = (int64_t)threadIdx.x * 4; j < ncols; j += 4 * NTH) {
       const float* p = part + m * ncols + j;
       float4 a = *reinterpret_cast<const float4*>(p);
       int s = 1;
@@ -309,7 +319,7 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
       }
     }
   } else {
-    for (int64_t j = threadIdx.x; j < ncols; j += 256) {
+    for (int64_t j = threadIdx.x; j < ncols; j += NTH) {
       float a = 0.0f;
       for (int s = 0; s < S; ++s) a += part[(int64_t)s * slice + m * ncols + j];
       const float dwq = sx * a;
@@ -331,11 +341,13 @@ __global__ __launch_bounds__(256) void k_dw_finish(const float* __restrict__ par
     }
   }
   acc = wave_sum(acc);
-  __shared__ float red[4];
+  __shared__ float red[NTH / 64];
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) {
-    const float ds = (red[0] + red[1]) + (red[2] + red[3]);
+    float ds = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NTH / 64; w += 4) ds += (red[w] + red[w + 1]) + (red[w + 2] + red[w + 3]);   // fixed order
     if (ds_w) ds_w[orow] = ds;
     if (sgd.s_w) {
       float gq = ds;
@@ -635,9 +647,15 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0 && ((uintptr_t)io.sgd.mom_w % 16) == 0) ? 1 : 0;
   // k blocks for the rows of dW plus one that finishes dS_x, dZ_x
-  hipLaunchKernelGGL(k_dw_finish, dim3((unsigned)io.k + 1), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k, p.Nw,
-                     fvec, io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w, part_dx,
-                     n_part_dx, io.ds_x, io.dz_x, io.sgd);
+  // long rows and few of them: the chain of dependent loads per row, not bandwidth, sets the time
+  if (fvec && p.Nw >= 2048 && io.k < 512)
+    hipLaunchKernelGGL(k_dw_finish<1024>, dim3((unsigned)io.k + 1), dim3(1024), 0, st, part_dw, p.plan_dw.split_k, io.k,
+                       p.Nw, fvec, io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w,
+                       part_dx, n_part_dx, io.ds_x, io.dz_x, io.sgd);
+  else
+    hipLaunchKernelGGL(k_dw_finish<256>, dim3((unsigned)io.k + 1), dim3(256), 0, st, part_dw, p.plan_dw.split_k, io.k,
+                       p.Nw, fvec, io.s_x, io.w_codes, io.w_clip, io.w, io.s_w, io.idx, io.dw, io.scatter, io.ds_w,
+                       part_dx, n_part_dx, io.ds_x, io.dz_x, io.sgd);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
