@@ -62,6 +62,7 @@ class Layer:
         self.a_bits, self.w_bits, self.layout = a_bits, w_bits, layout
         L = ef.lib()
         dyd = 1 if act_dtype == "bf16" else 0
+        self.dyd = dyd
         ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
         if conv is None:
             X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype, row_scale_sigma=row_sigma)
@@ -102,6 +103,9 @@ class Layer:
         # the weight-side calls (quantize W, select) get a workspace of their own: they may run on a second stream
         need_w = max(L.efqat_fakequant_fwd_workspace_bytes(c_out, block, 1), L.efqat_channel_select_workspace_bytes(c_out))
         self.ws_w = torch.empty(max(need_w, 256), dtype=torch.uint8, device=dev)
+        # bf16 W_q^T operand of the dX product, when the layer uses one: made on the weight side of the step
+        nop = 0 if conv is not None else L.efqat_linear_bwd_weight_operand_bytes(self.T, c_in, c_out, dyd, layout)
+        self.w_op = torch.empty(nop, dtype=torch.uint8, device=dev) if nop else None
 
     def quant_x(self, ef):
         x2 = self.x.view(self.T_in, self.c_in)
@@ -112,6 +116,11 @@ class Layer:
         w2 = self.w.view(self.c_out, -1)
         fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
         ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws_w, out=fw2)
+
+    def prepare_w(self, ef):
+        if self.w_op is not None:
+            ef.linear_bwd_weight_operand(self.fw["codes"].view(self.c_out, -1), self.fw["scale"], self.T,
+                                         self.dyd, self.layout, out=self.w_op)
 
     def forward_quant(self, ef):
         self.quant_x(ef)
@@ -137,13 +146,14 @@ class Layer:
         ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws_w, out=dict(scores=self.scores, idx=idx))
         return idx
 
-    def backward(self, ef, idx):
+    def backward(self, ef, idx, prepared=False):
         k = int(idx.numel())
         out = dict(dx=self.dx, dw=self.dw[:max(k, 1)], ds_w=self.ds_w[:max(k, 1)], ds_x=self.ds_x, dz_x=self.dz_x)
         if self.conv is None:
             ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                           self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
-                          idx if k else None, dy_layout=self.layout, ws=self.ws, out=out)
+                          idx if k else None, dy_layout=self.layout, ws=self.ws, out=out,
+                          w_operand=self.w_op if prepared else None)
         else:
             ef.conv_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                         self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
@@ -160,8 +170,10 @@ def make_step(torch, ef, layers, ks, streams):
 
     The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
     do not depend on its activations, so with streams == 2 they are issued on a second stream of the same (default)
-    priority and joined before the layer's backward; ev_bwd keeps the next step from rewriting a layer's weight
-    codes and idx while this step's backward still reads them.  streams == 1 issues everything on one stream."""
+    priority and joined before the layer's backward, together with the bf16 weight operand of the dX product
+    (efqat_linear_bwd_weight_operand; the backward is then efqat_linear_bwd_prepared); ev_bwd keeps the next step
+    from rewriting a layer's weight codes, operand and idx while this step's backward still reads them.
+    streams == 1 issues everything on one stream through the plain entry points."""
     main_stream = torch.cuda.current_stream()
     side_stream = torch.cuda.Stream() if streams == 2 else None
     ev_w = [torch.cuda.Event() for _ in layers]
@@ -176,11 +188,12 @@ def make_step(torch, ef, layers, ks, streams):
                 side_stream.wait_event(ev_bwd[i])
                 with torch.cuda.stream(side_stream):
                     l.quant_w(ef)
+                    l.prepare_w(ef)                      # the bf16 W_q^T operand of the dX product, where one is used
                     idx = l.select(ef, k)
                     ev_w[i].record(side_stream)
                 l.quant_x(ef)
                 main_stream.wait_event(ev_w[i])
-            l.backward(ef, idx)
+            l.backward(ef, idx, prepared=side_stream is not None)
             if side_stream is not None:
                 ev_bwd[i].record(main_stream)
     return step

@@ -219,6 +219,39 @@ int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int
                      int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                      float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------ weight operand made beforehand
+ * Where the dX product (Eq. 5 left) of efqat_linear_bwd multiplies by a bf16 copy of W_q^T,
+ * that copy depends on the weight codes and scales only, not on dY or the activations.  A
+ * caller that quantizes its weights away from the critical path (another stream, an earlier
+ * point of the step) can have it made there and hand it to efqat_linear_bwd_prepared, which
+ * then skips that pass; results are bit-identical to efqat_linear_bwd.
+ *
+ *   efqat_linear_bwd_weight_operand_bytes  size of the operand buffer for a layer, or 0 when the
+ *       dX product of that layer reads the int8 codes themselves (no copy exists; the two
+ *       calls below then ignore the buffer).  Depends on EFQAT_OPT_DX_KERNEL like the
+ *       workspace size.
+ *   efqat_linear_bwd_weight_operand        fills it from w_codes int8 [c_out][c_in] and s_w
+ *       float [c_out]: operand = bf16 [c_in][round_up(c_out, 8)] with
+ *       operand[i][c] = bf16(s_w[c] * w_codes[c][i]), zero padding, then 256 zero bytes.
+ *       operand: device, 256-byte aligned, owned by the caller, read-only afterwards.
+ *   efqat_linear_bwd_prepared              efqat_linear_bwd with one more argument, w_operand
+ *       (NULL: exactly efqat_linear_bwd).  The operand must come from the same w_codes, s_w,
+ *       sizes, dy_dtype and dy_layout, and the work that fills it must be ordered before this
+ *       call's stream reaches it (the caller's events).
+ * Errors as in efqat_linear_bwd; a buffer that is too small is EFQAT_ERR_WORKSPACE. */
+size_t efqat_linear_bwd_weight_operand_bytes(int64_t T, int64_t c_in, int64_t c_out, int dy_dtype,
+                                             int dy_layout);
+int efqat_linear_bwd_weight_operand(const int8_t* w_codes, const float* s_w, int64_t T, int64_t c_in,
+                                    int64_t c_out, int dy_dtype, int dy_layout, void* operand,
+                                    size_t operand_bytes, void* stream);
+int efqat_linear_bwd_prepared(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                              int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
+                              const void* x, int x_dtype, const float* s_x, const float* z_x,
+                              const int8_t* w_codes, const uint32_t* w_clip, const float* w,
+                              const float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                              float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                              const void* w_operand, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------ backward + optimizer step
  * efqat_linear_bwd followed, in the same pass over the k updated rows, by the optimizer step
  * that Alg. 1 applies to unfrozen channels (SGD; frozen rows, their scales and their momentum

@@ -19,6 +19,7 @@ EXPORTS = [
     "efqat_layer_select_workspace_bytes", "efqat_layer_select",
     "efqat_bias_grad_workspace_bytes", "efqat_bias_grad",
     "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
+    "efqat_linear_bwd_weight_operand_bytes", "efqat_linear_bwd_weight_operand", "efqat_linear_bwd_prepared",
     "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd", "efqat_linear_bwd_sgd", "efqat_conv_bwd_sgd",
     "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
     "efqat_profile_enable", "efqat_profile_read", "efqat_set_option",
@@ -84,6 +85,13 @@ def lib():
     L.efqat_linear_bwd.restype = ci
     L.efqat_linear_bwd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
                                    + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_linear_bwd_weight_operand_bytes.restype = sz
+    L.efqat_linear_bwd_weight_operand_bytes.argtypes = [i64, i64, i64, ci, ci]
+    L.efqat_linear_bwd_weight_operand.restype = ci
+    L.efqat_linear_bwd_weight_operand.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, sz, vp]
+    L.efqat_linear_bwd_prepared.restype = ci
+    L.efqat_linear_bwd_prepared.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
+                                            + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, vp, sz, vp])
     L.efqat_linear_bwd_sgd.restype = ci
     L.efqat_linear_bwd_sgd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
                                        + [vp, i64, vp, ci, vp, ci, vp, vp, vp] + [C.POINTER(SgdStep), vp, sz, vp])
@@ -287,11 +295,28 @@ def _sgd_struct(sgd):
                    float(sgd.get("weight_decay", 0.0)), _p(sgd.get("mom_w")), _p(sgd.get("mom_s")))
 
 
+def linear_bwd_weight_operand(w_codes, s_w, T, dy_dtype=BF16, dy_layout=DY_TOKEN_MAJOR, out=None):
+    """The bf16 W_q^T operand of the dX product, made ahead of efqat_linear_bwd_prepared (argument w_operand of
+    linear_bwd).  Returns a uint8 tensor, or None when the layer's dX product reads the int8 codes themselves."""
+    L = lib()
+    c_out, c_in = w_codes.shape
+    need = L.efqat_linear_bwd_weight_operand_bytes(T, c_in, c_out, dy_dtype, dy_layout)
+    if need == 0:
+        return None
+    if out is None:
+        out = torch.empty(need, dtype=torch.uint8, device=w_codes.device)
+    rc = L.efqat_linear_bwd_weight_operand(_p(w_codes), _p(s_w), T, c_in, c_out, dy_dtype, dy_layout, _p(out),
+                                           out.numel(), _stream())
+    _check(rc, "efqat_linear_bwd_weight_operand")
+    return out
+
+
 def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, dy_layout=DY_TOKEN_MAJOR,
-               dx_dtype=None, scatter=False, ws=None, out=None, sgd=None):
+               dx_dtype=None, scatter=False, ws=None, out=None, sgd=None, w_operand=None):
     """Backward of one quantized linear layer restricted to the rows idx.  Returns
     dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys).
-    sgd: dict for the fused optimizer step (efqat_linear_bwd_sgd): w and s_w are then updated in place."""
+    sgd: dict for the fused optimizer step (efqat_linear_bwd_sgd): w and s_w are then updated in place.
+    w_operand: the tensor made by linear_bwd_weight_operand for these weights (efqat_linear_bwd_prepared)."""
     L = lib()
     T, c_in = x_codes.shape
     c_out = w_codes.shape[0]
@@ -308,9 +333,13 @@ def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, d
             _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
             _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
             int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x))
-    if sgd is None:
+    if sgd is None and w_operand is not None:
+        rc = L.efqat_linear_bwd_prepared(*args, _p(w_operand), _p(ws), ws.numel(), _stream())
+    elif sgd is None:
         rc = L.efqat_linear_bwd(*args, _p(ws), ws.numel(), _stream())
     else:
+        if w_operand is not None:
+            raise ValueError("w_operand cannot be combined with the fused optimizer step")
         step = _sgd_struct(sgd)
         rc = L.efqat_linear_bwd_sgd(*args, C.byref(step), _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_linear_bwd")

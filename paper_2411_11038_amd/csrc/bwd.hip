@@ -481,6 +481,7 @@ struct BwdIo {
   const int8_t* w_codes; const uint32_t* w_clip; const float* w; const float* s_w; const int32_t* idx; int64_t k;
   void* dx; int dx_dtype; float* dw; int scatter; float* ds_w; float* ds_x; float* dz_x;
   SgdArgs sgd;     // fused optimizer step (sgd.w == nullptr: none)
+  const void* w_operand = nullptr;   // optional: the bf16 W_q^T matrix (then 256 zero bytes) made beforehand
 };
 
 // Shared driver.  For conv, T_in = N*H*W input pixels, T_out = N*Ho*Wo output pixels; for linear both are T.
@@ -503,7 +504,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   int rc;
 
   // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
-  if (p.dx8) {
+  if (!p.dx8 && io.w_operand) {
+    // made beforehand by efqat_linear_bwd_weight_operand (same kernel, same bits), with its own zero page behind it
+    wqT = (bf16_t*)const_cast<void*>(io.w_operand);
+    zero_page = (char*)const_cast<void*>(io.w_operand) + round_up((int64_t)p.b_wqT, 256);
+  } else if (p.dx8) {
     hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(64), 0, st, (uint32_t*)zero_page);
     EFQAT_LAUNCH_CHECK();
   } else {
@@ -711,6 +716,52 @@ extern "C" int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int
   int rc = check_common(io, c_out, ws);
   if (rc) return rc;
   if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
+  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
+}
+
+extern "C" size_t efqat_linear_bwd_weight_operand_bytes(int64_t T, int64_t c_in, int64_t c_out, int dy_dtype,
+                                                        int dy_layout) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30)) return 0;
+  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false);
+  return p.dx8 ? 0 : (size_t)round_up((int64_t)p.b_wqT, 256) + 256;
+}
+
+extern "C" int efqat_linear_bwd_weight_operand(const int8_t* w_codes, const float* s_w, int64_t T, int64_t c_in,
+                                               int64_t c_out, int dy_dtype, int dy_layout, void* operand,
+                                               size_t operand_bytes, void* stream) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
+    return EFQAT_ERR_BAD_SHAPE;
+  if (dy_dtype != EFQAT_F32 && dy_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
+  if (dy_layout != EFQAT_DY_TOKEN_MAJOR && dy_layout != EFQAT_DY_CHANNEL_MAJOR) return EFQAT_ERR_BAD_LAYOUT;
+  const size_t need = efqat_linear_bwd_weight_operand_bytes(T, c_in, c_out, dy_dtype, dy_layout);
+  if (need == 0) return EFQAT_OK;                      // this layer's dX product reads the int8 codes themselves
+  if (!w_codes || !s_w || !operand) return EFQAT_ERR_NULL_PTR;
+  if (operand_bytes < need) return EFQAT_ERR_WORKSPACE;
+  if (((uintptr_t)operand % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false);
+  TransposeExtra ex{};
+  ex.z_in = c_in; ex.z_out = p.ldc;
+  uint32_t* zero_page = (uint32_t*)((char*)operand + round_up((int64_t)p.b_wqT, 256));
+  return transpose_to_bf16<int8_t>(w_codes, c_in, c_out, c_in, nullptr, s_w, nullptr, (bf16_t*)operand, p.Kx, 0,
+                                   p.ldc, (hipStream_t)stream, zero_page, 1, &ex);
+}
+
+extern "C" int efqat_linear_bwd_prepared(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                                         int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
+                                         const void* x, int x_dtype, const float* s_x, const float* z_x,
+                                         const int8_t* w_codes, const uint32_t* w_clip, const float* w,
+                                         const float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                                         float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                                         const void* w_operand, void* ws, size_t ws_bytes, void* stream) {
+  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
+    return EFQAT_ERR_BAD_SHAPE;
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  int rc = check_common(io, c_out, ws);
+  if (rc) return rc;
+  if (w_operand && ((uintptr_t)w_operand % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
+  io.w_operand = w_operand;
   return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
 }
 

@@ -95,6 +95,25 @@ def test_argument_validation_needs_no_device():
     assert lin(ws=fake + 16) == -9
     assert lin(dy=fake + 2) == -9
 
+    # weight operand made beforehand
+    need = L.efqat_linear_bwd_weight_operand_bytes(384, 192, 384, 1, 0)
+    assert need == 192 * 384 * 2 + 256                 # bf16 [c_in][c_out] and a zero page
+    assert L.efqat_linear_bwd_weight_operand_bytes(8192, 4096, 11008, 1, 0) == 0     # reads the int8 codes instead
+    assert L.efqat_linear_bwd_weight_operand_bytes(0, 192, 384, 1, 0) == 0
+    def wop(codes=fake, sw=fake, T=384, op=fake, opb=need, dyd=1, lay=0):
+        return L.efqat_linear_bwd_weight_operand(codes, sw, T, 192, 384, dyd, lay, op, opb, None)
+    assert wop(codes=None) == -1 and wop(sw=None) == -1 and wop(op=None) == -1
+    assert wop(T=0) == -2
+    assert wop(opb=need - 1) == -6
+    assert wop(op=fake + 64) == -9
+    assert wop(dyd=5) == -8 and wop(lay=3) == -5
+    def lin_pre(wop_=fake, ws=fake, wsb=1 << 30, dy=fake):
+        return L.efqat_linear_bwd_prepared(dy, 1, 0, 8, 8, 8, fake, fake, fake, 1, fake, fake, fake, fake, fake,
+                                           fake, fake, 2, fake, 1, fake, 0, fake, fake, fake, wop_, ws, wsb, None)
+    assert lin_pre(dy=None) == -1
+    assert lin_pre(wop_=fake + 64) == -9
+    assert lin_pre(wsb=64) == -6 and lin_pre(wop_=None, wsb=64) == -6
+
     # fused optimizer step
     from paper_2411_11038_amd.binding import SgdStep
     def lin_sgd(step, w=fake, dw=fake):

@@ -326,6 +326,46 @@ def test_linear_bwd_matches_oracle(case):
     _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
 
 
+# (T, c_in, c_out, layout): the pinned 192-tile kernel, the 128-tile kernel with ragged edges, a padded C_out,
+# and two layers whose dX product reads the int8 codes (no operand exists: the call must behave like the plain one)
+PREPARED_CASES = [(384, 192, 384, 0), (300, 200, 136, 0), (129, 72, 43, 0), (2048, 512, 640, 0), (384, 256, 136, 1)]
+
+
+@pytest.mark.parametrize("case", PREPARED_CASES, ids=lambda c: "T%d_%dx%d_L%d" % c)
+def test_linear_bwd_with_weight_operand_made_beforehand_is_bit_identical(case):
+    T, c_in, c_out, layout = case
+    X, W, dY = synth.linear_layer(7000 + T, T, c_in, c_out, act_dtype="bf16")
+    xd, wd = act_tensor(X, "bf16"), dev(W)
+    fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, 8, init_minmax=True)
+    fw = ef.fakequant_fwd(wd, ef.W_PER_ROW_SYM, 8, init_minmax=True)
+    k = ef.k_from_ratio(c_out, 1, 4)
+    idx, _ = ef.channel_select(wd, k)
+    dyd = act_tensor(dY if layout == 0 else np.ascontiguousarray(dY.T), "bf16")
+    args = (dyd, fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"], fw["codes"], fw["clip_bits"], wd,
+            fw["scale"], idx)
+    ref = ef.linear_bwd(*args, dy_layout=layout)
+    op = ef.linear_bwd_weight_operand(fw["codes"], fw["scale"], T, ef.BF16, layout)
+    need = ef.lib().efqat_linear_bwd_weight_operand_bytes(T, c_in, c_out, ef.BF16, layout)
+    assert (op is None) == (need == 0)
+    if op is None:                                       # nothing to prepare: any aligned pointer is ignored
+        op = torch.zeros(256, dtype=torch.uint8, device=xd.device)
+    else:
+        # the operand is bf16(S_w[c] * code[c][i]) transposed, zero padded, followed by a zero page
+        ldc = (c_out + 7) // 8 * 8
+        got = op[:c_in * ldc * 2].view(torch.bfloat16).view(c_in, ldc).float().cpu().numpy()
+        wq = (fw["scale"].cpu().numpy()[:, None] * fw["codes"].cpu().numpy().astype(np.float32))
+        want = torch.from_numpy(wq.T.copy()).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(got[:, :c_out], want) and not got[:, c_out:].any()
+        assert not op[-256:].any()
+    out = ef.linear_bwd(*args, dy_layout=layout, w_operand=op)
+    torch.cuda.synchronize()
+    for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
+        a, b = out[key], ref[key]
+        if a.dtype == torch.bfloat16:
+            a, b = a.view(torch.int16), b.view(torch.int16)
+        assert torch.equal(a, b), key
+
+
 def _random_case(seed):
     """A seeded small layer with nothing aligned on purpose: shapes, dtypes, layout, fraction, scatter, bit widths."""
     rng = np.random.default_rng(9000 + seed)
