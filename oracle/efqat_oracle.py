@@ -242,11 +242,13 @@ def linear_bwd(dY, X, S_x, Z_x, a_bits, W, S_w, w_bits, idx):
     c_out, c_in = W.shape
     dW = np.zeros((c_out, c_in), dtype=np.float64)
     dS_w = np.zeros(c_out, dtype=np.float64)
+    dWq_sel = np.zeros((idx.size, c_in), dtype=np.float64)
     if idx.size:
         dWq_sel = dY[:, idx].T @ Xq                 # step 1-2 of Sec. 4 "Practical Speedups"
         dW[idx] = np.where(wm[idx], dWq_sel, 0.0)   # step 3: rows written back
         dS_w[idx] = grad_weight_scale(dWq_sel, W[idx], wc[idx], wm[idx], np.asarray(S_w)[idx])
-    return dict(dX=dX, dXq=dXq, dW=dW, dS_w=dS_w, dS_x=dS_x, dZ_x=dZ_x,
+    # dWq_sel: the un-masked rows idx of the weight gradient (an intermediate, handed out for error scales in tests)
+    return dict(dX=dX, dXq=dXq, dW=dW, dS_w=dS_w, dS_x=dS_x, dZ_x=dZ_x, dWq_sel=dWq_sel,
                 x_codes=xc, x_mask=xm, w_codes=wc, w_mask=wm)
 
 
@@ -299,7 +301,7 @@ def conv_bwd(dY, X, S_x, Z_x, a_bits, W, S_w, w_bits, idx, stride=1, pad=0):
     if idx.size:
         dW[idx] = np.where(wm[idx], dWq_sel, 0.0)
         dS_w[idx] = grad_weight_scale(dWq_sel, W[idx], wc[idx], wm[idx], np.asarray(S_w)[idx])
-    return dict(dX=dX, dXq=dXq, dW=dW, dS_w=dS_w, dS_x=dS_x, dZ_x=dZ_x,
+    return dict(dX=dX, dXq=dXq, dW=dW, dS_w=dS_w, dS_x=dS_x, dZ_x=dZ_x, dWq_sel=dWq_sel,
                 x_codes=xc, x_mask=xm, w_codes=wc, w_mask=wm)
 
 
