@@ -474,8 +474,17 @@ def test_linear_bwd_pinned_dx_kernel(case):
     assert np.array_equal(host(out["dx"]), host(out2["dx"]))
 
 
-@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4)])
-@pytest.mark.parametrize("shape", [(300, 208, 136), (260, 70, 43)])
+def _close_fp32_update(got, want, old, name):
+    """The kernel forms the optimizer update in fp32: each result carries a few units of rounding at the size of its
+    operands (old value and step), which is more than a relative bound on the result where the two nearly cancel."""
+    mag = np.abs(np.asarray(old, dtype=np.float64)) + np.abs(want - np.asarray(old, dtype=np.float64))
+    bad = np.abs(got - want) > 2e-6 * np.abs(want) + 2.0 ** -22 * mag
+    assert not bad.any(), (name, int(bad.sum()), float(np.abs(got - want).max()))
+
+
+# (453, 140, 232): a weight whose update nearly cancels it (found by a soak over random shapes)
+@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4), (0.0, 5e-4)])
+@pytest.mark.parametrize("shape", [(300, 208, 136), (260, 70, 43), (453, 140, 232)])
 def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
     # the fused optimizer step must equal the plain call followed by the SGD rule on the rows idx, and leave
     # everything else untouched
@@ -502,14 +511,15 @@ def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
     ii = idx.cpu().numpy().astype(np.int64)
     Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
                                          momentum, wd, mom_w0 if momentum else None, mom_s0 if momentum else None)
-    np.testing.assert_allclose(host(w2), Wn, rtol=2e-6, atol=1e-9)
-    np.testing.assert_allclose(host(s2), Sn, rtol=2e-6, atol=1e-12)
+    close = _close_fp32_update
+    close(host(w2), Wn, W, "w")
+    close(host(s2), Sn, host(fw["scale"]), "s_w")
     frozen = np.setdiff1d(np.arange(c_out), ii)
     assert np.array_equal(host(w2)[frozen], W[frozen].astype(np.float64))
     assert np.array_equal(host(s2)[frozen], host(fw["scale"])[frozen])
     if momentum:
-        np.testing.assert_allclose(host(mw), mwn, rtol=2e-6, atol=1e-9)
-        np.testing.assert_allclose(host(ms), msn, rtol=2e-6, atol=1e-12)
+        close(host(mw), mwn, mom_w0, "mom_w")
+        close(host(ms), msn, mom_s0, "mom_s")
         assert np.array_equal(host(mw)[frozen], mom_w0[frozen].astype(np.float64))
     # gradients are optional outputs of the fused call
     w3, s3 = wd_t.clone(), fw["scale"].clone()
@@ -552,10 +562,10 @@ def test_conv_bwd_fused_sgd_step():
     ii = idx.cpu().numpy().astype(np.int64)
     Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
                                          0.9, 1e-3, mom_w0, mom_s0)
-    np.testing.assert_allclose(host(w2), Wn, rtol=2e-6, atol=1e-9)
-    np.testing.assert_allclose(host(s2), Sn, rtol=2e-6, atol=1e-12)
-    np.testing.assert_allclose(host(mw), mwn, rtol=2e-6, atol=1e-9)
-    np.testing.assert_allclose(host(ms), msn, rtol=2e-6, atol=1e-12)
+    _close_fp32_update(host(w2), Wn, W, "w")
+    _close_fp32_update(host(s2), Sn, host(fw["scale"]), "s_w")
+    _close_fp32_update(host(mw), mwn, mom_w0, "mom_w")
+    _close_fp32_update(host(ms), msn, mom_s0, "mom_s")
 
 
 def test_linear_bwd_dx_independent_of_fraction_and_fp32_dx():
