@@ -182,6 +182,41 @@ def test_layer_select_lwpn():
         assert kpl.cpu().numpy().tolist() == [int(v) for v in kpl_ref]
 
 
+@pytest.mark.parametrize("trial", range(8))
+def test_network_and_layer_select_on_random_networks(trial):
+    """Seeded random networks (1 to 39 layers, some with identical rows or identical layers: ties) through the CWPN
+    and LWPN selections, against the oracle."""
+    rng = np.random.default_rng(31337 + trial)
+    nl = int(rng.integers(1, 40))
+    ws, scores, offs = [], [], [0]
+    for i in range(nl):
+        c, b = int(rng.integers(1, 700)), int(rng.integers(1, 64))
+        W = synth.normal(1000 + trial * 50 + i, 1, (c, b), std=0.02 * (1 + 0.3 * (i % 4))).astype(np.float32)
+        if rng.integers(0, 4) == 0:
+            W[:] = W[0]
+        ws.append(W)
+    if nl > 2 and rng.integers(0, 2):
+        ws[1] = ws[0].copy()
+    for W in ws:
+        scores.append(orc.channel_importance(W)); offs.append(offs[-1] + W.shape[0])
+    flat = dev(np.concatenate(scores)); off_d = dev(np.array(offs, dtype=np.int64))
+    total = offs[-1]
+    for k_total in sorted({0, 1, total, int(rng.integers(0, total + 1)), int(rng.integers(0, total + 1))}):
+        idx, kpl = ef.network_select(flat, off_d, k_total)
+        torch.cuda.synchronize()
+        ref = orc.network_top_k(scores, k_total)
+        assert kpl.cpu().numpy().tolist() == [len(r) for r in ref]
+        if k_total:
+            assert idx.cpu().numpy().tolist() == np.concatenate(ref).astype(np.int64).tolist()
+    for k_layers in sorted({0, 1, nl, int(rng.integers(0, nl + 1))}):
+        lidx, kpl, ls = ef.layer_select(flat, off_d, k_layers)
+        torch.cuda.synchronize()
+        sel, kpl_ref, imp = orc.layer_top_k(ws, k_layers)
+        np.testing.assert_allclose(ls.cpu().numpy(), imp, rtol=1e-12)
+        assert lidx.cpu().numpy().tolist() == [int(v) for v in sel]
+        assert kpl.cpu().numpy().tolist() == [int(v) for v in kpl_ref]
+
+
 BIAS_CASES = [
     # T, c_out, kind, layout
     (517, 264, "bf16", 0), (517, 264, "f32", 0), (300, 77, "bf16", 0), (300, 77, "f32", 0), (1, 8, "bf16", 0),
