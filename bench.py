@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
     ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
                     help="2: the weight-side calls of each layer run on a second stream, joined before its backward; "
-                         "1: one stream; 0: two streams except for the small convolution workload, whose kernels are "
+                         "1: one stream; 0: two streams except for the small workloads (cfg1, cfg4), whose kernels are "
                          "shorter than the cross-stream joins cost")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
@@ -273,7 +273,7 @@ def main():
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
     if args.streams == 0:
-        args.streams = 1 if args.workload == "cfg4" else 2
+        args.streams = 1 if args.workload in ("cfg1", "cfg4") else 2
     step = make_step(torch, ef, layers, ks, args.streams)
 
     for _ in range(args.warmup):
