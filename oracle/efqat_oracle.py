@@ -22,6 +22,12 @@ What is fixed by the paper and what is a reading of it:
     Eq. 1 / Eq. 3 with d round(u)/du := 1 (see grad_* below).  These functions are
     pinned by finite differences of that surrogate and by autograd, not by a
     formula in the paper.
+  * Optimizer step of Alg. 1: the unfrozen weight rows keep the full-precision run's
+    optimizer (SGD with momentum in the paper's CNN experiments), the quantization
+    parameters are always trained with Adam (Sec. 4 "Setup").  The paper gives no betas
+    or eps (the caller passes them) and does not say what happens to the Adam state of a
+    frozen channel; it is read here as: one Adam state and step count per channel, which
+    advance only in the steps that update that channel.
   * Non-integer Z_x and degenerate ranges (max == min, all-zero weight row) are
     this build's reading only: parity unpinned by the paper for those two cases.
 
@@ -155,25 +161,44 @@ def bias_grad(dY):
     return d.reshape(-1, d.shape[-1]).sum(axis=0)
 
 
-def sgd_step_rows(W, S_w, idx, dW_rows, dS_w_rows, lr_w, lr_s, momentum=0.0, weight_decay=0.0,
-                  mom_w=None, mom_s=None):
-    """Optimizer step of Alg. 1 on the unfrozen channels only (SGD with momentum and weight
-    decay; frozen rows, their scales and momentum buffers stay as they are):
+def sgd_step_rows(W, idx, dW_rows, lr_w, momentum=0.0, weight_decay=0.0, mom_w=None):
+    """Optimizer step of Alg. 1 on the unfrozen weight channels only.  The network parameters keep the
+    optimizer of the full-precision run (Sec. 4 "Setup"), which is SGD with momentum and weight decay in
+    the paper's CNN experiments; frozen rows and their momentum buffers stay as they are:
         g = dW + wd * W;  buf = mu * buf + g (if mu != 0);  W -= lr_w * buf
-    and the same for the scales with lr_s and without decay.  Returns new copies
-    (W, S_w, mom_w, mom_s) in fp64."""
-    W = np.array(W, dtype=np.float64); S = np.array(S_w, dtype=np.float64)
+    Returns new copies (W, mom_w) in fp64."""
+    W = np.array(W, dtype=np.float64)
     mw = None if mom_w is None else np.array(mom_w, dtype=np.float64)
-    ms = None if mom_s is None else np.array(mom_s, dtype=np.float64)
     idx = np.asarray(idx, dtype=np.int64)
     g = np.asarray(dW_rows, dtype=np.float64) + weight_decay * W[idx]
-    gs = np.asarray(dS_w_rows, dtype=np.float64)
     if momentum != 0.0:
-        mw[idx] = momentum * mw[idx] + g; g = mw[idx]
-        ms[idx] = momentum * ms[idx] + gs; gs = ms[idx]
+        mw[idx] = momentum * mw[idx] + g
+        g = mw[idx]
     W[idx] = W[idx] - lr_w * g
-    S[idx] = S[idx] - lr_s * gs
-    return W, S, mw, ms
+    return W, mw
+
+
+def adam_step_rows(S_w, idx, dS_w_rows, lr, m, v, t, beta1=0.9, beta2=0.999, eps=1e-8):
+    """Optimizer step of Alg. 1 on the weight scales of the unfrozen channels.  Quantization parameters are
+    always trained with Adam (Sec. 4 "Setup"); a frozen channel's scale is not updated (Sec. 3.2,
+    "Quantization Granularity"), so every channel carries its own first / second moment and its own step
+    count t[c], and only the channels in idx advance:
+        t += 1;  m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2
+        S -= lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+    (Adam as published, with bias correction, no weight decay; the paper names no betas or eps, the
+    defaults of the Adam paper are the caller's to pass).  Returns new copies (S_w, m, v, t)."""
+    S = np.array(S_w, dtype=np.float64)
+    m = np.array(m, dtype=np.float64); v = np.array(v, dtype=np.float64)
+    t = np.array(t, dtype=np.int64)
+    idx = np.asarray(idx, dtype=np.int64)
+    g = np.asarray(dS_w_rows, dtype=np.float64)
+    t[idx] += 1
+    m[idx] = beta1 * m[idx] + (1.0 - beta1) * g
+    v[idx] = beta2 * v[idx] + (1.0 - beta2) * g * g
+    m_hat = m[idx] / (1.0 - np.power(float(beta1), t[idx]))
+    v_hat = v[idx] / (1.0 - np.power(float(beta2), t[idx]))
+    S[idx] = S[idx] - lr * m_hat / (np.sqrt(v_hat) + eps)
+    return S, m, v, t
 
 
 # --------------------------------------------------------------------------

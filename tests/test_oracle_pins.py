@@ -192,29 +192,71 @@ def test_bias_grad_is_gradient_of_bias():
 
 @pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 0.0), (0.9, 5e-4), (0.0, 1e-2)])
 def test_sgd_step_rows_matches_torch_sgd_on_the_unfrozen_rows(momentum, wd):
-    # torch.optim.SGD over parameters that hold only the unfrozen rows (two steps, so the momentum buffer is used);
+    # torch.optim.SGD over a parameter that holds only the unfrozen rows (two steps, so the momentum buffer is used);
     # frozen rows must come back untouched
     rng = np.random.default_rng(11)
-    W = rng.normal(size=(9, 5)); S = rng.uniform(0.5, 1.5, size=9)
+    W = rng.normal(size=(9, 5))
     idx = np.array([1, 4, 7])
     pw = torch.tensor(W[idx], dtype=torch.float64, requires_grad=True)
-    ps = torch.tensor(S[idx], dtype=torch.float64, requires_grad=True)
     opt_w = torch.optim.SGD([pw], lr=0.1, momentum=momentum, weight_decay=wd)
-    opt_s = torch.optim.SGD([ps], lr=0.01, momentum=momentum)
     mw = np.zeros_like(W) if momentum else None
-    ms = np.zeros_like(S) if momentum else None
-    Wc, Sc = W.copy(), S.copy()
+    Wc = W.copy()
     for step in range(2):
-        dW = rng.normal(size=(3, 5)); dS = rng.normal(size=3)
-        pw.grad = torch.tensor(dW); ps.grad = torch.tensor(dS)
-        opt_w.step(); opt_s.step()
-        Wc, Sc, mw, ms = orc.sgd_step_rows(Wc, Sc, idx, dW, dS, 0.1, 0.01, momentum, wd, mw, ms)
+        dW = rng.normal(size=(3, 5))
+        pw.grad = torch.tensor(dW)
+        opt_w.step()
+        Wc, mw = orc.sgd_step_rows(Wc, idx, dW, 0.1, momentum, wd, mw)
     np.testing.assert_allclose(Wc[idx], pw.detach().numpy(), rtol=1e-13, atol=1e-15)
-    np.testing.assert_allclose(Sc[idx], ps.detach().numpy(), rtol=1e-13, atol=1e-15)
     frozen = np.setdiff1d(np.arange(9), idx)
-    assert np.array_equal(Wc[frozen], W[frozen]) and np.array_equal(Sc[frozen], S[frozen])
+    assert np.array_equal(Wc[frozen], W[frozen])
     if momentum:
-        assert not mw[frozen].any() and not ms[frozen].any()
+        assert not mw[frozen].any()
+
+
+@pytest.mark.parametrize("betas,eps", [((0.9, 0.999), 1e-8), ((0.8, 0.95), 1e-6)])
+def test_adam_step_rows_matches_torch_adam_on_the_unfrozen_rows(betas, eps):
+    # Quantization parameters are trained with Adam (Sec. 4 "Setup").  torch.optim.Adam over a parameter that holds
+    # only the unfrozen scales, five steps with the same idx (every selected channel then has the optimizer's own step
+    # count); frozen channels and their state must come back untouched
+    rng = np.random.default_rng(12)
+    S = rng.uniform(0.5, 1.5, size=9)
+    idx = np.array([0, 3, 4, 8])
+    ps = torch.tensor(S[idx], dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([ps], lr=1e-2, betas=betas, eps=eps)
+    Sc, m, v, t = S.copy(), np.zeros(9), np.zeros(9), np.zeros(9, dtype=np.int64)
+    for step in range(5):
+        g = rng.normal(size=4) * 10.0 ** rng.integers(-3, 2)
+        ps.grad = torch.tensor(g)
+        opt.step()
+        Sc, m, v, t = orc.adam_step_rows(Sc, idx, g, 1e-2, m, v, t, betas[0], betas[1], eps)
+    np.testing.assert_allclose(Sc[idx], ps.detach().numpy(), rtol=1e-12, atol=1e-15)
+    st = opt.state[ps]
+    np.testing.assert_allclose(m[idx], st["exp_avg"].numpy(), rtol=1e-12, atol=1e-300)
+    np.testing.assert_allclose(v[idx], st["exp_avg_sq"].numpy(), rtol=1e-12, atol=1e-300)
+    frozen = np.setdiff1d(np.arange(9), idx)
+    assert np.array_equal(Sc[frozen], S[frozen]) and not m[frozen].any() and not v[frozen].any()
+    assert t[idx].tolist() == [5] * 4 and not t[frozen].any()
+
+
+def test_adam_step_rows_with_a_changing_selection_is_one_adam_per_channel():
+    # The selected set changes between steps (channel importance is re-evaluated, Sec. 3.2 "Freezing Frequency"): a
+    # channel's scale, moments and step count move only in the steps that select it, i.e. every channel behaves like a
+    # torch.optim.Adam of its own that is stepped only then
+    rng = np.random.default_rng(13)
+    C = 6
+    S = rng.uniform(0.5, 1.5, size=C)
+    ps = [torch.tensor([S[c]], dtype=torch.float64, requires_grad=True) for c in range(C)]
+    opts = [torch.optim.Adam([p], lr=3e-3) for p in ps]
+    Sc, m, v, t = S.copy(), np.zeros(C), np.zeros(C), np.zeros(C, dtype=np.int64)
+    picks = [[0, 2, 5], [2, 3], [0, 1, 2, 3, 4, 5], [5], [1, 2]]
+    for idx in picks:
+        g = rng.normal(size=len(idx))
+        for j, c in enumerate(idx):
+            ps[c].grad = torch.tensor([g[j]])
+            opts[c].step()
+        Sc, m, v, t = orc.adam_step_rows(Sc, np.array(idx), g, 3e-3, m, v, t)
+    np.testing.assert_allclose(Sc, np.array([p.item() for p in ps]), rtol=1e-12)
+    assert t.tolist() == [sum(c in p for p in picks) for c in range(C)]
 
 
 def test_ops_model_golden():
