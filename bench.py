@@ -1,22 +1,31 @@
 #!/usr/bin/env python3
 """Benchmark of the EfQAT backward hot path on one MI355X.
 
-One "step" = one pass of the whole hot path over one batch of synthetic input, for every layer of
-the workload: activation statistic + fake-quant, weight statistic + fake-quant, channel importance +
-Top-K, then the restricted backward (dX product with fused STE / S_x, Z_x gradients; gathered dW
-product; mask + S_w gradients).  The headline value is the backward TFLOP/s at the headline update
-fraction, 2*T*C_in*(C_out + k) per layer (Eq. 7 of the paper times 2*T), over the whole step time.
-A sweep over update fractions (backward call only) is attached, with the speedup over the full
-(r = 100 %) backward, which is the quantity the paper reports (1.44-1.64x on A10 / A100, whole
-networks, as context only).
+One "step" = one pass of the whole hot path over one batch of synthetic input, for every layer of the workload:
+activation statistic + fake-quant, weight statistic + fake-quant, channel importance + Top-K, then the restricted
+backward (dX product with fused STE / S_x, Z_x gradients; gathered dW product; mask + S_w gradients).  The headline
+value is the backward TFLOP/s at the headline update fraction, 2*T*C_in*(C_out + k) per layer (Eq. 7 of the paper
+times 2*T), over the whole step time.
+
+The headline workload is the largest single-GPU configuration (config 5, the LLM-sized MLP pair) at r = 25 %.  The
+`roofline` object of the output line carries, besides the dominant kernel (the dX product) against the bf16 matrix-core
+peak:
+  kernels    every kernel class of the headline step: time per step, algorithmic flops and bytes, the roofline time
+             max(flops / peak, bytes / bandwidth) and the fraction of it that was reached;
+  sweep      the backward call alone at every update fraction the config names (and r = 0), with the speedup over the
+             full (r = 100 %) backward - the quantity the paper reports - and the cost over r = 0 against k;
+  workloads  the same sweep, compact, for the other configurations (config 2 BERT FFN pair, config 3 encoder linears
+             at W4A8 and W8A8, config 4 ResNet convolutions) and for both layouts of dY.
 
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,19 +36,15 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the dX product kernel, mean of the two layers of config 2 with token-major dY: from the
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_bert_ffn_r25_kernel_stats.md
-# (k_gemm_kk, both layers: 189.7 MB read + 47.3 MB written per launch on average).  Not measurable live; other
-# workloads: null.
-DX_KERNEL_TRAFFIC_BYTES = {("cfg2", 0): 189.7e6 + 47.3e6}
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--w-bits", type=int, default=0, help="weight bit width (default: the config's first)")
     ap.add_argument("--fraction", default=None, help="headline update fraction num/den (default 1/4)")
     ap.add_argument("--dy-layout", type=int, default=0, help="0 token major [T,C_out], 1 channel major")
     ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
@@ -48,9 +53,21 @@ def parse_args():
                          "shorter than the cross-stream joins cost")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-attach", action="store_true",
+                    help="leave out the compact blocks for the other configurations and the other dY layout")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of 256 MiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
+
+
+_HOST_CACHE = {}
+
+
+def host_tensors(synth, key, make):
+    """Seeded host tensors are shared by the variants of one layer (layouts, weight bit widths)."""
+    if key not in _HOST_CACHE:
+        _HOST_CACHE[key] = make()
+    return _HOST_CACHE[key]
 
 
 class Layer:
@@ -65,13 +82,16 @@ class Layer:
         self.dyd = dyd
         ks = sorted({ef.k_from_ratio(c_out, n_, d_) for (n_, d_) in fracs} | {c_out})
         if conv is None:
-            X, W, dY = synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype, row_scale_sigma=row_sigma)
+            X, W, dY = host_tensors(synth, ("lin", seed, T, c_in, c_out, act_dtype, row_sigma),
+                                    lambda: synth.linear_layer(seed, T, c_in, c_out, act_dtype=act_dtype,
+                                                               row_scale_sigma=row_sigma))
             self.T, self.T_in, self.taps = T, T, 1
             bwd_ws = [L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k_, dyd, layout) for k_ in ks]
         else:
             g = conv
-            X, W, dY = synth.conv_layer(seed, g["N"], g["H"], g["W"], c_in, c_out, g["kh"], g["kw"], g["stride"],
-                                        g["pad"], act_dtype=act_dtype)
+            X, W, dY = host_tensors(synth, ("conv", seed, tuple(sorted(g.items())), act_dtype),
+                                    lambda: synth.conv_layer(seed, g["N"], g["H"], g["W"], c_in, c_out, g["kh"], g["kw"],
+                                                             g["stride"], g["pad"], act_dtype=act_dtype))
             self.T = int(np.prod(dY.shape[:3]))         # output pixels
             self.T_in = int(np.prod(X.shape[:3]))       # input pixels
             self.taps = g["kh"] * g["kw"]
@@ -81,8 +101,10 @@ class Layer:
         tdt = torch.bfloat16 if act_dtype == "bf16" else torch.float32
         self.x = torch.from_numpy(X).to(tdt).cuda()
         self.w = torch.from_numpy(W).cuda()
-        dyh = dY if layout == 0 else dY.reshape(-1, c_out).T.copy()
-        self.dy = torch.from_numpy(dyh).to(tdt).cuda()
+        dy_dev = torch.from_numpy(dY).to(tdt).cuda()
+        # channel major: [C_out][T] (transposed on the device: the values are the same bits)
+        self.dy = dy_dev if layout == 0 else dy_dev.reshape(-1, c_out).t().contiguous()
+        del dy_dev
         dev = self.x.device
         e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
         block = self.taps * c_in                         # weights per output channel
@@ -164,6 +186,32 @@ class Layer:
         # Eq. 7 / Eq. 8 op counts (x2 for multiply + add): dX over every channel, dW over the k selected ones
         return 2.0 * self.T * self.c_in * self.taps * (self.c_out + k)
 
+    # ---- algorithmic work of each kernel class for one call on this layer: (flops, HBM bytes).  Bytes are what the
+    # operation must move once: inputs read once, outputs written once; e = bytes per activation element.
+    def work(self, k):
+        e = 2 if self.dyd else 4
+        T, Ti, ci, co, taps = self.T, self.T_in, self.c_in, self.c_out, self.taps
+        nw = taps * ci                                   # weights per output channel
+        w = {}
+        # dX product + fused epilogue: dY, the int8 weight codes, x / codes / mask in, dX out
+        w["dx"] = (2.0 * T * ci * taps * co, T * co * e + co * nw + Ti * ci * (e + 1 + 0.125) + Ti * ci * e)
+        # dW product: the k selected columns (rows) of dY, the uint8 codes, k x n fp32 out
+        w["dw"] = (2.0 * T * nw * k, T * k * e + Ti * ci + k * nw * 4.0) if k else (0.0, 0.0)
+        # compaction of the selected dY columns (token-major dY only): read them, write them once as bf16
+        w["prep"] = (0.0, (T * k * e + T * k * 2.0) if (k and k < co and self.layout == 0) else 0.0)
+        # second pass: mask, master weights and codes of the k rows in, dW out (dS_w, dS_x, dZ_x are scalars)
+        w["finish"] = (0.0, k * nw * (4 + 1 + 0.125) + k * nw * 4.0)
+        # activation statistic (one read) + quantizer (one read, codes and mask out)
+        w["quant_act"] = (0.0, Ti * ci * e + Ti * ci * (e + 1 + 0.125))
+        w["quant_w"] = (0.0, co * nw * (4 + 1 + 0.125))
+        w["importance"] = (0.0, co * nw * 4.0)
+        w["topk"] = (0.0, co * 8.0 + k * 4.0)
+        return w
+
+
+CLASSES = [("dx", 0), ("dw", 1), ("prep", 3), ("finish", 4), ("quant_act", 5), ("quant_w", 6), ("importance", 7),
+           ("topk", 8)]
+
 
 def make_step(torch, ef, layers, ks, streams):
     """One step over `layers` with ks[i] selected channels each: quantize X and W, select, restricted backward.
@@ -171,8 +219,8 @@ def make_step(torch, ef, layers, ks, streams):
     The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
     do not depend on its activations, so with streams == 2 they are issued on a second stream of the same (default)
     priority and joined before the layer's backward, together with the bf16 weight operand of the dX product
-    (efqat_linear_bwd_weight_operand; the backward is then efqat_linear_bwd_prepared); ev_bwd keeps the next step
-    from rewriting a layer's weight codes, operand and idx while this step's backward still reads them.
+    (efqat_linear_bwd_weight_operand, handed to efqat_linear_bwd_ex); ev_bwd keeps the next step from rewriting a
+    layer's weight codes, operand and idx while this step's backward still reads them.
     streams == 1 issues everything on one stream through the plain entry points."""
     main_stream = torch.cuda.current_stream()
     side_stream = torch.cuda.Stream() if streams == 2 else None
@@ -208,8 +256,146 @@ def time_region(torch, fn, steps):
     return (time.perf_counter() - t0) / steps
 
 
+def profiled(torch, ef, fn, steps):
+    """`steps` more runs of fn with the library's HIP events around every kernel class (on the stream the kernels go
+    to).  Returns {class: (ms per run, brackets per run)}.  A separate pass, because every event record costs a few
+    microseconds on the stream."""
+    ef.profile_enable(True)
+    sec = time_region(torch, fn, steps)
+    res = {}
+    for name, which in CLASSES:
+        ms, n = ef.profile_read(which)
+        res[name] = (ms / steps, n / steps)
+    ef.profile_enable(False)
+    res["_ms_with_events"] = sec * 1e3
+    return res
+
+
+def kernel_rows(layers, ks, prof):
+    """Per kernel class of one step: measured time against the roofline time of its algorithmic work."""
+    rows = []
+    for name, _ in CLASSES:
+        fl = sum(l.work(k)[name][0] for l, k in zip(layers, ks))
+        by = sum(l.work(k)[name][1] for l, k in zip(layers, ks))
+        ms, n = prof[name]
+        if n == 0:
+            continue
+        t_mfma = fl / (PEAK_BF16_TFLOPS * 1e12) * 1e3
+        t_hbm = by / (PEAK_HBM_GBS * 1e9) * 1e3
+        roof = max(t_mfma, t_hbm)
+        row = dict(kernel=name, ms=round(ms, 5), launches=round(n, 2), gflop=round(fl / 1e9, 3), mbytes=round(by / 1e6, 3),
+                   bound="mfma" if t_mfma >= t_hbm else "hbm", roof_ms=round(roof, 5),
+                   frac=round(roof / ms, 4) if (ms > 0 and roof > 0) else None)
+        if fl:
+            row["tflops"] = round(fl / ms / 1e9, 1)
+        if by:
+            row["gbps"] = round(by / ms / 1e6, 1)
+        if name == "topk":                               # one workgroup, latency bound: microseconds are the figure
+            row = dict(kernel=name, ms=round(ms, 5), launches=round(n, 2), bound="latency")
+        rows.append(row)
+    return rows
+
+
+def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer):
+    """The backward call alone at every fraction: total time, speedup over r = 100 %, cost over r = 0 against k."""
+    for l in layers:
+        l.forward_quant(ef)
+    fr = sorted(set(fracs) | {(0, 1), (1, 1)}, key=lambda f: f[0] / f[1])
+    rows, times = [], {}
+    for (n_, d_) in fr:
+        kk = [ef.k_from_ratio(l.c_out, n_, d_) for l in layers]
+        idxs = [l.select(ef, k) for l, k in zip(layers, kk)]
+
+        def bwd():
+            for l, idx in zip(layers, idxs):
+                l.backward(ef, idx)
+        for _ in range(max(2, warmup)):
+            bwd()
+        t = time_region(torch, bwd, max(3, steps))
+        prof = profiled(torch, ef, bwd, max(3, steps // 2))
+        times[(n_, d_)] = t
+        fl = sum(l.flops(k) for l, k in zip(layers, kk))
+        row = dict(r="%d/%d" % (n_, d_), k=kk, ms=round(t * 1e3, 5), tflops=round(fl / t / 1e12, 1),
+                   dx_ms=round(prof["dx"][0], 5), dw_ms=round(prof["dw"][0], 5), prep_ms=round(prof["prep"][0], 5),
+                   finish_ms=round(prof["finish"][0], 5))
+        if per_layer:
+            lay = []
+            for l, idx, k_ in zip(layers, idxs, kk):
+                one = lambda: l.backward(ef, idx)
+                for _ in range(2):
+                    one()
+                tl = time_region(torch, one, max(3, steps))
+                lay.append(dict(name=l.name, k=k_, ms=round(tl * 1e3, 5), tflops=round(l.flops(k_) / tl / 1e12, 1)))
+            row["layers"] = lay
+        rows.append(row)
+    full, zero = times[(1, 1)], times[(0, 1)]
+    for row, key in zip(rows, fr):
+        row["speedup_vs_full"] = round(full / times[key], 4)
+        row["ideal_speedup"] = round(sum(l.flops(l.c_out) for l in layers)
+                                     / sum(l.flops(k) for l, k in zip(layers, row["k"])), 4)   # Eq. 7 / Eq. 8 op counts
+        row["over_r0_ms"] = round((times[key] - zero) * 1e3, 5)
+        ksum = sum(row["k"])
+        row["over_r0_us_per_channel"] = round((times[key] - zero) * 1e6 / ksum, 4) if ksum else None
+    return rows
+
+
+def build_layers(ef, torch, synth, workload, w_bits, layout, fracs, row_sigma=0.0):
+    cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg4": synth.CFG4, "cfg5": synth.CFG5}[workload]
+    if "layers" in cfg:
+        return [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits, layout, synth,
+                      fracs, row_sigma=row_sigma) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
+    return [Layer(ef, torch, n, cfg["seed"] + i, 0, cfg[n]["c_in"], cfg[n]["c_out"], cfg["act_dtype"], cfg["a_bits"],
+                  w_bits, layout, synth, fracs, conv=cfg[n]) for i, n in enumerate(("conv", "conv1x1"))]
+
+
+def describe(workload, layers, num, den, w_bits, a_bits, layout):
+    return "%s: %s, r=%d/%d, W%dA%d, dY %s-major" % (
+        workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers), num, den, w_bits,
+        a_bits, "token" if layout == 0 else "channel")
+
+
+def compact_block(torch, ef, synth, workload, w_bits, layout, num, den, steps, warmup):
+    """Step time at the headline fraction and the backward sweep for one more workload / layout (compact)."""
+    cfg = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg4": synth.CFG4, "cfg5": synth.CFG5}[workload]
+    fracs = list(cfg["fractions"]) + [(num, den), (0, 1), (1, 1)]
+    layers = build_layers(ef, torch, synth, workload, w_bits, layout, fracs)
+    ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
+    streams = 1 if workload in ("cfg1", "cfg4") else 2
+    step = make_step(torch, ef, layers, ks, streams)
+    for _ in range(warmup):
+        step()
+    sec = time_region(torch, step, steps)
+    prof = profiled(torch, ef, step, max(3, steps // 2))
+    flops = sum(l.flops(k) for l, k in zip(layers, ks))
+    dx_fl = sum(l.work(k)["dx"][0] for l, k in zip(layers, ks))
+    blk = dict(workload=describe(workload, layers, num, den, w_bits, cfg["a_bits"], layout), k=ks,
+               step_ms=round(sec * 1e3, 5), tflops=round(flops / sec / 1e12, 1),
+               dx_frac_of_mfma_peak=round(dx_fl / (prof["dx"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+               kernels=kernel_rows(layers, ks, prof),
+               sweep=sweep_backward(torch, ef, layers, cfg["fractions"], steps, warmup, per_layer=False))
+    if workload == "cfg3":
+        blk["note"] = ("the four linears of one encoder layer; the 12 layers of the stack repeat exactly this work "
+                       "(x12 in time and flops)")
+    del layers, step
+    torch.cuda.empty_cache()
+    return blk
+
+
+def measured_traffic(workload, layout):
+    """HBM bytes per launch of the dX product kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE: read
+    from the tracked profile summaries (lines `TRAFFIC <workload> layout=<0|1> kernel=dx fetch_bytes=.. write_bytes=..`).
+    None when no summary covers this workload: the counters cannot be read from inside this process."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md")) + glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            m = re.match(r"\s*TRAFFIC\s+(\S+)\s+layout=(\d)\s+kernel=dx\s+fetch_bytes=([0-9.eE+]+)\s+write_bytes=([0-9.eE+]+)", line)
+            if m and m.group(1) == workload and int(m.group(2)) == layout:
+                return dict(fetch_bytes=float(m.group(3)), write_bytes=float(m.group(4)),
+                            total_bytes=float(m.group(3)) + float(m.group(4)), source=os.path.relpath(path, ROOT))
+    return None
+
+
 def cpu_baseline(layers, num, den, a_bits, w_bits):
-    """The oracle, as it stands, on the host cores: one whole step (every layer, all tokens)."""
+    """The oracle, as it stands, on the host cores: whole steps (every layer, all tokens) of the headline workload."""
     from oracle import efqat_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -236,7 +422,7 @@ def cpu_baseline(layers, num, den, a_bits, w_bits):
         reps += 1
     dt = time.perf_counter() - t0
     return dict(value=fl / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
-                sample="%d whole steps of the same workload (%s; all tokens; r=%d/%d; quantize, select, backward), "
+                sample="%d whole step(s) of the same workload (%s; all tokens; r=%d/%d; quantize, select, backward), "
                        "fp64 NumPy, %.1f s" % (reps, ", ".join(l.name for l in layers), num, den, dt))
 
 
@@ -257,19 +443,13 @@ def main():
     torch.cuda.set_device(0)
     cfg = {"cfg1": synth.CFG1, "cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg4": synth.CFG4,
            "cfg5": synth.CFG5}[args.workload]     # cfg3: the four linears of one encoder layer (the stack repeats them 12x)
-    w_bits = cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0]
+    w_bits = args.w_bits or (cfg["w_bits"] if isinstance(cfg["w_bits"], int) else cfg["w_bits"][0])
     if args.fraction:
         num, den = (int(t) for t in args.fraction.split("/"))
     else:
         num, den = 1, 4
-    fracs = list(cfg["fractions"]) + [(num, den), (1, 1)]
-    if "layers" in cfg:
-        layers = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
-                        args.dy_layout, synth, fracs) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
-    else:   # the convolution pair of config 4
-        layers = [Layer(ef, torch, n, cfg["seed"] + i, 0, cfg[n]["c_in"], cfg[n]["c_out"], cfg["act_dtype"],
-                        cfg["a_bits"], w_bits, args.dy_layout, synth, fracs, conv=cfg[n])
-                  for i, n in enumerate(("conv", "conv1x1"))]
+    fracs = list(cfg["fractions"]) + [(num, den), (0, 1), (1, 1)]
+    layers = build_layers(ef, torch, synth, args.workload, w_bits, args.dy_layout, fracs)
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
     if args.streams == 0:
@@ -280,91 +460,43 @@ def main():
         step()
     # the timed region: exactly --steps steps, nothing but the library's launches on the stream
     sec = time_region(torch, step, args.steps)
-    # a second pass of the same steps with HIP events recorded by the library around the product launches (on the
-    # stream they run on) gives the kernel durations of the roofline block; the event records themselves cost a few
-    # microseconds per launch, which is why this pass is not the one that is timed as a whole
-    ef.profile_enable(True)
-    sec_profiled = time_region(torch, step, args.steps)
-    dx_ms, dx_n = ef.profile_read(0)
-    dw_ms, dw_n = ef.profile_read(1)
-    ef.profile_enable(False)
+    # a second pass of the same steps with HIP events recorded by the library around every kernel class (on the stream
+    # the kernels run on) gives the kernel durations of the roofline block
+    prof = profiled(torch, ef, step, args.steps)
     flops = sum(l.flops(k) for l, k in zip(layers, ks))
     value = flops / sec / 1e12
 
     # dominant kernel: the dX product (always the full C_out); algorithmic flops per launch
-    dx_flops = sum(2.0 * l.T * l.c_in * l.taps * l.c_out for l in layers) / len(layers)
-    dx_avg_s = dx_ms / max(dx_n, 1) / 1e3
-    achieved = dx_flops / dx_avg_s / 1e12 if dx_n else 0.0
+    dx_flops = sum(l.work(k)["dx"][0] for l, k in zip(layers, ks)) / len(layers)
+    dx_avg_s = prof["dx"][0] / max(prof["dx"][1], 1e-9) / 1e3
+    achieved = dx_flops / dx_avg_s / 1e12 if prof["dx"][1] else 0.0
+    traffic = measured_traffic(args.workload, args.dy_layout)
     roofline = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS,
-                    traffic=DX_KERNEL_TRAFFIC_BYTES.get((args.workload, args.dy_layout)),
-                    kernel="dX product with fused epilogue (k_gemm_kk / k_gemm_nt / k_gemm_dx8 by shape)", algorithmic_flops_per_launch=dx_flops,
-                    avg_kernel_ms=dx_avg_s * 1e3, launches=int(dx_n), ms_per_step_with_events=sec_profiled * 1e3,
-                    dw_kernel_avg_ms=(dw_ms / dw_n) if dw_n else None)
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=traffic["total_bytes"] if traffic else None,
+                    traffic_detail=traffic,
+                    kernel="dX product with fused epilogue (k_gemm_dx8 / k_gemm_kk / k_gemm_nt by shape)",
+                    algorithmic_flops_per_launch=dx_flops,
+                    algorithmic_bytes_per_launch=sum(l.work(k)["dx"][1] for l, k in zip(layers, ks)) / len(layers),
+                    avg_kernel_ms=dx_avg_s * 1e3, launches_per_step=prof["dx"][1],
+                    ms_per_step_with_events=prof["_ms_with_events"],
+                    peaks=dict(bf16_mfma_tflops=PEAK_BF16_TFLOPS, hbm_gbps=PEAK_HBM_GBS),
+                    kernels=kernel_rows(layers, ks, prof))
 
-    sweep = []
     if not args.no_sweep:
-        for l in layers:
-            l.forward_quant(ef)
-        fr = list(cfg["fractions"])
-        if (1, 1) not in fr:
-            fr.append((1, 1))
-        times = {}
-        for (n_, d_) in fr:
-            kk = [ef.k_from_ratio(l.c_out, n_, d_) for l in layers]
-            idxs = [l.select(ef, k) for l, k in zip(layers, kk)]
-
-            def bwd():
-                for l, idx in zip(layers, idxs):
-                    l.backward(ef, idx)
-            for _ in range(max(2, args.warmup // 2)):
-                bwd()
-            t = time_region(torch, bwd, max(3, args.steps // 2))
-            ef.profile_enable(True)                      # kernel durations from a second pass (see above)
-            time_region(torch, bwd, max(3, args.steps // 4))
-            pdx, ndx = ef.profile_read(0)
-            pdw, ndw = ef.profile_read(1)
-            ef.profile_enable(False)
-            times[(n_, d_)] = t
-            fl = sum(l.flops(k) for l, k in zip(layers, kk))
-            # the same call layer by layer: total, the dX product, the dW product, and the rest (operand preparation,
-            # compaction of the selected dY columns, second pass with the masks, scatter and dS_w)
-            per_layer = []
-            for l, idx, k_ in zip(layers, idxs, kk):
-                one = lambda: l.backward(ef, idx)
-                for _ in range(3):
-                    one()
-                tl = time_region(torch, one, max(3, args.steps // 2))
-                ef.profile_enable(True)
-                time_region(torch, one, max(3, args.steps // 4))
-                ldx, lndx = ef.profile_read(0)
-                ldw, lndw = ef.profile_read(1)
-                ef.profile_enable(False)
-                a_dx = ldx / max(lndx, 1)
-                a_dw = (ldw / lndw) if lndw else 0.0
-                per_layer.append(dict(name=l.name, k=k_, ms=tl * 1e3, tflops=l.flops(k_) / tl / 1e12, dx_kernel_ms=a_dx,
-                                      dw_kernel_ms=a_dw, other_ms=max(tl * 1e3 - a_dx - a_dw, 0.0)))
-            sweep.append(dict(r="%d/%d" % (n_, d_), k=kk, ms=t * 1e3, tflops=fl / t / 1e12,
-                              dx_kernel_ms=pdx / max(ndx, 1) * len(layers),
-                              dw_kernel_ms=(pdw / ndw * len(layers)) if ndw else 0.0, layers=per_layer))
-        full = times[(1, 1)]
-        for row, key in zip(sweep, fr):
-            row["speedup_vs_full"] = full / times[key]
+        roofline["sweep"] = sweep_backward(torch, ef, layers, cfg["fractions"], args.steps, args.warmup, per_layer=True)
 
     # The backward call at the headline fraction on inputs of different structure (not part of `value`): a contiguous
     # block of channels (the best case for the compaction of dY columns; the selected set of i.i.d. rows is scattered,
-    # the worst case), scales shrunk to 0.7x after the min/max initialisation (a few per cent of the elements fall
-    # outside the range, so the clip masks and dZ_x do real work), and weight rows with log-normal factors (a few
-    # dominant channels, as in trained networks; linear workloads only).
-    variants = None
+    # the worst case) and scales shrunk to 0.7x after the min/max initialisation (a few per cent of the elements fall
+    # outside the range, so the clip masks and dZ_x do real work).
     if not args.no_sweep:
         def time_bwd(lays, idxs):
             def bwd():
                 for l, idx in zip(lays, idxs):
                     l.backward(ef, idx)
-            for _ in range(20):                          # host-side set-up precedes every variant: let the clocks settle
+            for _ in range(10):                          # host-side set-up precedes every variant: let the clocks settle
                 bwd()
-            return time_region(torch, bwd, max(3, args.steps)) * 1e3
+            return round(time_region(torch, bwd, max(3, args.steps)) * 1e3, 5)
         for l in layers:
             l.forward_quant(ef)
         idx_sel = [l.select(ef, k) for l, k in zip(layers, ks)]
@@ -379,43 +511,32 @@ def main():
         variants["scales_x0p7_clipped_activation_share"] = [round(l.clipped_fraction(torch), 5) for l in layers]
         for l in layers:
             l.forward_quant(ef)                          # back to the min/max scales
-        if "layers" in cfg and args.workload != "cfg5":
-            lo = [Layer(ef, torch, n, cfg["seed"] + i, T, ci, co, cfg["act_dtype"], cfg["a_bits"], w_bits,
-                        args.dy_layout, synth, fracs, row_sigma=0.5) for i, (n, T, ci, co) in enumerate(cfg["layers"])]
-            for l in lo:
-                l.forward_quant(ef)
-            idx_o = [l.select(ef, k) for l, k in zip(lo, ks)]
-            variants["lognormal_rows_sigma0p5_ms"] = time_bwd(lo, idx_o)
-            del lo, idx_o
+        roofline["variants"] = variants
 
-    # low-precision forward (int8 matrix cores), not part of the step or of `value`: the paper leaves the forward
-    # pass out of its timings
-    fwd = None
-    if not args.no_sweep and all(l.conv is None for l in layers):
-        ys = [torch.empty((l.T, l.c_out), dtype=l.x.dtype if l.x.dtype == torch.bfloat16 else torch.float32,
-                          device="cuda") for l in layers]
-        fws = [torch.empty(max(ef.lib().efqat_linear_fwd_workspace_bytes(l.T, l.c_in, l.c_out), 256),
-                           dtype=torch.uint8, device="cuda") for l in layers]
-
-        def fwd_all():
-            for l, y, w_ in zip(layers, ys, fws):
-                ef.linear_fwd(l.fx["codes"], l.fx["scale"], l.fx["zero_point"], l.fw["codes"], l.fw["scale"],
-                              ws=w_, out=y)
-        for _ in range(3):
-            fwd_all()
-        tf = time_region(torch, fwd_all, max(3, args.steps // 2))
-        ef.profile_enable(True)
-        time_region(torch, fwd_all, max(3, args.steps // 4))
-        kms, kn = ef.profile_read(2)
-        ef.profile_enable(False)
-        ops = sum(2.0 * l.T * l.c_in * l.c_out for l in layers)
-        fwd = dict(ms=tf * 1e3, tops=ops / tf / 1e12, kernel_ms=kms / max(kn, 1) * len(layers),
-                   kernel_tops=ops / (kms / max(kn, 1) * len(layers) / 1e3) / 1e12 if kn else None,
-                   peak_tops=5000.0, note="Y = X_q W_q^T from the 8-bit codes, v_mfma_i32_32x32x32_i8, all layers")
-
-    # bias gradient (always-updated parameters), HBM bound: one read of dY.  Not part of the step or of `value`.
-    bias = None
+    # low-precision forward (int8 matrix cores) and bias gradient of the same layers: not part of the step or of
+    # `value` (the paper leaves the forward pass out of its timings; biases are always updated)
     if not args.no_sweep:
+        extras = {}
+        if all(l.conv is None for l in layers):
+            ys = [torch.empty((l.T, l.c_out), dtype=l.x.dtype, device="cuda") for l in layers]
+            fws = [torch.empty(max(ef.lib().efqat_linear_fwd_workspace_bytes(l.T, l.c_in, l.c_out), 256),
+                               dtype=torch.uint8, device="cuda") for l in layers]
+
+            def fwd_all():
+                for l, y, w_ in zip(layers, ys, fws):
+                    ef.linear_fwd(l.fx["codes"], l.fx["scale"], l.fx["zero_point"], l.fw["codes"], l.fw["scale"],
+                                  ws=w_, out=y)
+            for _ in range(3):
+                fwd_all()
+            ef.profile_enable(True)
+            time_region(torch, fwd_all, max(3, args.steps // 2))
+            kms, kn = ef.profile_read(ef.PROF_FWD)
+            ef.profile_enable(False)
+            ops = sum(2.0 * l.T * l.c_in * l.c_out for l in layers) / len(layers)
+            extras["forward_int8"] = dict(kernel_ms=round(kms / max(kn, 1), 5), tops=round(ops / (kms / max(kn, 1)) / 1e9, 1),
+                                          peak_tops=5000.0, frac=round(ops / (kms / max(kn, 1)) / 1e9 / 5000.0, 4),
+                                          note="Y = X_q W_q^T from the 8-bit codes, v_mfma_i32_32x32x32_i8, per layer")
+            del ys, fws
         dbs = [torch.empty(l.c_out, dtype=torch.float32, device="cuda") for l in layers]
         bws = [torch.empty(max(ef.lib().efqat_bias_grad_workspace_bytes(l.T, l.c_out, args.dy_layout), 256),
                            dtype=torch.uint8, device="cuda") for l in layers]
@@ -427,19 +548,48 @@ def main():
             bias_all()
         tb = time_region(torch, bias_all, max(3, args.steps // 2))
         nbytes = sum(l.dy.numel() * l.dy.element_size() for l in layers)
-        bias = dict(ms=tb * 1e3, gbps=nbytes / tb / 1e9, peak_gbps=8000.0,
-                    note="db = column sums of dY, all layers, two launches per layer")
+        extras["bias_grad"] = dict(ms=round(tb * 1e3, 5), gbps=round(nbytes / tb / 1e9, 1), peak_gbps=PEAK_HBM_GBS,
+                                   frac=round(nbytes / tb / 1e9 / PEAK_HBM_GBS, 4),
+                                   note="db = column sums of dY, all layers, two launches per layer")
+        roofline["extras"] = extras
+        del dbs, bws
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(layers, num, den, cfg["a_bits"], w_bits)
+    workload_name = describe(args.workload, layers, num, den, w_bits, cfg["a_bits"], args.dy_layout)
+    del layers, step
+    torch.cuda.empty_cache()
+
+    # the other configurations and the other dY layout, compact
+    if not args.no_attach and not args.no_sweep:
+        blocks = []
+        st, wu = max(5, args.steps // 2), max(2, args.warmup // 2)
+        plan = [(args.workload, w_bits, 1 - args.dy_layout)]
+        for wl in ("cfg2", "cfg3", "cfg4"):
+            if wl == args.workload:
+                continue
+            c = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg4": synth.CFG4}[wl]
+            for wb in ((c["w_bits"],) if isinstance(c["w_bits"], int) else c["w_bits"]):
+                for lay in (0, 1):
+                    plan.append((wl, wb, lay))
+        last = None
+        for wl, wb, lay in plan:
+            if last is not None and last != wl:
+                _HOST_CACHE.clear()                      # host tensors of a finished workload
+            last = wl
+            blocks.append(compact_block(torch, ef, synth, wl, wb, lay, num, den, st, wu))
+        roofline["workloads"] = blocks
+        _HOST_CACHE.clear()
 
     out = dict(metric="QAT backward time + TFLOP/s per layer vs update fraction; speedup over full bwd",
                value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
                data="synthetic",
-               config=dict(workload="%s: %s, r=%d/%d, W%dA%d, dY %s-major" % (
-                   args.workload, ", ".join("%s T=%d %d->%d" % (l.name, l.T, l.c_in, l.c_out) for l in layers),
-                   num, den, w_bits, cfg["a_bits"], "token" if args.dy_layout == 0 else "channel"),
-                   k=ks, step="fakequant(X,W) + select + restricted backward, every layer", streams=args.streams),
-               roofline=roofline, sweep=sweep, variants=variants, forward_int8=fwd, bias_grad=bias,
-               paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)")
+               config=dict(workload=workload_name, k=ks,
+                           step="fakequant(X,W) + select + restricted backward, every layer", streams=args.streams,
+                           paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)"),
+               roofline=roofline)
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
@@ -447,8 +597,8 @@ def main():
         for _ in range(5):
             b.copy_(a)                                  # reads 256 MiB, writes 256 MiB per launch
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers, num, den, cfg["a_bits"], w_bits)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

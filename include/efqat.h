@@ -13,9 +13,10 @@
  *
  * Conventions common to every call
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
- *     allocates nothing and keeps no state between calls.  Scratch memory comes in
- *     through (ws, ws_bytes); the matching *_workspace_bytes() query gives the size
- *     needed (a host-only computation).  ws must be 256-byte aligned.
+ *     allocates nothing and keeps no state between calls (the benchmark timing hooks
+ *     at the end of this file excepted).  Scratch memory comes in through
+ *     (ws, ws_bytes); the matching *_workspace_bytes() query gives the size needed (a
+ *     host-only computation).  ws must be 256-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue kernels on it and return without synchronising.  Two calls that share
  *     a workspace must be ordered on one stream.
@@ -42,7 +43,7 @@
 extern "C" {
 #endif
 
-#define EFQAT_VERSION 100
+#define EFQAT_VERSION 200
 
 /* element types of activation / gradient tensors */
 #define EFQAT_F32 0
@@ -115,6 +116,18 @@ size_t efqat_channel_select_workspace_bytes(int64_t c_out);
 int efqat_channel_select(const float* w, int64_t c_out, int64_t block, int64_t k, double* scores,
                          int32_t* idx, void* ws, size_t ws_bytes, void* stream);
 
+/* efqat_channel_select for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the per-channel
+ * scores are kept in a device array that is part of the library image (512 KiB on every GPU the
+ * library runs on, for the life of the process) and are not returned.  Same w, k, idx and result as
+ * efqat_channel_select; c_out above EFQAT_STATIC_SELECT_MAX_CHANNELS is EFQAT_ERR_WORKSPACE.  The call
+ * allocates and frees nothing.  All calls on one GPU share that array: calls that overlap on one GPU
+ * (different streams) race; order them.  The array's address is looked up on the first call on each
+ * GPU, so make that first call outside a graph capture. */
+#define EFQAT_STATIC_SELECT_MAX_CHANNELS 65536
+int efqat_channel_select_static(const float* w, int64_t c_out, int64_t block, int64_t k, int32_t* idx,
+                                void* stream);
+
 /* EfQAT-CWPN (Table 2): one Top-K over the channels of several layers together.
  *   scores      in   double[total] = the per-layer score arrays of efqat_channel_select,
  *                    concatenated in layer order (device)
@@ -159,22 +172,19 @@ size_t efqat_bias_grad_workspace_bytes(int64_t T, int64_t c_out, int dy_layout);
 int efqat_bias_grad(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_out,
                     float* db, void* ws, size_t ws_bytes, void* stream);
 
-/* ------------------------------------------------------------------ options
- * Process-wide overrides for tests and measurements (like the profiling hooks below they are
- * the library's only state).  EFQAT_OPT_DX_KERNEL chooses the kernel of the dX product
- * (Eq. 5 left) of efqat_linear_bwd where both apply (bf16 token-major dY, C_out % 8 == 0,
- * C_in % 16 == 0): AUTO picks by problem size, BF16 always stages a bf16 copy of W_q^T, INT8
- * always reads the weight operand from the int8 codes.  BF16_PINNED (any linear layer, and
- * convolutions whose dX product runs on a staged im2col matrix) stages the bf16 copy and always
- * uses the 192 x 192 kernel with the hand-pinned instruction order, which AUTO and BF16 take
- * only where the planner picks that tile.  All choices give the same results up to the order
- * of the fp32 sums.  Changes the workspace size: query it after setting the option. */
-#define EFQAT_OPT_DX_KERNEL 1
+/* ------------------------------------------------------------------ choice of the dX kernel
+ * Argument dx_kernel of the *_ex entry points below, for tests and measurements; the plain entry
+ * points use AUTO.  It chooses the kernel of the dX product (Eq. 5 left) where more than one applies
+ * (bf16 token-major dY, C_out % 8 == 0, C_in % 16 == 0): AUTO picks by problem size, BF16 always
+ * stages a bf16 copy of W_q^T, INT8 always reads the weight operand from the int8 codes.  BF16_PINNED
+ * (any linear layer, and convolutions whose dX product runs on a staged im2col matrix) stages the bf16
+ * copy and always uses the 192 x 192 kernel with the hand-pinned instruction order, which AUTO and
+ * BF16 take only where the planner picks that tile.  All choices give the same results up to the
+ * order of the fp32 sums.  The workspace size depends on it: *_workspace_bytes_ex takes it too. */
 #define EFQAT_DX_KERNEL_AUTO 0
 #define EFQAT_DX_KERNEL_BF16 1
 #define EFQAT_DX_KERNEL_INT8 2
 #define EFQAT_DX_KERNEL_BF16_PINNED 3
-int efqat_set_option(int option, int value);
 
 /* ------------------------------------------------------------------ linear backward
  * Backward step of Alg. 1 for one layer Y = X_q W_q^T, X_q = S_x (x_codes - Z_x),
@@ -220,65 +230,75 @@ int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int
                      float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ weight operand made beforehand
- * Where the dX product (Eq. 5 left) of efqat_linear_bwd multiplies by a bf16 copy of W_q^T,
- * that copy depends on the weight codes and scales only, not on dY or the activations.  A
- * caller that quantizes its weights away from the critical path (another stream, an earlier
- * point of the step) can have it made there and hand it to efqat_linear_bwd_prepared, which
- * then skips that pass; results are bit-identical to efqat_linear_bwd.
+ * Where the dX product (Eq. 5 left) of efqat_linear_bwd multiplies by a bf16 copy of W_q^T, that copy
+ * depends on the weight codes and scales only, not on dY or the activations.  A caller that quantizes
+ * its weights away from the critical path (another stream, an earlier point of the step) can have it
+ * made there and hand it to efqat_linear_bwd_ex (argument w_operand), which then skips that pass;
+ * results are bit-identical to efqat_linear_bwd.
  *
  *   efqat_linear_bwd_weight_operand_bytes  size of the operand buffer for a layer, or 0 when the
- *       dX product of that layer reads the int8 codes themselves (no copy exists; the two
- *       calls below then ignore the buffer).  Depends on EFQAT_OPT_DX_KERNEL like the
- *       workspace size.
+ *       dX product of that layer reads the int8 codes themselves (no copy exists; the buffer is
+ *       then ignored).
  *   efqat_linear_bwd_weight_operand        fills it from w_codes int8 [c_out][c_in] and s_w
  *       float [c_out]: operand = bf16 [c_in][round_up(c_out, 8)] with
  *       operand[i][c] = bf16(s_w[c] * w_codes[c][i]), zero padding, then 256 zero bytes.
  *       operand: device, 256-byte aligned, owned by the caller, read-only afterwards.
- *   efqat_linear_bwd_prepared              efqat_linear_bwd with one more argument, w_operand
- *       (NULL: exactly efqat_linear_bwd).  The operand must come from the same w_codes, s_w,
- *       sizes, dy_dtype and dy_layout, and the work that fills it must be ordered before this
- *       call's stream reaches it (the caller's events).
- * Errors as in efqat_linear_bwd; a buffer that is too small is EFQAT_ERR_WORKSPACE. */
+ * The operand must come from the same w_codes, s_w, sizes, dy_dtype and dy_layout as the backward
+ * call, and the work that fills it must be ordered before that call's stream reaches it (the
+ * caller's events).  A buffer that is too small is EFQAT_ERR_WORKSPACE. */
 size_t efqat_linear_bwd_weight_operand_bytes(int64_t T, int64_t c_in, int64_t c_out, int dy_dtype,
                                              int dy_layout);
 int efqat_linear_bwd_weight_operand(const int8_t* w_codes, const float* s_w, int64_t T, int64_t c_in,
                                     int64_t c_out, int dy_dtype, int dy_layout, void* operand,
                                     size_t operand_bytes, void* stream);
-int efqat_linear_bwd_prepared(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
-                              int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
-                              const void* x, int x_dtype, const float* s_x, const float* z_x,
-                              const int8_t* w_codes, const uint32_t* w_clip, const float* w,
-                              const float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
-                              float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
-                              const void* w_operand, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ backward + optimizer step
- * efqat_linear_bwd followed, in the same pass over the k updated rows, by the optimizer step
- * that Alg. 1 applies to unfrozen channels (SGD; frozen rows, their scales and their momentum
- * are not touched), so that the weight gradient need not travel through memory:
+ * Optimizer step of Alg. 1 on the unfrozen channels, applied in the same pass over the k updated rows
+ * that finishes the weight gradient, so that it need not travel through memory.  Frozen rows, their
+ * scales and every piece of optimizer state that belongs to them are not touched.
  *
- *   g   = dW[c][:] + weight_decay * w[c][:]          c in idx
+ * Weight rows idx keep the optimizer of the full-precision run (Sec. 4 "Setup"): SGD with momentum
+ * and weight decay,
+ *   g   = dW[c][:] + weight_decay * w[c][:]
  *   buf = momentum * mom_w[c][:] + g  (stored back)  when momentum != 0, else buf = g
- *   w[c][:] -= lr_w * buf;   s_w[c] likewise from dS_w[c] with lr_s, mom_s and no decay.
+ *   w[c][:] -= lr_w * buf
+ * Their scales s_w[idx] are quantization parameters, which are always trained with Adam (Sec. 4
+ * "Setup"); with g = dS_w[c], per channel c in idx,
+ *   adam_t[c] += 1;  m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2   (stored back)
+ *   s_w[c] -= lr_s * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ * (Adam as published, with bias correction and no weight decay).  The paper gives no betas or eps
+ * and does not say what the Adam state of a frozen channel does: here every channel has its own
+ * moments and step count, which advance only when that channel is updated.
  *
- * w and s_w are read (old values: dX, the clip masks and dS_w refer to them) and then
- * updated in place; dw and ds_w become optional (NULL: not written).  Everything else as in
- * efqat_linear_bwd, including the workspace size. */
-typedef struct efqat_sgd_step {
+ * w and s_w are read (old values: dX, the clip masks and dS_w refer to them) and then updated in
+ * place; dw and ds_w become optional (NULL: not written). */
+typedef struct efqat_opt_step {
   float lr_w;          /* learning rate of the weights */
-  float lr_s;          /* learning rate of the weight scales */
-  float momentum;      /* 0: plain SGD, mom_w / mom_s are ignored and may be NULL */
+  float momentum;      /* 0: plain SGD, mom_w is ignored and may be NULL */
   float weight_decay;  /* weights only */
   float* mom_w;        /* device, float [c_out][c_in] (conv: [c_out][KH][KW][c_in]) */
-  float* mom_s;        /* device, float [c_out] */
-} efqat_sgd_step;
-int efqat_linear_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
-                         int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
-                         const void* x, int x_dtype, const float* s_x, const float* z_x,
-                         const int8_t* w_codes, const uint32_t* w_clip, float* w, float* s_w,
-                         const int32_t* idx, int64_t k, void* dx, int dx_dtype, float* dw,
-                         int scatter, float* ds_w, float* ds_x, float* dz_x,
-                         const efqat_sgd_step* step, void* ws, size_t ws_bytes, void* stream);
+  float lr_s;          /* Adam on the weight scales: learning rate, */
+  float beta1, beta2;  /*   decay rates in [0, 1), */
+  float eps;           /*   eps >= 0 */
+  float* adam_m;       /* device, float [c_out]: first moments  (zero before the first step) */
+  float* adam_v;       /* device, float [c_out]: second moments (zero before the first step) */
+  int32_t* adam_t;     /* device, int32 [c_out]: steps taken per channel (zero before the first) */
+} efqat_opt_step;
+
+/* efqat_linear_bwd with three optional extras (all NULL / 0: exactly efqat_linear_bwd):
+ *   w_operand  the dX weight operand made beforehand (see above); needs dx_kernel == AUTO
+ *   step       fused optimizer step (see above); w and s_w are then updated in place
+ *   dx_kernel  EFQAT_DX_KERNEL_*
+ * Workspace: efqat_linear_bwd_workspace_bytes_ex with the same dx_kernel. */
+size_t efqat_linear_bwd_workspace_bytes_ex(int64_t T, int64_t c_in, int64_t c_out, int64_t k,
+                                           int dy_dtype, int dy_layout, int dx_kernel);
+int efqat_linear_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
+                        int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
+                        int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
+                        const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
+                        void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
+                        float* dz_x, const void* w_operand, const efqat_opt_step* step, int dx_kernel,
+                        void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ conv backward
  * Same as efqat_linear_bwd for Y[n][ho][wo][co] = sum_{kh,kw,ci}
@@ -299,16 +319,17 @@ int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64
                    int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                    float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
-/* efqat_conv_bwd with the fused optimizer step of efqat_linear_bwd_sgd. */
-int efqat_conv_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
-                       int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride,
-                       int64_t pad, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
-                       int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
-                       const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
-                       void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
-                       float* dz_x, const efqat_sgd_step* step, void* ws, size_t ws_bytes,
-                       void* stream);
-
+/* efqat_conv_bwd with the optional fused optimizer step and dX kernel choice of efqat_linear_bwd_ex. */
+size_t efqat_conv_bwd_workspace_bytes_ex(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
+                                         int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                                         int64_t k, int dy_dtype, int dy_layout, int dx_kernel);
+int efqat_conv_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                      int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                      const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                      const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                      float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                      float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                      const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ low-precision forward
  * The forward product of Sec. 3.1, Y = X_q W_q^T, computed from the 8-bit codes on the int8 matrix
@@ -326,15 +347,24 @@ int efqat_linear_fwd(const uint8_t* x_codes, const float* s_x, const float* z_x,
                      void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------ kernel timing (benchmarks)
- * The two products of Eq. 5 dominate the backward pass; to report them against the matrix-core
- * roofline a benchmark can have every product kernel bracketed by HIP events on the stream it is
- * launched on.  This is the only process-wide state of the library; it is off by default and not
- * thread-safe.
+ * To report each kernel class against its roofline a benchmark can have the library bracket its
+ * launches with HIP events on the stream they go to.  This is the only process-wide state of the
+ * library; it is off by default and not thread-safe.
  *   efqat_profile_enable(on)  on != 0 starts a new measurement (counters reset), 0 stops it.
- *                             At most 4096 launches per product are recorded.
- *   efqat_profile_read(which, total_ms, launches)  which = 0: input-gradient product (dX),
- *                             1: weight-gradient product (dW), 2: forward product.  Waits for the recorded events
- *                             (host pointers out: summed kernel time in ms, number of launches). */
+ *                             At most 4096 brackets per class are recorded.
+ *   efqat_profile_read(which, total_ms, launches)  waits for the recorded events of one class
+ *                             (host pointers out: summed time in ms, number of brackets). */
+#define EFQAT_PROF_DX 0          /* input-gradient product with its fused epilogue */
+#define EFQAT_PROF_DW 1          /* weight-gradient product */
+#define EFQAT_PROF_FWD 2         /* low-precision forward product */
+#define EFQAT_PROF_PREP 3        /* operand preparation: compaction of the selected dY columns, staged copies */
+#define EFQAT_PROF_FINISH 4      /* second pass of the weight gradient (split-K sum, masks, dS_w, dS_x, dZ_x) */
+#define EFQAT_PROF_QUANT_ACT 5   /* efqat_fakequant_fwd, activations (all its kernels) */
+#define EFQAT_PROF_QUANT_W 6     /* efqat_fakequant_fwd, weights */
+#define EFQAT_PROF_IMPORTANCE 7  /* Eq. 6 scores */
+#define EFQAT_PROF_TOPK 8        /* Top-K */
+#define EFQAT_PROF_BIAS 9        /* efqat_bias_grad (both kernels) */
+#define EFQAT_PROF_CLASSES 10
 int efqat_profile_enable(int on);
 int efqat_profile_read(int which, double* total_ms, int64_t* launches);
 

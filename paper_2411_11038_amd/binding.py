@@ -14,22 +14,23 @@ DY_TOKEN_MAJOR, DY_CHANNEL_MAJOR = 0, 1
 EXPORTS = [
     "efqat_version", "efqat_strerror", "efqat_k_from_ratio",
     "efqat_fakequant_fwd_workspace_bytes", "efqat_fakequant_fwd",
-    "efqat_channel_select_workspace_bytes", "efqat_channel_select",
+    "efqat_channel_select_workspace_bytes", "efqat_channel_select", "efqat_channel_select_static",
     "efqat_network_select_workspace_bytes", "efqat_network_select",
     "efqat_layer_select_workspace_bytes", "efqat_layer_select",
     "efqat_bias_grad_workspace_bytes", "efqat_bias_grad",
-    "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd",
-    "efqat_linear_bwd_weight_operand_bytes", "efqat_linear_bwd_weight_operand", "efqat_linear_bwd_prepared",
-    "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd", "efqat_linear_bwd_sgd", "efqat_conv_bwd_sgd",
+    "efqat_linear_bwd_workspace_bytes", "efqat_linear_bwd_workspace_bytes_ex", "efqat_linear_bwd", "efqat_linear_bwd_ex",
+    "efqat_linear_bwd_weight_operand_bytes", "efqat_linear_bwd_weight_operand",
+    "efqat_conv_bwd_workspace_bytes", "efqat_conv_bwd_workspace_bytes_ex", "efqat_conv_bwd", "efqat_conv_bwd_ex",
     "efqat_linear_fwd_workspace_bytes", "efqat_linear_fwd",
-    "efqat_profile_enable", "efqat_profile_read", "efqat_set_option",
+    "efqat_profile_enable", "efqat_profile_read",
 ]
 
 
-class SgdStep(C.Structure):
-    """efqat_sgd_step of include/efqat.h."""
-    _fields_ = [("lr_w", C.c_float), ("lr_s", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
-                ("mom_w", C.c_void_p), ("mom_s", C.c_void_p)]
+class OptStep(C.Structure):
+    """efqat_opt_step of include/efqat.h."""
+    _fields_ = [("lr_w", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float), ("mom_w", C.c_void_p),
+                ("lr_s", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("adam_t", C.c_void_p)]
 
 
 class EfqatError(RuntimeError):
@@ -68,6 +69,8 @@ def lib():
     L.efqat_channel_select_workspace_bytes.argtypes = [i64]
     L.efqat_channel_select.restype = ci
     L.efqat_channel_select.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+    L.efqat_channel_select_static.restype = ci
+    L.efqat_channel_select_static.argtypes = [vp, i64, i64, i64, vp, vp]
     L.efqat_network_select_workspace_bytes.restype = sz
     L.efqat_network_select_workspace_bytes.argtypes = [i64]
     L.efqat_network_select.restype = ci
@@ -80,35 +83,32 @@ def lib():
     L.efqat_bias_grad_workspace_bytes.argtypes = [i64, i64, ci]
     L.efqat_bias_grad.restype = ci
     L.efqat_bias_grad.argtypes = [vp, ci, ci, i64, i64, vp, vp, sz, vp]
+    bwd_common = [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp] + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp]
     L.efqat_linear_bwd_workspace_bytes.restype = sz
     L.efqat_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+    L.efqat_linear_bwd_workspace_bytes_ex.restype = sz
+    L.efqat_linear_bwd_workspace_bytes_ex.argtypes = [i64, i64, i64, i64, ci, ci, ci]
     L.efqat_linear_bwd.restype = ci
-    L.efqat_linear_bwd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
-                                   + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_linear_bwd.argtypes = [vp, ci, ci, i64, i64, i64] + bwd_common + [vp, sz, vp]
+    L.efqat_linear_bwd_ex.restype = ci
+    L.efqat_linear_bwd_ex.argtypes = ([vp, ci, ci, i64, i64, i64] + bwd_common + [vp, C.POINTER(OptStep), ci]
+                                      + [vp, sz, vp])
     L.efqat_linear_bwd_weight_operand_bytes.restype = sz
     L.efqat_linear_bwd_weight_operand_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.efqat_linear_bwd_weight_operand.restype = ci
     L.efqat_linear_bwd_weight_operand.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, sz, vp]
-    L.efqat_linear_bwd_prepared.restype = ci
-    L.efqat_linear_bwd_prepared.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
-                                            + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, vp, sz, vp])
-    L.efqat_linear_bwd_sgd.restype = ci
-    L.efqat_linear_bwd_sgd.argtypes = ([vp, ci, ci, i64, i64, i64] + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
-                                       + [vp, i64, vp, ci, vp, ci, vp, vp, vp] + [C.POINTER(SgdStep), vp, sz, vp])
-    L.efqat_conv_bwd_sgd.restype = ci
-    L.efqat_conv_bwd_sgd.argtypes = ([vp, ci, ci] + [i64] * 9 + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
-                                     + [vp, i64, vp, ci, vp, ci, vp, vp, vp] + [C.POINTER(SgdStep), vp, sz, vp])
     L.efqat_conv_bwd_workspace_bytes.restype = sz
     L.efqat_conv_bwd_workspace_bytes.argtypes = [i64] * 10 + [ci, ci]
+    L.efqat_conv_bwd_workspace_bytes_ex.restype = sz
+    L.efqat_conv_bwd_workspace_bytes_ex.argtypes = [i64] * 10 + [ci, ci, ci]
     L.efqat_conv_bwd.restype = ci
-    L.efqat_conv_bwd.argtypes = ([vp, ci, ci] + [i64] * 9 + [vp, vp, vp, ci, vp, vp] + [vp, vp, vp, vp]
-                                 + [vp, i64] + [vp, ci, vp, ci, vp, vp, vp] + [vp, sz, vp])
+    L.efqat_conv_bwd.argtypes = [vp, ci, ci] + [i64] * 9 + bwd_common + [vp, sz, vp]
+    L.efqat_conv_bwd_ex.restype = ci
+    L.efqat_conv_bwd_ex.argtypes = [vp, ci, ci] + [i64] * 9 + bwd_common + [C.POINTER(OptStep), ci] + [vp, sz, vp]
     L.efqat_linear_fwd_workspace_bytes.restype = sz
     L.efqat_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.efqat_linear_fwd.restype = ci
     L.efqat_linear_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp, ci, vp, sz, vp]
-    L.efqat_set_option.restype = ci
-    L.efqat_set_option.argtypes = [ci, ci]
     L.efqat_profile_enable.restype = ci
     L.efqat_profile_enable.argtypes = [ci]
     L.efqat_profile_read.restype = ci
@@ -153,8 +153,12 @@ def profile_enable(on: bool) -> None:
     _check(lib().efqat_profile_enable(int(bool(on))), "efqat_profile_enable")
 
 
+PROF_DX, PROF_DW, PROF_FWD, PROF_PREP, PROF_FINISH, PROF_QUANT_ACT, PROF_QUANT_W, PROF_IMPORTANCE, PROF_TOPK, \
+    PROF_BIAS, PROF_CLASSES = range(11)
+
+
 def profile_read(which: int):
-    """(total kernel ms, launches) of the dX (which=0) or dW (which=1) product since profile_enable(True)."""
+    """(total ms, brackets) of kernel class `which` (PROF_*) since profile_enable(True)."""
     ms, n = C.c_double(0.0), C.c_int64(0)
     _check(lib().efqat_profile_read(which, C.byref(ms), C.byref(n)), "efqat_profile_read")
     return ms.value, n.value
@@ -219,6 +223,17 @@ def channel_select(w: torch.Tensor, k: int, want_scores: bool = True, ws=None, o
     return idx, scores
 
 
+def channel_select_static(w: torch.Tensor, k: int, out=None):
+    """efqat_channel_select_static: the same selection with the library's built-in scratch (no workspace, no scores
+    output).  `out`: preallocated int32[k].  Returns idx."""
+    c_out = w.shape[0]
+    block = w[0].numel()
+    idx = out if out is not None else torch.empty(max(k, 0), dtype=torch.int32, device=w.device)
+    rc = lib().efqat_channel_select_static(_p(w), c_out, block, k, _p(idx) if k > 0 else None, _stream())
+    _check(rc, "efqat_channel_select_static")
+    return idx
+
+
 def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, ws=None):
     """Returns (idx int32[k_total] of layer-local channel indices, k_per_layer int32[n_layers])."""
     L = lib()
@@ -234,12 +249,7 @@ def network_select(scores: torch.Tensor, layer_off: torch.Tensor, k_total: int, 
     return idx, kpl
 
 
-OPT_DX_KERNEL, DX_KERNEL_AUTO, DX_KERNEL_BF16, DX_KERNEL_INT8, DX_KERNEL_BF16_PINNED = 1, 0, 1, 2, 3
-
-
-def set_option(option: int, value: int):
-    """Process-wide override (tests, measurements); see efqat_set_option in include/efqat.h."""
-    _check(lib().efqat_set_option(option, value), "efqat_set_option")
+DX_KERNEL_AUTO, DX_KERNEL_BF16, DX_KERNEL_INT8, DX_KERNEL_BF16_PINNED = 0, 1, 2, 3
 
 
 def layer_select(scores: torch.Tensor, layer_off: torch.Tensor, k_layers: int, ws=None):
@@ -289,10 +299,13 @@ def _bwd_outputs(x, w, k, dx_dtype, scatter):
     return dx, dw, ds_w, ds_x, dz_x
 
 
-def _sgd_struct(sgd):
-    """dict(lr_w, lr_s, momentum=0, weight_decay=0, mom_w=None, mom_s=None) -> SgdStep"""
-    return SgdStep(float(sgd["lr_w"]), float(sgd["lr_s"]), float(sgd.get("momentum", 0.0)),
-                   float(sgd.get("weight_decay", 0.0)), _p(sgd.get("mom_w")), _p(sgd.get("mom_s")))
+def _step_struct(step):
+    """dict(lr_w, momentum=0, weight_decay=0, mom_w=None, lr_s, beta1=0.9, beta2=0.999, eps=1e-8, adam_m, adam_v,
+    adam_t) -> OptStep"""
+    return OptStep(float(step["lr_w"]), float(step.get("momentum", 0.0)), float(step.get("weight_decay", 0.0)),
+                   _p(step.get("mom_w")), float(step["lr_s"]), float(step.get("beta1", 0.9)),
+                   float(step.get("beta2", 0.999)), float(step.get("eps", 1e-8)), _p(step["adam_m"]),
+                   _p(step["adam_v"]), _p(step["adam_t"]))
 
 
 def linear_bwd_weight_operand(w_codes, s_w, T, dy_dtype=BF16, dy_layout=DY_TOKEN_MAJOR, out=None):
@@ -312,11 +325,12 @@ def linear_bwd_weight_operand(w_codes, s_w, T, dy_dtype=BF16, dy_layout=DY_TOKEN
 
 
 def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, dy_layout=DY_TOKEN_MAJOR,
-               dx_dtype=None, scatter=False, ws=None, out=None, sgd=None, w_operand=None):
+               dx_dtype=None, scatter=False, ws=None, out=None, step=None, w_operand=None, dx_kernel=DX_KERNEL_AUTO):
     """Backward of one quantized linear layer restricted to the rows idx.  Returns
     dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys).
-    sgd: dict for the fused optimizer step (efqat_linear_bwd_sgd): w and s_w are then updated in place.
-    w_operand: the tensor made by linear_bwd_weight_operand for these weights (efqat_linear_bwd_prepared)."""
+    step: dict for the fused optimizer step (see _step_struct): w and s_w are then updated in place.
+    w_operand: the tensor made by linear_bwd_weight_operand for these weights.
+    dx_kernel: DX_KERNEL_* (tests and measurements).  Any of the three routes the call to efqat_linear_bwd_ex."""
     L = lib()
     T, c_in = x_codes.shape
     c_out = w_codes.shape[0]
@@ -326,22 +340,18 @@ def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, d
         dx, dw, ds_w, ds_x, dz_x = _bwd_outputs(x, w, k, dx_dtype, scatter)
     else:
         dx, dw, ds_w, ds_x, dz_x = out["dx"], out["dw"], out["ds_w"], out["ds_x"], out["dz_x"]
-    need = L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, _dt(dy), dy_layout)
     if ws is None:
-        ws = _ws(need, x)
+        ws = _ws(L.efqat_linear_bwd_workspace_bytes_ex(T, c_in, c_out, k, _dt(dy), dy_layout, dx_kernel), x)
     args = (_p(dy), _dt(dy), dy_layout, T, c_in, c_out, _p(x_codes), _p(x_clip), _p(x), _dt(x),
             _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
-            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
-            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x))
-    if sgd is None and w_operand is not None:
-        rc = L.efqat_linear_bwd_prepared(*args, _p(w_operand), _p(ws), ws.numel(), _stream())
-    elif sgd is None:
+            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 and dw is not None else None,
+            int(bool(scatter)), _p(ds_w) if k > 0 and ds_w is not None else None, _p(ds_x), _p(dz_x))
+    if step is None and w_operand is None and dx_kernel == DX_KERNEL_AUTO:
         rc = L.efqat_linear_bwd(*args, _p(ws), ws.numel(), _stream())
     else:
-        if w_operand is not None:
-            raise ValueError("w_operand cannot be combined with the fused optimizer step")
-        step = _sgd_struct(sgd)
-        rc = L.efqat_linear_bwd_sgd(*args, C.byref(step), _p(ws), ws.numel(), _stream())
+        st = _step_struct(step) if step is not None else None
+        rc = L.efqat_linear_bwd_ex(*args, _p(w_operand), C.byref(st) if st is not None else None, dx_kernel,
+                                   _p(ws), ws.numel(), _stream())
     _check(rc, "efqat_linear_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)
 
@@ -361,7 +371,8 @@ def linear_fwd(x_codes, s_x, z_x, w_codes, s_w, y_dtype=torch.bfloat16, ws=None,
 
 
 def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, stride=1, pad=0,
-             dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None, sgd=None):
+             dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None, step=None,
+             dx_kernel=DX_KERNEL_AUTO):
     """Backward of one quantized conv layer (x NHWC, w OHWI) restricted to output channels idx."""
     L = lib()
     N, H, W, c_in = x_codes.shape
@@ -372,17 +383,18 @@ def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, str
         dx, dw, ds_w, ds_x, dz_x = _bwd_outputs(x, w, k, dx_dtype, scatter)
     else:
         dx, dw, ds_w, ds_x, dz_x = out["dx"], out["dw"], out["ds_w"], out["ds_x"], out["dz_x"]
-    need = L.efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, _dt(dy), dy_layout)
     if ws is None:
-        ws = _ws(need, x)
+        ws = _ws(L.efqat_conv_bwd_workspace_bytes_ex(N, H, W, c_in, c_out, KH, KW, stride, pad, k, _dt(dy), dy_layout,
+                                                     dx_kernel), x)
     args = (_p(dy), _dt(dy), dy_layout, N, H, W, c_in, c_out, KH, KW, stride, pad, _p(x_codes),
             _p(x_clip), _p(x), _dt(x), _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
-            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 else None,
-            int(bool(scatter)), _p(ds_w) if k > 0 else None, _p(ds_x), _p(dz_x))
-    if sgd is None:
+            _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 and dw is not None else None,
+            int(bool(scatter)), _p(ds_w) if k > 0 and ds_w is not None else None, _p(ds_x), _p(dz_x))
+    if step is None and dx_kernel == DX_KERNEL_AUTO:
         rc = L.efqat_conv_bwd(*args, _p(ws), ws.numel(), _stream())
     else:
-        step = _sgd_struct(sgd)
-        rc = L.efqat_conv_bwd_sgd(*args, C.byref(step), _p(ws), ws.numel(), _stream())
+        st = _step_struct(step) if step is not None else None
+        rc = L.efqat_conv_bwd_ex(*args, C.byref(st) if st is not None else None, dx_kernel, _p(ws), ws.numel(),
+                                 _stream())
     _check(rc, "efqat_conv_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)

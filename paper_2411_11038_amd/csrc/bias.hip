@@ -134,6 +134,7 @@ extern "C" int efqat_bias_grad(const void* dy, int dy_dtype, int dy_layout, int6
   if (ws_bytes < efqat_bias_grad_workspace_bytes(T, c_out, dy_layout)) return EFQAT_ERR_WORKSPACE;
   if (((uintptr_t)ws % 256) != 0) return EFQAT_ERR_ALIGNMENT;
   hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(PROF_BIAS, st);
   float* part = (float*)ws;
   int64_t seg = 0;
   const int64_t nchunks = bias_chunks(T, c_out, dy_layout, &seg);

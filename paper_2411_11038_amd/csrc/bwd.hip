@@ -237,12 +237,17 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
   sum_partials_block<256>(part, n, ds_x, dz_x);
 }
 
-// Optional optimizer step fused into the second pass (off when w == nullptr): SGD with momentum and weight decay
-// on the rows idx of the master weights and on their scales, the rule of Alg. 1's optimizer step for unfrozen
-// channels:  g = dW + wd * W;  buf = mu * buf + g;  W -= lr_w * buf   (buf is skipped when mu == 0; scales: no decay).
-struct SgdArgs {
-  float* w; float* s_w; float* mom_w; float* mom_s;
-  float lr_w, lr_s, mu, wd;
+// Optional optimizer step fused into the second pass (off when w == nullptr), the rule of Alg. 1's optimizer step for
+// unfrozen channels.  Weight rows idx: SGD with momentum and weight decay, the optimizer the network parameters keep from
+// the full-precision run:  g = dW + wd * W;  buf = mu * buf + g;  W -= lr_w * buf  (buf is skipped when mu == 0).
+// Their scales S_w[idx]: Adam, which the quantization parameters are always trained with (Sec. 4 "Setup"), one state
+// and step count per channel:  t += 1;  m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;
+// S_w -= lr_s * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
+struct StepArgs {
+  float* w; float* mom_w;
+  float lr_w, mu, wd;
+  float* s_w; float* adam_m; float* adam_v; int32_t* adam_t;
+  float lr_s, b1, b2, eps;
 };
 
 // Second pass of the restricted weight gradient: ordered split-K sum, S_x scaling, straight-through mask
@@ -258,7 +263,7 @@ __global__ __launch_bounds__(NTH) void k_dw_finish(const float* __restrict__ par
                                                    float* __restrict__ dw, int scatter, float* __restrict__ ds_w,
                                                    const float* __restrict__ part_dx, int64_t n_part_dx,
                                                    float* __restrict__ ds_x, float* __restrict__ dz_x,
-                                                   const SgdArgs sgd) {
+                                                   const StepArgs sgd) {
   if ((int64_t)blockIdx.x == k) {                     // one extra block: dS_x, dZ_x from the dX epilogue's partials
     sum_partials_block<NTH>(part_dx, n_part_dx, ds_x, dz_x);
     return;
@@ -350,12 +355,16 @@ __global__ __launch_bounds__(NTH) void k_dw_finish(const float* __restrict__ par
     for (int w = 0; w < NTH / 64; w += 4) ds += (red[w] + red[w + 1]) + (red[w + 2] + red[w + 3]);   // fixed order
     if (ds_w) ds_w[orow] = ds;
     if (sgd.s_w) {
-      float gq = ds;
-      if (sgd.mom_s) {
-        gq = fmaf(sgd.mu, sgd.mom_s[c], gq);
-        sgd.mom_s[c] = gq;
-      }
-      sgd.s_w[c] = fmaf(-sgd.lr_s, gq, sw);
+      // one scalar per row: double precision costs nothing here and leaves only the fp32 storage rounding
+      const int t = sgd.adam_t[c] + 1;
+      const double g = (double)ds, b1 = (double)sgd.b1, b2 = (double)sgd.b2;
+      const double m = b1 * (double)sgd.adam_m[c] + (1.0 - b1) * g;
+      const double v = b2 * (double)sgd.adam_v[c] + (1.0 - b2) * g * g;
+      const double m_hat = m / (1.0 - pow(b1, (double)t)), v_hat = v / (1.0 - pow(b2, (double)t));
+      sgd.adam_t[c] = t;
+      sgd.adam_m[c] = (float)m;
+      sgd.adam_v[c] = (float)v;
+      sgd.s_w[c] = (float)((double)sw - (double)sgd.lr_s * m_hat / (sqrt(v_hat) + (double)sgd.eps));
     }
   }
 }
@@ -386,9 +395,6 @@ static int transpose_to_bf16(const T* in, int64_t ld_in, int64_t R, int64_t Cn, 
   return EFQAT_OK;
 }
 
-// Process-wide override of the dX kernel choice (efqat_set_option), for tests and measurements.
-static int g_opt_dx_kernel = EFQAT_DX_KERNEL_AUTO;
-
 // Plan of one backward call: sizes of every workspace slice (shared by the size query and the call).
 struct BwdPlan {
   int64_t Mx;      // rows of dX as a matrix (T, or N*H*W)
@@ -413,10 +419,11 @@ struct BwdPlan {
   size_t b_wqT, b_dyn, b_colA, b_part_dx, b_xcT, b_sel, b_part_dw, b_zero, total;
 };
 
-// io_bf16: x and dX are both bf16 (known at the call, not at the workspace query: nothing it changes may change
-// a workspace size).
+// dxk: the caller's choice of the dX kernel (EFQAT_DX_KERNEL_*); it changes workspace sizes, so the size query takes
+// it as well.  io_bf16: x and dX are both bf16 (known at the call, not at the workspace query: nothing it changes
+// may change a workspace size).
 static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, int taps, int64_t k,
-                         int dy_dtype, int dy_layout, bool im2col, const ConvGeom* cg = nullptr,
+                         int dy_dtype, int dy_layout, bool im2col, int dxk, const ConvGeom* cg = nullptr,
                          bool io_bf16 = false) {
   BwdPlan p{};
   p.Mx = T_in; p.Tw = T_out; p.Nw = (int64_t)taps * c_in;
@@ -429,7 +436,7 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   p.tn = k > 0 && dy_layout == EFQAT_DY_TOKEN_MAJOR && ((!im2col && (c_in % 16) == 0) || p.cdw);
   p.tn_direct = p.tn && direct_tok && k == c_out;
   p.rdw = k > 0 && direct_rows && !im2col && (c_in % 16) == 0;
-  p.cmx = direct_rows && !im2col && taps == 1 && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16_PINNED;
+  p.cmx = direct_rows && !im2col && taps == 1 && (c_in % 16) == 0 && dxk != EFQAT_DX_KERNEL_BF16_PINNED;
   if (p.cmx) p.need_dyn = false;
   p.kp = round_up(k, 8);
   p.need_sel = k > 0 && !direct_rows && !p.tn_direct;
@@ -442,20 +449,20 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   if (p.cmx) {
     p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, false);
     p.dx8 = true; p.dx8_tile = p.plan_dx.tile;
-  } else if (g_opt_dx_kernel == EFQAT_DX_KERNEL_BF16_PINNED) {
+  } else if (dxk == EFQAT_DX_KERNEL_BF16_PINNED) {
     if (!p.cdx) {
       p.plan_dx.tile = 192; p.plan_dx.split_k = 1;
       p.plan_dx.tiles_m = (int)ceil_div(p.Mx, 192); p.plan_dx.tiles_n = (int)ceil_div(c_in, 192);
     }
-  } else if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16 &&
-      (p.plan_dx.tile == 256 || g_opt_dx_kernel == EFQAT_DX_KERNEL_INT8)) {
+  } else if (taps == 1 && !im2col && direct_tok && (c_in % 16) == 0 && dxk != EFQAT_DX_KERNEL_BF16 &&
+      (p.plan_dx.tile == 256 || dxk == EFQAT_DX_KERNEL_INT8)) {
     p.dx8 = true; p.dx8_tile = (p.plan_dx.tile == 256 || (p.Mx >= 1024 && c_in >= 512)) ? 256 : 128;
     p.plan_dx.tiles_m = (int)ceil_div(p.Mx, p.dx8_tile); p.plan_dx.tiles_n = (int)ceil_div(c_in, p.dx8_tile);
   }
   // bf16 in and out, whole 192 x 192 tiles: the pinned kernel with its straight-line epilogue changes the ranking of
   // the tiles below 256 (the workspace slices do not depend on the outcome)
   if (!p.dx8 && !p.cdx && io_bf16 && p.plan_dx.tile != 256 && (p.Mx % 192) == 0 && (c_in % 192) == 0 &&
-      p.Mx * c_in <= (int64_t)INT32_MAX && g_opt_dx_kernel != EFQAT_DX_KERNEL_BF16_PINNED)
+      p.Mx * c_in <= (int64_t)INT32_MAX && dxk != EFQAT_DX_KERNEL_BF16_PINNED)
     p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, true, false, true);
   p.kk = !p.dx8 && !p.cdx && p.plan_dx.tile == 192;
   p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !(p.tn || p.rdw), !p.cdw) : GemmPlan{128, 1, 0, 0};
@@ -480,18 +487,32 @@ struct BwdIo {
   const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype; const float* s_x; const float* z_x;
   const int8_t* w_codes; const uint32_t* w_clip; const float* w; const float* s_w; const int32_t* idx; int64_t k;
   void* dx; int dx_dtype; float* dw; int scatter; float* ds_w; float* ds_x; float* dz_x;
-  SgdArgs sgd;     // fused optimizer step (sgd.w == nullptr: none)
+  StepArgs sgd;    // fused optimizer step (sgd.w == nullptr: none)
   const void* w_operand = nullptr;   // optional: the bf16 W_q^T matrix (then 256 zero bytes) made beforehand
 };
 
+// Everything that can still fail once the plan is known, checked before the first launch: pointer alignment of the
+// operands that the chosen kernels copy 16 bytes at a time, and the grid limits of the staging kernels.
+static int check_plan(const BwdPlan& p, const BwdIo& io, int64_t T_out, int64_t c_in, int64_t c_out, bool im2col) {
+  if (p.dx8 && ((uintptr_t)io.w_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
+  if ((p.tn || p.rdw) && ((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
+  const int64_t ymax = 65535 * (int64_t)64;           // the transposing copies put 64 source columns on grid.y
+  if (!p.dx8 && !io.w_operand && c_in > ymax) return EFQAT_ERR_BAD_SHAPE;
+  if (p.need_dyn && io.dy_layout == EFQAT_DY_CHANNEL_MAJOR && T_out > ymax) return EFQAT_ERR_BAD_SHAPE;
+  if (io.k > 0 && !p.tn && !p.rdw && (c_in > ymax || io.k > ymax)) return EFQAT_ERR_BAD_SHAPE;
+  // 32-bit per-stage pointer steps of the kernels that read operands as they lie
+  if ((p.dx8 || p.tn || p.rdw) && (c_in >= (1 << 24) || c_out >= (1 << 24))) return EFQAT_ERR_BAD_SHAPE;
+  if ((p.cmx || p.rdw) && T_out >= (1 << 24)) return EFQAT_ERR_BAD_SHAPE;
+  (void)im2col;
+  return EFQAT_OK;
+}
+
 // Shared driver.  For conv, T_in = N*H*W input pixels, T_out = N*Ho*Wo output pixels; for linear both are T.
-static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out, const ConvGeom* cg,
-                   void* ws, hipStream_t st) {
+static int run_bwd(const BwdIo& io, const BwdPlan& p, int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_out,
+                   const ConvGeom* cg, void* ws, hipStream_t st) {
   const int taps = cg ? cg->KH * cg->KW : 1;
   // a 1x1 / stride 1 / no-padding convolution is a linear layer over pixels: no im2col needed
   const bool im2col = cg != nullptr && !(taps == 1 && cg->stride == 1 && cg->pad == 0);
-  const BwdPlan p = make_plan(T_in, T_out, c_in, c_out, taps, io.k, io.dy_dtype, io.dy_layout, im2col, cg,
-                              io.x_dtype == EFQAT_BF16 && io.dx_dtype == EFQAT_BF16);
   WsCarver cv(ws);
   bf16_t* wqT = (bf16_t*)cv.take(p.b_wqT);
   bf16_t* dyn = (bf16_t*)cv.take(p.b_dyn);
@@ -503,6 +524,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   float* part_dw = (float*)cv.take(p.b_part_dw);
   int rc;
 
+  ProfScope prep(PROF_PREP, st);                       // operand preparation ahead of the dX product
   // ---- W_q^T in bf16:  wqT[ci][tap*ldc + co] = S_w[co] * code[co][tap][ci], zero for co in [c_out, ldc)
   if (!p.dx8 && io.w_operand) {
     // made beforehand by efqat_linear_bwd_weight_operand (same kernel, same bits), with its own zero page behind it
@@ -552,9 +574,9 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     EFQAT_LAUNCH_CHECK();
     A = colA; lda = p.Kx;
   }
+  prep.close();
   GemmEpilogueDx epi{io.x_codes, io.x_clip, io.x, io.x_dtype, io.s_x, io.z_x, io.dx, io.dx_dtype, part_dx};
   if (p.dx8) {
-    if (((uintptr_t)io.w_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
     if (p.cmx)
       rc = launch_gemm_dx8_cm((const bf16_t*)io.dy, T_out, io.w_codes, c_in, io.s_w, zero_page, p.Mx, c_in, c_out,
                               p.dx8_tile, epi, st);
@@ -571,6 +593,7 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   if (rc) return rc;
   const int64_t n_part_dx = (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n;
   if (io.k == 0) {
+    ProfScope fin(PROF_FINISH, st);
     hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, part_dx, n_part_dx, io.ds_x, io.dz_x);
     EFQAT_LAUNCH_CHECK();
     return EFQAT_OK;
@@ -579,10 +602,10 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   if (p.tn) {
     // ---- dW product straight from token-major operands: A = the selected columns of dY (compacted once, or dY
     // itself when every channel is selected), B = the uint8 codes; transposition happens in the LDS reads
-    if (((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
     const bf16_t* At = (const bf16_t*)io.dy;
     int64_t ldat = c_out, acols = c_out;
     if (!p.tn_direct) {
+      ProfScope gat(PROF_PREP, st);
       const dim3 ggrid((unsigned)ceil_div(p.kp, 128), (unsigned)std::min<int64_t>(ceil_div(T_out, kGatherRows), 65535));
       if (io.dy_dtype == EFQAT_F32)
         hipLaunchKernelGGL((k_gather_cols<float>), ggrid, dim3(256), 0, st, (const float*)io.dy, c_out, T_out, io.idx,
@@ -604,11 +627,11 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     if (rc) return rc;
   } else if (p.rdw) {
     // ---- channel-major dY: the selected rows are gathered by the tile loads, the codes are read as they lie
-    if (((uintptr_t)io.x_codes % 16) != 0) return EFQAT_ERR_ALIGNMENT;
     rc = launch_gemm_dw_rows((const bf16_t*)io.dy, T_out, io.idx, io.x_codes, c_in, zero_page, io.z_x, io.k, p.Nw,
                              T_out, p.plan_dw, part_dw, st);
     if (rc) return rc;
   } else {
+  ProfScope stg(PROF_PREP, st);                        // staged bf16 operands of the fall-back product
   // ---- B operand of the dW product: (codes - Z_x)^T, exact in bf16
   if (im2col) {
     TransposeExtra ex{};
@@ -646,11 +669,13 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
     Aw = sel; ldaw = p.ldt; a_rows = nullptr;
   }
   const int64_t Kw = p.need_sel ? p.ldt : T_out;
+  stg.close();
   rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.plan_dw, part_dw, nullptr, st);
   if (rc) return rc;
   }
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0 && ((uintptr_t)io.sgd.mom_w % 16) == 0) ? 1 : 0;
+  ProfScope fin(PROF_FINISH, st);
   // k blocks for the rows of dW plus one that finishes dS_x, dZ_x
   // long rows and few of them: the chain of dependent loads per row, not bandwidth, sets the time
   if (fvec && p.Nw >= 2048 && io.k < 512)
@@ -665,11 +690,12 @@ static int run_bwd(const BwdIo& io, int64_t T_in, int64_t T_out, int64_t c_in, i
   return EFQAT_OK;
 }
 
-static int check_common(const BwdIo& io, int64_t c_out, const void* ws) {
+static int check_common(const BwdIo& io, int64_t c_out, const void* ws, int dxk) {
   if (io.dy_dtype != EFQAT_F32 && io.dy_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
   if (io.x_dtype != EFQAT_F32 && io.x_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
   if (io.dx_dtype != EFQAT_F32 && io.dx_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
   if (io.dy_layout != EFQAT_DY_TOKEN_MAJOR && io.dy_layout != EFQAT_DY_CHANNEL_MAJOR) return EFQAT_ERR_BAD_LAYOUT;
+  if (dxk < EFQAT_DX_KERNEL_AUTO || dxk > EFQAT_DX_KERNEL_BF16_PINNED) return EFQAT_ERR_BAD_LAYOUT;
   if (io.k < 0 || io.k > c_out) return EFQAT_ERR_BAD_K;
   if (io.scatter != 0 && io.scatter != 1) return EFQAT_ERR_BAD_LAYOUT;
   if (!io.dy || !io.x_codes || !io.x_clip || !io.x || !io.s_x || !io.z_x || !io.w_codes || !io.s_w || !io.dx ||
@@ -683,24 +709,72 @@ static int check_common(const BwdIo& io, int64_t c_out, const void* ws) {
   if (((uintptr_t)io.dy % 16) != 0 || ((uintptr_t)io.dy % dysz) != 0) return EFQAT_ERR_ALIGNMENT;
   if (((uintptr_t)io.x % (io.x_dtype == EFQAT_F32 ? 4 : 2)) != 0) return EFQAT_ERR_ALIGNMENT;
   if (((uintptr_t)io.dx % (io.dx_dtype == EFQAT_F32 ? 4 : 2)) != 0) return EFQAT_ERR_ALIGNMENT;
+  if (((uintptr_t)io.w % 4) != 0 || ((uintptr_t)io.s_w % 4) != 0 || ((uintptr_t)io.dw % 4) != 0 ||
+      ((uintptr_t)io.ds_w % 4) != 0 || ((uintptr_t)io.idx % 4) != 0 || ((uintptr_t)io.x_clip % 4) != 0 ||
+      ((uintptr_t)io.w_clip % 4) != 0)
+    return EFQAT_ERR_ALIGNMENT;
   return EFQAT_OK;
+}
+
+static int fill_step(const efqat_opt_step* step, float* w, float* s_w, StepArgs* out) {
+  if (!step || !w || !s_w) return EFQAT_ERR_NULL_PTR;
+  if (step->momentum != 0.0f && !step->mom_w) return EFQAT_ERR_NULL_PTR;
+  if (!step->adam_m || !step->adam_v || !step->adam_t) return EFQAT_ERR_NULL_PTR;
+  if (((uintptr_t)step->mom_w % 4) != 0 || ((uintptr_t)step->adam_m % 4) != 0 || ((uintptr_t)step->adam_v % 4) != 0 ||
+      ((uintptr_t)step->adam_t % 4) != 0)
+    return EFQAT_ERR_ALIGNMENT;
+  // 0 <= beta < 1 (the bias correction divides by 1 - beta^t), eps >= 0
+  if (!(step->beta1 >= 0.0f && step->beta1 < 1.0f) || !(step->beta2 >= 0.0f && step->beta2 < 1.0f) ||
+      !(step->eps >= 0.0f))
+    return EFQAT_ERR_BAD_LAYOUT;
+  out->w = w; out->s_w = s_w;
+  out->mom_w = step->momentum != 0.0f ? step->mom_w : nullptr;
+  out->lr_w = step->lr_w; out->mu = step->momentum; out->wd = step->weight_decay;
+  out->adam_m = step->adam_m; out->adam_v = step->adam_v; out->adam_t = step->adam_t;
+  out->lr_s = step->lr_s; out->b1 = step->beta1; out->b2 = step->beta2; out->eps = step->eps;
+  return EFQAT_OK;
+}
+
+// Upper limits of the linear entry points: tokens up to 2^30, channel counts below 2^24 (32-bit pointer steps)
+static bool linear_shape_ok(int64_t T, int64_t c_in, int64_t c_out) {
+  return T > 0 && c_in > 0 && c_out > 0 && T <= (1 << 30) && c_in < (1 << 24) && c_out < (1 << 24);
+}
+
+// All linear entry points end here: every check first, then the launches.
+static int linear_bwd_entry(BwdIo& io, int64_t T, int64_t c_in, int64_t c_out, const efqat_opt_step* step, float* w_rw,
+                            float* s_w_rw, int dxk, void* ws, size_t ws_bytes, void* stream) {
+  if (!linear_shape_ok(T, c_in, c_out)) return EFQAT_ERR_BAD_SHAPE;
+  int rc;
+  if (step) {
+    rc = fill_step(step, w_rw, s_w_rw, &io.sgd);
+    if (rc) return rc;
+  }
+  rc = check_common(io, c_out, ws, dxk);
+  if (rc) return rc;
+  if (io.w_operand && dxk != EFQAT_DX_KERNEL_AUTO) return EFQAT_ERR_BAD_LAYOUT;   // the operand belongs to the default plan
+  if (io.w_operand && ((uintptr_t)io.w_operand % 256) != 0) return EFQAT_ERR_ALIGNMENT;
+  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, io.k, io.dy_dtype, io.dy_layout, false, dxk, nullptr,
+                              io.x_dtype == EFQAT_BF16 && io.dx_dtype == EFQAT_BF16);
+  if (ws_bytes < p.total) return EFQAT_ERR_WORKSPACE;
+  rc = check_plan(p, io, T, c_in, c_out, false);
+  if (rc) return rc;
+  return run_bwd(io, p, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
 }
 
 }  // namespace efqat
 
 using namespace efqat;
 
-extern "C" int efqat_set_option(int option, int value) {
-  if (option != EFQAT_OPT_DX_KERNEL) return EFQAT_ERR_BAD_LAYOUT;
-  if (value < EFQAT_DX_KERNEL_AUTO || value > EFQAT_DX_KERNEL_BF16_PINNED) return EFQAT_ERR_BAD_LAYOUT;
-  g_opt_dx_kernel = value;
-  return EFQAT_OK;
+extern "C" size_t efqat_linear_bwd_workspace_bytes_ex(int64_t T, int64_t c_in, int64_t c_out, int64_t k, int dy_dtype,
+                                                      int dy_layout, int dx_kernel) {
+  if (!linear_shape_ok(T, c_in, c_out) || k < 0 || k > c_out) return 0;
+  if (dx_kernel < EFQAT_DX_KERNEL_AUTO || dx_kernel > EFQAT_DX_KERNEL_BF16_PINNED) return 0;
+  return make_plan(T, T, c_in, c_out, 1, k, dy_dtype, dy_layout, false, dx_kernel).total;
 }
 
 extern "C" size_t efqat_linear_bwd_workspace_bytes(int64_t T, int64_t c_in, int64_t c_out, int64_t k, int dy_dtype,
                                                    int dy_layout) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || k < 0 || k > c_out) return 0;
-  return make_plan(T, T, c_in, c_out, 1, k, dy_dtype, dy_layout, false).total;
+  return efqat_linear_bwd_workspace_bytes_ex(T, c_in, c_out, k, dy_dtype, dy_layout, EFQAT_DX_KERNEL_AUTO);
 }
 
 extern "C" int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in, int64_t c_out,
@@ -709,28 +783,35 @@ extern "C" int efqat_linear_bwd(const void* dy, int dy_dtype, int dy_layout, int
                                 const float* w, const float* s_w, const int32_t* idx, int64_t k, void* dx,
                                 int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
                                 void* ws, size_t ws_bytes, void* stream) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
-    return EFQAT_ERR_BAD_SHAPE;
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
-  int rc = check_common(io, c_out, ws);
-  if (rc) return rc;
-  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
-  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
+  return linear_bwd_entry(io, T, c_in, c_out, nullptr, nullptr, nullptr, EFQAT_DX_KERNEL_AUTO, ws, ws_bytes, stream);
+}
+
+extern "C" int efqat_linear_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in, int64_t c_out,
+                                   const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                                   const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                                   float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                                   float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                                   const void* w_operand, const efqat_opt_step* step, int dx_kernel, void* ws,
+                                   size_t ws_bytes, void* stream) {
+  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
+           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  io.w_operand = w_operand;
+  return linear_bwd_entry(io, T, c_in, c_out, step, w, s_w, dx_kernel, ws, ws_bytes, stream);
 }
 
 extern "C" size_t efqat_linear_bwd_weight_operand_bytes(int64_t T, int64_t c_in, int64_t c_out, int dy_dtype,
                                                         int dy_layout) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30)) return 0;
-  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false);
+  if (!linear_shape_ok(T, c_in, c_out)) return 0;
+  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false, EFQAT_DX_KERNEL_AUTO);
   return p.dx8 ? 0 : (size_t)round_up((int64_t)p.b_wqT, 256) + 256;
 }
 
 extern "C" int efqat_linear_bwd_weight_operand(const int8_t* w_codes, const float* s_w, int64_t T, int64_t c_in,
                                                int64_t c_out, int dy_dtype, int dy_layout, void* operand,
                                                size_t operand_bytes, void* stream) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
-    return EFQAT_ERR_BAD_SHAPE;
+  if (!linear_shape_ok(T, c_in, c_out)) return EFQAT_ERR_BAD_SHAPE;
   if (dy_dtype != EFQAT_F32 && dy_dtype != EFQAT_BF16) return EFQAT_ERR_BAD_DTYPE;
   if (dy_layout != EFQAT_DY_TOKEN_MAJOR && dy_layout != EFQAT_DY_CHANNEL_MAJOR) return EFQAT_ERR_BAD_LAYOUT;
   const size_t need = efqat_linear_bwd_weight_operand_bytes(T, c_in, c_out, dy_dtype, dy_layout);
@@ -738,61 +819,15 @@ extern "C" int efqat_linear_bwd_weight_operand(const int8_t* w_codes, const floa
   if (!w_codes || !s_w || !operand) return EFQAT_ERR_NULL_PTR;
   if (operand_bytes < need) return EFQAT_ERR_WORKSPACE;
   if (((uintptr_t)operand % 256) != 0) return EFQAT_ERR_ALIGNMENT;
-  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false);
+  if (c_in > 65535 * (int64_t)64) return EFQAT_ERR_BAD_SHAPE;
+  const BwdPlan p = make_plan(T, T, c_in, c_out, 1, 0, dy_dtype, dy_layout, false, EFQAT_DX_KERNEL_AUTO);
   TransposeExtra ex{};
   ex.z_in = c_in; ex.z_out = p.ldc;
   uint32_t* zero_page = (uint32_t*)((char*)operand + round_up((int64_t)p.b_wqT, 256));
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prep(PROF_PREP, st);
   return transpose_to_bf16<int8_t>(w_codes, c_in, c_out, c_in, nullptr, s_w, nullptr, (bf16_t*)operand, p.Kx, 0,
-                                   p.ldc, (hipStream_t)stream, zero_page, 1, &ex);
-}
-
-extern "C" int efqat_linear_bwd_prepared(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
-                                         int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip,
-                                         const void* x, int x_dtype, const float* s_x, const float* z_x,
-                                         const int8_t* w_codes, const uint32_t* w_clip, const float* w,
-                                         const float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
-                                         float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
-                                         const void* w_operand, void* ws, size_t ws_bytes, void* stream) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
-    return EFQAT_ERR_BAD_SHAPE;
-  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
-           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
-  int rc = check_common(io, c_out, ws);
-  if (rc) return rc;
-  if (w_operand && ((uintptr_t)w_operand % 256) != 0) return EFQAT_ERR_ALIGNMENT;
-  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
-  io.w_operand = w_operand;
-  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
-}
-
-static int fill_sgd(const efqat_sgd_step* step, float* w, float* s_w, SgdArgs* out) {
-  if (!step || !w || !s_w) return EFQAT_ERR_NULL_PTR;
-  if (step->momentum != 0.0f && (!step->mom_w || !step->mom_s)) return EFQAT_ERR_NULL_PTR;
-  if (((uintptr_t)step->mom_w % 4) != 0 || ((uintptr_t)step->mom_s % 4) != 0) return EFQAT_ERR_ALIGNMENT;
-  out->w = w; out->s_w = s_w;
-  out->mom_w = step->momentum != 0.0f ? step->mom_w : nullptr;
-  out->mom_s = step->momentum != 0.0f ? step->mom_s : nullptr;
-  out->lr_w = step->lr_w; out->lr_s = step->lr_s; out->mu = step->momentum; out->wd = step->weight_decay;
-  return EFQAT_OK;
-}
-
-extern "C" int efqat_linear_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t T, int64_t c_in,
-                                    int64_t c_out, const uint8_t* x_codes, const uint32_t* x_clip, const void* x,
-                                    int x_dtype, const float* s_x, const float* z_x, const int8_t* w_codes,
-                                    const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
-                                    void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
-                                    float* dz_x, const efqat_sgd_step* step, void* ws, size_t ws_bytes,
-                                    void* stream) {
-  if (T <= 0 || c_in <= 0 || c_out <= 0 || T > (1 << 30) || c_in > (1 << 30) || c_out > (1 << 30))
-    return EFQAT_ERR_BAD_SHAPE;
-  BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
-           dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
-  int rc = fill_sgd(step, w, s_w, &io.sgd);
-  if (rc) return rc;
-  rc = check_common(io, c_out, ws);
-  if (rc) return rc;
-  if (ws_bytes < efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, dy_dtype, dy_layout)) return EFQAT_ERR_WORKSPACE;
-  return run_bwd(io, T, T, c_in, c_out, nullptr, ws, (hipStream_t)stream);
+                                   p.ldc, st, zero_page, 1, &ex);
 }
 
 static int conv_geom(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out, int64_t KH, int64_t KW,
@@ -811,14 +846,46 @@ static int conv_geom(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_ou
   return EFQAT_OK;
 }
 
+static BwdPlan conv_plan(const ConvGeom& g, int64_t k, int dy_dtype, int dy_layout, int dxk, bool io_bf16) {
+  const bool im2col = !(g.KH * g.KW == 1 && g.stride == 1 && g.pad == 0);
+  return make_plan((int64_t)g.N * g.H * g.W, (int64_t)g.N * g.Ho * g.Wo, g.c_in, g.c_out, g.KH * g.KW, k, dy_dtype,
+                   dy_layout, im2col, dxk, &g, io_bf16);
+}
+
+extern "C" size_t efqat_conv_bwd_workspace_bytes_ex(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
+                                                    int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t k,
+                                                    int dy_dtype, int dy_layout, int dx_kernel) {
+  ConvGeom g;
+  if (conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g) || k < 0 || k > c_out) return 0;
+  if (dx_kernel < EFQAT_DX_KERNEL_AUTO || dx_kernel > EFQAT_DX_KERNEL_BF16_PINNED) return 0;
+  return conv_plan(g, k, dy_dtype, dy_layout, dx_kernel, false).total;
+}
+
 extern "C" size_t efqat_conv_bwd_workspace_bytes(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
                                                  int64_t KH, int64_t KW, int64_t stride, int64_t pad, int64_t k,
                                                  int dy_dtype, int dy_layout) {
+  return efqat_conv_bwd_workspace_bytes_ex(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout,
+                                           EFQAT_DX_KERNEL_AUTO);
+}
+
+static int conv_bwd_entry(BwdIo& io, int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out, int64_t KH,
+                          int64_t KW, int64_t stride, int64_t pad, const efqat_opt_step* step, float* w_rw,
+                          float* s_w_rw, int dxk, void* ws, size_t ws_bytes, void* stream) {
   ConvGeom g;
-  if (conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g) || k < 0 || k > c_out) return 0;
-  const bool im2col = !(g.KH * g.KW == 1 && g.stride == 1 && g.pad == 0);
-  return make_plan((int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, g.KH * g.KW, k, dy_dtype, dy_layout,
-                   im2col, &g).total;
+  int rc = conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g);
+  if (rc) return rc;
+  if (step) {
+    rc = fill_step(step, w_rw, s_w_rw, &io.sgd);
+    if (rc) return rc;
+  }
+  rc = check_common(io, c_out, ws, dxk);
+  if (rc) return rc;
+  const BwdPlan p = conv_plan(g, io.k, io.dy_dtype, io.dy_layout, dxk, io.x_dtype == EFQAT_BF16 && io.dx_dtype == EFQAT_BF16);
+  if (ws_bytes < p.total) return EFQAT_ERR_WORKSPACE;
+  const int64_t T_in = (int64_t)N * H * W, T_out = (int64_t)N * g.Ho * g.Wo;
+  rc = check_plan(p, io, T_out, c_in, c_out, true);
+  if (rc) return rc;
+  return run_bwd(io, p, T_in, T_out, c_in, c_out, &g, ws, (hipStream_t)stream);
 }
 
 extern "C" int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
@@ -828,35 +895,20 @@ extern "C" int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64
                               const float* w, const float* s_w, const int32_t* idx, int64_t k, void* dx,
                               int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x, void* ws,
                               size_t ws_bytes, void* stream) {
-  ConvGeom g;
-  int rc = conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g);
-  if (rc) return rc;
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
-  rc = check_common(io, c_out, ws);
-  if (rc) return rc;
-  if (ws_bytes < efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout))
-    return EFQAT_ERR_WORKSPACE;
-  return run_bwd(io, (int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, &g, ws, (hipStream_t)stream);
+  return conv_bwd_entry(io, N, H, W, c_in, c_out, KH, KW, stride, pad, nullptr, nullptr, nullptr,
+                        EFQAT_DX_KERNEL_AUTO, ws, ws_bytes, stream);
 }
 
-extern "C" int efqat_conv_bwd_sgd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
-                                  int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
-                                  const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
-                                  const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
-                                  float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
-                                  float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
-                                  const efqat_sgd_step* step, void* ws, size_t ws_bytes, void* stream) {
-  ConvGeom g;
-  int rc = conv_geom(N, H, W, c_in, c_out, KH, KW, stride, pad, &g);
-  if (rc) return rc;
+extern "C" int efqat_conv_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64_t H, int64_t W,
+                                 int64_t c_in, int64_t c_out, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                                 const uint8_t* x_codes, const uint32_t* x_clip, const void* x, int x_dtype,
+                                 const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
+                                 float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
+                                 float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
+                                 const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream) {
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
-  rc = fill_sgd(step, w, s_w, &io.sgd);
-  if (rc) return rc;
-  rc = check_common(io, c_out, ws);
-  if (rc) return rc;
-  if (ws_bytes < efqat_conv_bwd_workspace_bytes(N, H, W, c_in, c_out, KH, KW, stride, pad, k, dy_dtype, dy_layout))
-    return EFQAT_ERR_WORKSPACE;
-  return run_bwd(io, (int64_t)N * H * W, (int64_t)N * g.Ho * g.Wo, c_in, c_out, &g, ws, (hipStream_t)stream);
+  return conv_bwd_entry(io, N, H, W, c_in, c_out, KH, KW, stride, pad, step, w, s_w, dx_kernel, ws, ws_bytes, stream);
 }

@@ -170,9 +170,24 @@ int launch_gemm_dx8_cm(const bf16_t* dy_cm, int64_t lda, const int8_t* w_codes, 
 int launch_gemm_dw_rows(const bf16_t* dy_cm, int64_t lda, const int32_t* idx, const uint8_t* x_codes, int64_t ldb,
                         const void* zero_page, const float* z_x, int64_t M, int64_t N, int64_t K, const GemmPlan& plan,
                         float* out_partial, hipStream_t stream);
-// event timing hooks shared by the product kernels (which: 0 dX, 1 dW, 2 forward)
-bool gemm_prof_begin(int which, hipStream_t st, int* slot);
-void gemm_prof_end(int which, hipStream_t st, int slot);
+// Event timing of kernel classes (benchmarks only, off by default): a ProfScope brackets the launches made during its
+// lifetime with two HIP events on the stream they go to.  Classes = the `which` argument of efqat_profile_read.
+enum ProfClass {
+  PROF_DX = 0, PROF_DW = 1, PROF_FWD = 2, PROF_PREP = 3, PROF_FINISH = 4, PROF_QACT = 5, PROF_QW = 6,
+  PROF_IMPORTANCE = 7, PROF_TOPK = 8, PROF_BIAS = 9, PROF_CLASSES = 10
+};
+bool prof_begin(int which, hipStream_t st, int* slot);
+void prof_end(int which, hipStream_t st, int slot);
+struct ProfScope {
+  int which, slot;
+  hipStream_t st;
+  bool on;
+  ProfScope(int w, hipStream_t s) : which(w), slot(0), st(s), on(prof_begin(w, s, &slot)) {}
+  void close() { if (on) { prof_end(which, st, slot); on = false; } }
+  ~ProfScope() { close(); }
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+};
 
 // Forward product on int8 matrix cores: y[m][n] = S_x * S_w[n] * sum_k (x_codes[m][k] - round(Z_x)) * w_codes[n][k].
 // K, lda, ldb multiples of 16; wsum[n] = sum_k w_codes[n][k].

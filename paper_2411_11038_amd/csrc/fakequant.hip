@@ -331,6 +331,7 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
                          float* scale, float* zp, void* codes, uint32_t* clip, bf16_t* xq, void* ws,
                          hipStream_t st) {
   const int64_t n = rows * cols;
+  ProfScope prof(mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM ? PROF_QACT : PROF_QW, st);
   const int vec_flat = aligned_to(x, 16) ? 1 : 0;
   const int vec_row = (vec_flat && cols % 8 == 0 && aligned_to(codes, 8) && (!xq || aligned_to(xq, 16))) ? 1 : 0;
   if (init_minmax && mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM) {

@@ -454,45 +454,18 @@ bool gemm_epilogue_vec_ok(const GemmEpilogueDx& e, int64_t N) {
   return (N % 8) == 0 && ((uintptr_t)e.x_codes % 8) == 0 && ((uintptr_t)e.x % 16) == 0 && ((uintptr_t)e.dx % 16) == 0;
 }
 
-// ---- optional event timing of the contraction kernels (benchmarks only; off by default)
-static const int kMaxProf = 4096;
-static bool g_prof_on = false;
-static hipEvent_t g_prof_ev[3][kMaxProf][2];
-static int g_prof_made[3] = {0, 0, 0};
-static int g_prof_used[3] = {0, 0, 0};
-
-bool gemm_prof_begin(int which, hipStream_t st, int* slot) {
-  if (!g_prof_on || g_prof_used[which] >= kMaxProf) return false;
-  const int i = g_prof_used[which];
-  if (i >= g_prof_made[which]) {
-    if (hipEventCreate(&g_prof_ev[which][i][0]) != hipSuccess) return false;
-    if (hipEventCreate(&g_prof_ev[which][i][1]) != hipSuccess) return false;
-    g_prof_made[which] = i + 1;
-  }
-  if (hipEventRecord(g_prof_ev[which][i][0], st) != hipSuccess) return false;
-  *slot = i;
-  return true;
-}
-void gemm_prof_end(int which, hipStream_t st, int slot) {
-  if (hipEventRecord(g_prof_ev[which][slot][1], st) == hipSuccess) g_prof_used[which] = slot + 1;
-}
-
 template <int BM, int BN, int EPI, bool I8, bool CONV = false>
 static int launch_cfg(const GemmArgs& a, int split_k, hipStream_t st) {
   using C = TileCfg<BM, BN, 2>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, EPI, I8, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            C::LDS_BYTES) != hipSuccess)
-      return EFQAT_ERR_HIP;
-    attr_done = true;
-  }
+  // set once per process (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_nt<BM, BN, EPI, I8, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  if (attr != hipSuccess) return EFQAT_ERR_HIP;
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
-  int slot = 0;
-  constexpr int kProf = (EPI == EPI_DX || EPI == EPI_DXF) ? 0 : (EPI == EPI_RAW ? 1 : 2);   // dX, dW, forward
-  const bool timed = gemm_prof_begin(kProf, st, &slot);
-  hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) gemm_prof_end(kProf, st, slot);
+  constexpr int kProf = (EPI == EPI_DX || EPI == EPI_DXF) ? PROF_DX : (EPI == EPI_RAW ? PROF_DW : PROF_FWD);
+  {
+    ProfScope prof(kProf, st);
+    hipLaunchKernelGGL((k_gemm_nt<BM, BN, EPI, I8, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
+  }
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -587,26 +560,3 @@ int launch_gemm_fwd_i8(const uint8_t* x_codes, int64_t lda, const int8_t* w_code
 }
 
 }  // namespace efqat
-
-extern "C" int efqat_profile_enable(int on) {
-  efqat::g_prof_on = on != 0;
-  efqat::g_prof_used[0] = efqat::g_prof_used[1] = efqat::g_prof_used[2] = 0;
-  return EFQAT_OK;
-}
-
-extern "C" int efqat_profile_read(int which, double* total_ms, int64_t* launches) {
-  if (which < 0 || which > 2) return EFQAT_ERR_BAD_LAYOUT;
-  if (!total_ms || !launches) return EFQAT_ERR_NULL_PTR;
-  double sum = 0.0;
-  const int n = efqat::g_prof_used[which];
-  for (int i = 0; i < n; ++i) {
-    float ms = 0.0f;
-    if (hipEventSynchronize(efqat::g_prof_ev[which][i][1]) != hipSuccess) return EFQAT_ERR_HIP;
-    if (hipEventElapsedTime(&ms, efqat::g_prof_ev[which][i][0], efqat::g_prof_ev[which][i][1]) != hipSuccess)
-      return EFQAT_ERR_HIP;
-    sum += (double)ms;
-  }
-  *total_ms = sum;
-  *launches = n;
-  return EFQAT_OK;
-}

@@ -204,8 +204,9 @@ __device__ __forceinline__ void epilogue_dx(const GemmArgs& g, floatx16_t (&acc)
 // of pass p of the next slab are requested as soon as pass p of this slab has consumed its own (one register set, a
 // whole slab of prefetch distance).  With a single resident block per CU the predicated, branching formulation
 // above runs at about half this speed.
-// Per lane: s1 = sum a (code - Z), s3 = sum o x, sd = sum (a - o) with o = in range ? a : 0; then
-// sum a gs = s1 - s3 / S (the reduction epilogue_dx forms term by term).
+// Per lane: s1 = sum a gs with gs = in range ? (code - Z) - x / S : code - Z, formed term by term as in epilogue_dx
+// (in range |gs| <= 1/2, whereas sum a (code - Z) and sum a x / S taken apart would each be some hundred times larger
+// and cancel); sd = sum (a - o) with o = in range ? a : 0.
 template <class C>
 struct EpiDxFast {
   static constexpr int PITCH = C::WN + 8;            // floats; 4*PITCH = 32 (mod 64) banks
@@ -259,7 +260,7 @@ struct EpiDxFast {
     };
     const uint32_t msh = col_b & 31u;                 // a pass moves by a multiple of 32 columns
     static_assert((8 * LPR) % 32 == 0, "mask bit offset is the same in every pass");
-    float s1 = 0.0f, s3 = 0.0f, sd = 0.0f;
+    float s1 = 0.0f, sd = 0.0f;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i) {
       if (i > 0) lds_barrier();
@@ -284,9 +285,10 @@ struct EpiDxFast {
           const float xv = (t & 1) ? __uint_as_float(xw[t >> 1] & 0xFFFF0000u) : __uint_as_float(xw[t >> 1] << 16);
           const uint32_t byte = ((t < 4 ? q8.cw.x : q8.cw.y) >> (8 * (t & 3))) & 0xFFu;
           const bool inr = (q8.mb >> (msh + t)) & 1u;
-          s1 = fmaf(a[t], (float)byte - z, s1);
+          const float q = (float)byte - z;
+          const float gs = inr ? fmaf(xv, ninv_s, q) : q;   // term by term: |gs| <= 1/2 in range, no cancellation later
+          s1 = fmaf(a[t], gs, s1);
           o[t] = inr ? a[t] : 0.0f;
-          s3 = fmaf(o[t], xv, s3);
           sd += a[t] - o[t];
         }
         *reinterpret_cast<uint4*>(dxp + elem(i, p)) =
@@ -295,7 +297,7 @@ struct EpiDxFast {
         __builtin_amdgcn_sched_barrier(0);            // keeps the passes from piling up in registers
       }
     }
-    const float ps = wave_sum(fmaf(s3, ninv_s, s1));
+    const float ps = wave_sum(s1);
     const float pz = wave_sum(sd);
     lds_barrier();                                   // staging area is dead: reuse for the block sum
     float* red = reinterpret_cast<float*>(smem);

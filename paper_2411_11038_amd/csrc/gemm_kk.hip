@@ -301,19 +301,14 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 template <int T, int WGM, int WGN, int EPI>
 static int launch_kk_cfg(const GemmKkArgs& a, int split_k, hipStream_t st) {
   using C = KkCfg<T, WGM, WGN>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_kk<T, WGM, WGN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            C::LDS_BYTES) != hipSuccess)
-      return EFQAT_ERR_HIP;
-    attr_done = true;
-  }
+  // set once per process (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_kk<T, WGM, WGN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  if (attr != hipSuccess) return EFQAT_ERR_HIP;
   dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
-  int slot = 0;
-  constexpr int kProf = EPI == EPI_RAW ? 1 : 0;
-  const bool timed = gemm_prof_begin(kProf, st, &slot);
-  hipLaunchKernelGGL((k_gemm_kk<T, WGM, WGN, EPI>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) gemm_prof_end(kProf, st, slot);
+  {
+    ProfScope prof(EPI == EPI_RAW ? PROF_DW : PROF_DX, st);
+    hipLaunchKernelGGL((k_gemm_kk<T, WGM, WGN, EPI>), grid, dim3(256), C::LDS_BYTES, st, a);
+  }
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }

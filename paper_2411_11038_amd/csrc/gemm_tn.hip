@@ -771,18 +771,14 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
 template <int T, bool CONV = false>
 static int launch_tn_cfg(const GemmTnArgs& a, int split_k, hipStream_t st) {
   using C = TnCfg<T>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_tn<T, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) !=
-        hipSuccess)
-      return EFQAT_ERR_HIP;
-    attr_done = true;
-  }
+  // set once per process (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_tn<T, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  if (attr != hipSuccess) return EFQAT_ERR_HIP;
   dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)split_k);
-  int slot = 0;
-  const bool timed = gemm_prof_begin(1, st, &slot);
-  hipLaunchKernelGGL((k_gemm_tn<T, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) gemm_prof_end(1, st, slot);
+  {
+    ProfScope prof(PROF_DW, st);
+    hipLaunchKernelGGL((k_gemm_tn<T, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
+  }
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }
@@ -812,18 +808,14 @@ int launch_gemm_tn(const bf16_t* A, int64_t lda, int64_t a_cols, const uint8_t* 
 template <int T, bool DW = false, bool ATN = false, bool FAST = false>
 static int launch_dx8_cfg(const GemmDx8Args& a, int split_k, hipStream_t st) {
   using C = Dx8Cfg<T, ATN>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute((const void*)k_gemm_dx8<T, DW, ATN, FAST>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            C::LDS_BYTES) != hipSuccess)
-      return EFQAT_ERR_HIP;
-    attr_done = true;
-  }
+  // set once per process (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_dx8<T, DW, ATN, FAST>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  if (attr != hipSuccess) return EFQAT_ERR_HIP;
   dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
-  int slot = 0;
-  const bool timed = gemm_prof_begin(DW ? 1 : 0, st, &slot);
-  hipLaunchKernelGGL((k_gemm_dx8<T, DW, ATN, FAST>), grid, dim3(256), C::LDS_BYTES, st, a);
-  if (timed) gemm_prof_end(DW ? 1 : 0, st, slot);
+  {
+    ProfScope prof(DW ? PROF_DW : PROF_DX, st);
+    hipLaunchKernelGGL((k_gemm_dx8<T, DW, ATN, FAST>), grid, dim3(256), C::LDS_BYTES, st, a);
+  }
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }

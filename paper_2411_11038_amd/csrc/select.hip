@@ -336,11 +336,66 @@ extern "C" int efqat_channel_select(const float* w, int64_t c_out, int64_t block
   double* sc = (double*)carve.take((size_t)c_out * sizeof(double));
   double* sc_out = scores ? scores : sc;
   const int vec = (((uintptr_t)w % 16) == 0 && block % 4 == 0) ? 1 : 0;
-  hipLaunchKernelGGL(k_row_importance, dim3((unsigned)ceil_div(c_out, 4)), dim3(256), 0, st, w, c_out, block, vec,
-                     sc_out);
+  {
+    ProfScope prof(PROF_IMPORTANCE, st);
+    hipLaunchKernelGGL(k_row_importance, dim3((unsigned)ceil_div(c_out, 4)), dim3(256), 0, st, w, c_out, block, vec,
+                       sc_out);
+  }
   EFQAT_LAUNCH_CHECK();
   if (k == 0) return EFQAT_OK;
-  launch_topk(sc_out, c_out, k, idx, st);
+  {
+    ProfScope prof(PROF_TOPK, st);
+    launch_topk(sc_out, c_out, k, idx, st);
+  }
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// efqat_channel_select for callers that cannot allocate device memory: the per-channel scores, which the plain entry
+// point keeps in the caller's workspace, live in a file-scope device array of the library instead.
+namespace efqat {
+
+constexpr int64_t kStaticSelectMaxChannels = EFQAT_STATIC_SELECT_MAX_CHANNELS;
+static __device__ __align__(256) double scratch[kStaticSelectMaxChannels];   // 512 KiB per GPU, for the process' life
+
+// Host code must not pass `scratch` itself to a kernel: here that name is only a handle for the symbol.  The
+// array's device address differs per GPU (each holds its own copy) and is looked up once per device, with that
+// device current.
+constexpr int kMaxDevices = 64;
+static double* g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(double** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return EFQAT_ERR_HIP;
+  if (!g_scratch_ptr[dev]) {
+    double* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return EFQAT_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return EFQAT_OK;
+}
+
+}  // namespace efqat
+
+extern "C" int efqat_channel_select_static(const float* w, int64_t c_out, int64_t block, int64_t k, int32_t* idx,
+                                           void* stream) {
+  if (c_out <= 0 || block <= 0 || c_out > INT64_MAX / block) return EFQAT_ERR_BAD_SHAPE;
+  if (c_out > kStaticSelectMaxChannels) return EFQAT_ERR_WORKSPACE;   // more channels than the built-in scratch holds
+  if (k < 0 || k > c_out) return EFQAT_ERR_BAD_K;
+  if (!w || (k > 0 && !idx)) return EFQAT_ERR_NULL_PTR;
+  if (((uintptr_t)w % 4) != 0 || ((uintptr_t)idx % 4) != 0) return EFQAT_ERR_ALIGNMENT;
+  double* sc = nullptr;
+  const int rc = static_scratch(&sc);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const int vec = (((uintptr_t)w % 16) == 0 && block % 4 == 0) ? 1 : 0;
+  // every score that Top-K reads is written by this launch first: nothing in the scratch has to start at zero
+  hipLaunchKernelGGL(k_row_importance, dim3((unsigned)ceil_div(c_out, 4)), dim3(256), 0, st, w, c_out, block, vec, sc);
+  EFQAT_LAUNCH_CHECK();
+  if (k == 0) return EFQAT_OK;
+  launch_topk(sc, c_out, k, idx, st);
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
 }

@@ -4,6 +4,17 @@ import numpy as np
 import torch
 
 
+def report(line):
+    """Measured error figures: printed (pytest shows them with -s / -rP) and, when EFQAT_ERR_REPORT names a file,
+    appended there with the id of the running test."""
+    import os
+    print(line)
+    path = os.environ.get("EFQAT_ERR_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write("%s :: %s\n" % (os.environ.get("PYTEST_CURRENT_TEST", "?"), line))
+
+
 def dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a))
     if dtype is not None:

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_strerror_k_from_ratio():
     _ensure_built()
     L = ef.lib()
-    assert L.efqat_version() == 100
+    assert L.efqat_version() == 200
     assert L.efqat_strerror(0) == b"ok"
     for code in range(-9, 0):
         assert L.efqat_strerror(code) not in (b"", b"unknown error code")
@@ -69,10 +69,13 @@ def test_argument_validation_needs_no_device():
     assert L.efqat_layer_select(fake, fake, 0, 0, None, fake, fake, fake, 1 << 20, None) == -2
     assert L.efqat_layer_select(fake, fake, 4, 2, None, None, fake, fake, 1 << 20, None) == -1
     assert L.efqat_layer_select(fake, fake, 4, 2, None, fake, fake, fake, 8, None) == -6
-    # options
-    assert L.efqat_set_option(1, 2) == 0 and L.efqat_set_option(1, 0) == 0
-    assert L.efqat_set_option(1, 3) == 0 and L.efqat_set_option(1, 0) == 0
-    assert L.efqat_set_option(1, 4) == -5 and L.efqat_set_option(1, -1) == -5 and L.efqat_set_option(9, 0) == -5
+    # select with the built-in scratch: argument errors come before anything touches a device
+    assert L.efqat_channel_select_static(fake, 8, 4, 9, fake, None) == -4
+    assert L.efqat_channel_select_static(fake, 0, 4, 0, fake, None) == -2
+    assert L.efqat_channel_select_static(None, 8, 4, 2, fake, None) == -1
+    assert L.efqat_channel_select_static(fake, 8, 4, 2, None, None) == -1
+    assert L.efqat_channel_select_static(fake, 65537, 4, 2, fake, None) == -6      # beyond the built-in scratch
+    assert L.efqat_channel_select_static(fake + 2, 8, 4, 2, fake, None) == -9
     # bias gradient
     assert L.efqat_bias_grad(None, 1, 0, 8, 8, fake, fake, 1 << 20, None) == -1
     assert L.efqat_bias_grad(fake, 1, 0, 0, 8, fake, fake, 1 << 20, None) == -2
@@ -107,22 +110,34 @@ def test_argument_validation_needs_no_device():
     assert wop(opb=need - 1) == -6
     assert wop(op=fake + 64) == -9
     assert wop(dyd=5) == -8 and wop(lay=3) == -5
-    def lin_pre(wop_=fake, ws=fake, wsb=1 << 30, dy=fake):
-        return L.efqat_linear_bwd_prepared(dy, 1, 0, 8, 8, 8, fake, fake, fake, 1, fake, fake, fake, fake, fake,
-                                           fake, fake, 2, fake, 1, fake, 0, fake, fake, fake, wop_, ws, wsb, None)
-    assert lin_pre(dy=None) == -1
-    assert lin_pre(wop_=fake + 64) == -9
-    assert lin_pre(wsb=64) == -6 and lin_pre(wop_=None, wsb=64) == -6
+    def lin_ex(wop_=None, step=None, dxk=0, ws=fake, wsb=1 << 30, dy=fake, w=fake, dw=fake, c_in=8, xc=fake, wc=fake,
+               lay=0, k=2):
+        return L.efqat_linear_bwd_ex(dy, 1, lay, 8, c_in, 8, xc, fake, fake, 1, fake, fake, wc, fake, w, fake, fake, k,
+                                     fake, 1, dw, 0, fake, fake, fake, wop_, step, dxk, ws, wsb, None)
+    assert lin_ex(dy=None) == -1
+    assert lin_ex(wop_=fake + 64) == -9
+    assert lin_ex(wsb=64) == -6 and lin_ex(wop_=fake, wsb=64) == -6
+    assert lin_ex(dxk=4) == -5 and lin_ex(dxk=-1) == -5
+    assert lin_ex(wop_=fake, dxk=2) == -5              # the prepared operand belongs to the default kernel choice
+    # operands that the chosen kernels copy 16 bytes at a time: found misaligned before anything is launched
+    assert lin_ex(c_in=16, xc=fake + 8) == -9          # token-major dW product reads the codes as they lie
+    assert lin_ex(c_in=16, dxk=2, wc=fake + 8) == -9   # dX product on the int8 weight codes
+    assert lin_ex(c_in=16, lay=1, xc=fake + 8) == -9 and lin_ex(c_in=16, lay=1, wc=fake + 8, k=0) == -9
+    assert L.efqat_linear_bwd_workspace_bytes_ex(8, 16, 8, 2, 1, 0, 7) == 0
+    assert (L.efqat_linear_bwd_workspace_bytes_ex(1024, 512, 640, 64, 1, 0, 2)
+            != L.efqat_linear_bwd_workspace_bytes_ex(1024, 512, 640, 64, 1, 0, 1))   # no bf16 W_q^T copy with INT8
 
     # fused optimizer step
-    from paper_2411_11038_amd.binding import SgdStep
-    def lin_sgd(step, w=fake, dw=fake):
-        return L.efqat_linear_bwd_sgd(fake, 1, 0, 8, 8, 8, fake, fake, fake, 1, fake, fake, fake, fake, w, fake,
-                                      fake, 2, fake, 1, dw, 0, fake, fake, fake, step, fake, 64, None)
-    assert lin_sgd(None) == -1
-    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.9, 0.0, None, None))) == -1       # momentum without buffers
-    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.0, 0.0, None, None)), w=None) == -1
-    assert lin_sgd(C.byref(SgdStep(0.1, 0.1, 0.0, 0.0, None, None)), dw=None) == -6   # valid up to the workspace check
+    from paper_2411_11038_amd.binding import OptStep
+    def st(momentum=0.0, mom_w=None, b1=0.9, b2=0.999, eps=1e-8, m=fake, v=fake, t=fake):
+        return C.byref(OptStep(0.1, momentum, 0.0, mom_w, 0.01, b1, b2, eps, m, v, t))
+    assert lin_ex(step=st(momentum=0.9)) == -1         # momentum without a buffer
+    assert lin_ex(step=st(m=None)) == -1 and lin_ex(step=st(v=None)) == -1 and lin_ex(step=st(t=None)) == -1
+    assert lin_ex(step=st(), w=None) == -1
+    assert lin_ex(step=st(b1=1.0)) == -5 and lin_ex(step=st(b2=-0.1)) == -5 and lin_ex(step=st(eps=-1.0)) == -5
+    assert lin_ex(step=st(t=fake + 2)) == -9
+    assert lin_ex(step=st(), dw=None, wsb=64) == -6    # gradients are optional with the step: valid up to the workspace check
+    assert lin_ex(dw=None) == -1                       # ... and required without it
 
     # conv backward
     def conv(N=1, H=4, W=4, c_in=8, c_out=8, KH=3, KW=3, stride=1, pad=1, k=2, wsb=1 << 30):
@@ -132,6 +147,10 @@ def test_argument_validation_needs_no_device():
     assert conv(stride=0) == -2 and conv(pad=-1) == -2 and conv(H=1, pad=0) == -2
     assert conv(k=9) == -4
     assert conv(wsb=64) == -6
+    def conv_ex(step=None, dxk=0, wsb=1 << 30):
+        return L.efqat_conv_bwd_ex(fake, 1, 0, 1, 4, 4, 8, 8, 3, 3, 1, 1, fake, fake, fake, 1, fake, fake, fake, fake,
+                                   fake, fake, fake, 2, fake, 1, fake, 0, fake, fake, fake, step, dxk, fake, wsb, None)
+    assert conv_ex(dxk=9) == -5 and conv_ex(wsb=64) == -6 and conv_ex(step=st(m=None)) == -1
 
 
 def test_workspace_queries_are_host_only_and_monotone():

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
 element on the same seeded inputs.  Integer results (codes, clip masks, indices) must be
 bit-exact; bf16-MFMA gradients within max|err| <= 2e-2 * max|ref|; fp32 reductions within
-1e-5 relative."""
+1e-5 relative; the quantizer-parameter gradients within the bounds derived in bwd_checks.py."""
 import numpy as np
 import pytest
 import torch
@@ -10,13 +10,10 @@ import paper_2411_11038_amd as ef
 from oracle import efqat_oracle as orc
 from workloads import synth
 
+from bwd_checks import GEMM_TOL, check_backward
 from gpu_util import (act_tensor, assert_max_err, assert_rms_err, clip_words, dev, host, pack_mask)
 
 pytestmark = pytest.mark.gpu
-
-GEMM_TOL = 2e-2      # bf16 operands, fp32 accumulation (stated bound)
-GEMM_RMS = 5e-3      # derived: one bf16 rounding (2^-9 relative) per W_q / fp32-dY element
-EXACT_TOL = 2e-4     # bf16 dY and integer codes are exact in bf16: only fp32 accumulation error
 
 
 # ---------------------------------------------------------------- fake-quant forward
@@ -239,7 +236,8 @@ def test_bias_grad_matches_oracle(T, c_out, kind, layout):
 
 
 # ---------------------------------------------------------------- linear backward
-def _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter, dx_dtype=None):
+def _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter, dx_dtype=None,
+                dx_kernel=ef.DX_KERNEL_AUTO):
     T, c_in = X.shape; c_out = W.shape[0]
     xd, wd = act_tensor(X, kind), dev(W)
     fx = ef.fakequant_fwd(xd, ef.ACT_PER_TENSOR_ASYM, a_bits, init_minmax=True)
@@ -258,62 +256,10 @@ def _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatte
     dy_host = dY if layout == ef.DY_TOKEN_MAJOR else np.ascontiguousarray(dY.T)
     out = ef.linear_bwd(act_tensor(dy_host, kind), fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"],
                         fw["codes"], fw["clip_bits"], wd, fw["scale"], idx if k else None, dy_layout=layout,
-                        scatter=scatter, dx_dtype=dx_dtype)
+                        scatter=scatter, dx_dtype=dx_dtype, dx_kernel=dx_kernel)
     torch.cuda.synchronize()
     ref = orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx_ref)
     return out, ref, idx, idx_ref, fx, fw, (sx, zx, sw)
-
-
-def _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, dx_is_bf16, shape_w):
-    sx, zx, sw = qp
-    k = len(idx_ref)
-    assert idx.cpu().numpy().tolist() == idx_ref.tolist()
-    # ---- dX: masked entries are exactly zero, the rest within the bf16-MFMA bound
-    dx = host(out["dx"]).reshape(ref["dX"].shape)
-    assert not dx[~ref["x_mask"]].any()
-    assert_max_err(dx, ref["dX"], GEMM_TOL, "dX")
-    assert_rms_err(dx, ref["dX"], GEMM_RMS + (4e-3 if dx_is_bf16 else 0.0), "dX rms")
-    # ---- dS_x, dZ_x: sums of dXq * g; tolerance relative to the l2 size of the summands
-    z = np.rint(float(zx)); q = ref["x_codes"] - z
-    g = np.where(ref["x_mask"], q - X.astype(np.float64) / float(sx), q)
-    l2 = np.sqrt(np.sum((ref["dXq"] * g) ** 2))
-    assert abs(out["ds_x"].item() - ref["dS_x"]) <= GEMM_TOL * l2 + 1e-30, (out["ds_x"].item(), ref["dS_x"], l2)
-    l2z = float(sx) * np.sqrt(np.sum((ref["dXq"][~ref["x_mask"]]) ** 2))
-    assert abs(out["dz_x"].item() - ref["dZ_x"]) <= GEMM_TOL * l2z + 1e-30, (out["dz_x"].item(), ref["dZ_x"])
-    if ref["x_mask"].all():
-        assert out["dz_x"].item() == 0.0
-    if k == 0:
-        return
-    # ---- dW rows idx (+ frozen rows untouched in scatter mode)
-    tol = EXACT_TOL if kind == "bf16" else GEMM_TOL
-    dw = host(out["dw"]).astype(np.float64)
-    dsw = host(out["ds_w"]).astype(np.float64)
-    dw_ref = ref["dW"].reshape(ref["dW"].shape[0], -1)
-    if scatter:
-        dw = dw.reshape(dw_ref.shape)
-        frozen = np.setdiff1d(np.arange(dw_ref.shape[0]), idx_ref)
-        assert not dw[frozen].any() and not dsw[frozen].any()
-        dw = dw[idx_ref]; dsw = dsw[idx_ref]
-    else:
-        dw = dw.reshape(k, -1)
-    wm = ref["w_mask"].reshape(dw_ref.shape)[idx_ref]
-    assert not dw[~wm].any()
-    assert_max_err(dw, dw_ref[idx_ref], tol, "dW")
-    # dS_w per row: tolerance relative to the l2 size of that row's summands
-    wc = ref["w_codes"].reshape(dw_ref.shape)[idx_ref].astype(np.float64)
-    W2 = W.reshape(dw_ref.shape)[idx_ref].astype(np.float64)
-    gw = np.where(wm, wc - W2 / sw[idx_ref, None].astype(np.float64), wc)
-    # error scale: the larger of the l2 size of the row's actual summands dW_q * g (un-masked dW_q from the oracle) and
-    # of the summands with every |dW_q| replaced by the row's largest gradient entry (the scale used so far; it is
-    # zero when the whole row is clipped, the other is small when the large entries of g meet small entries of dW_q);
-    # plus the fp32 rounding of g = code - w / S_w itself (|w / S_w| < 2^9: 2^-15 absolute per element)
-    dwq = np.asarray(ref["dWq_sel"], dtype=np.float64).reshape(k, -1)
-    l2_sum = np.sqrt(np.sum((dwq * gw) ** 2, axis=1))
-    l2_max = np.sqrt(np.sum((np.abs(dw_ref[idx_ref]).max(axis=1, keepdims=True) * gw) ** 2, axis=1))
-    row_l2 = np.maximum(l2_sum, l2_max)
-    floor = 2.0 ** -15 * np.sum(np.abs(dwq), axis=1)
-    err = np.abs(dsw - ref["dS_w"][idx_ref])
-    assert np.all(err <= tol * row_l2 + floor + 1e-30), (err.max(), row_l2.min())
 
 
 LIN_CASES = [
@@ -365,7 +311,7 @@ def test_linear_bwd_matches_oracle(case):
     assert np.array_equal(fw["codes"].cpu().numpy().astype(np.int64), ref["w_codes"])
     assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"]))
     assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"]))
-    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+    check_backward(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
 
 
 # (T, c_in, c_out, layout): the pinned 192-tile kernel, the 128-tile kernel with ragged edges, a padded C_out,
@@ -432,11 +378,11 @@ def test_linear_bwd_random_shapes_match_oracle(seed):
     assert np.array_equal(fw["codes"].cpu().numpy().astype(np.int64), ref["w_codes"])
     assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"]))
     assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"]))
-    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+    check_backward(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
 
 
 # dX product with the weight operand read from the int8 codes (bf16 token-major dY, C_out % 8 == 0, C_in % 16 == 0):
-# forced through the option hook so that both tile sizes meet ragged edges in every dimension
+# forced through the dx_kernel argument so that both tile sizes meet ragged edges in every dimension
 DX8_CASES = [
     # T, c_in, c_out, a_bits, w_bits, shrink, (num, den), scatter
     (300, 208, 136, 8, 4, 0.7, (1, 4), False),      # 128 tile; K tail 136 % 64 = 8, N tail, M tail
@@ -457,21 +403,17 @@ DX8_CASES = [
 def test_linear_bwd_int8_weight_operand(case):
     T, c_in, c_out, a_bits, w_bits, shrink, (num, den), scatter = case
     X, W, dY = synth.linear_layer(3000 + T + c_in, T, c_in, c_out, act_dtype="bf16")
-    try:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_INT8)
-        out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter)
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16)
-        out2, *_ = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter)
-    finally:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
-    _check_bwd(out, ref, idx, idx_ref, X, W, qp, "bf16", scatter, True, W.shape)
+    out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter,
+                                                     dx_kernel=ef.DX_KERNEL_INT8)
+    out2, *_ = _run_linear(X, W, dY, "bf16", a_bits, w_bits, shrink, num, den, 0, scatter, dx_kernel=ef.DX_KERNEL_BF16)
+    check_backward(out, ref, idx, idx_ref, X, W, qp, "bf16", scatter, True, W.shape)
     # both kernels round S_w * code to bf16 once and accumulate in fp32; only the fp32 summation order differs, so
     # the bf16 outputs agree to an ulp or two of the largest element
     assert_max_err(host(out["dx"]), host(out2["dx"]), 8e-3, "dX int8-operand vs bf16-operand kernel")
 
 
 # dX product by the 192 x 192 kernel with the pinned instruction order and the three-stage LDS ring, forced through
-# the option hook (the planner takes it only for large products): ragged edges in every dimension, K from a single
+# the dx_kernel argument (the planner takes it only for large products): ragged edges in every dimension, K from a single
 # 8-wide chunk to many stages, so that the pipelined loop, its drain and the zero-page tail all run
 PINNED_CASES = [
     # T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter
@@ -495,15 +437,11 @@ PINNED_CASES = [
 def test_linear_bwd_pinned_dx_kernel(case):
     T, c_in, c_out, kind, a_bits, w_bits, shrink, (num, den), layout, scatter = case
     X, W, dY = synth.linear_layer(7000 + T + c_out, T, c_in, c_out, act_dtype=kind)
-    try:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16_PINNED)
-        out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout,
-                                                         scatter)
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16)
-        out2, *_ = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter)
-    finally:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
-    _check_bwd(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
+    out, ref, idx, idx_ref, fx, fw, qp = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter,
+                                                     dx_kernel=ef.DX_KERNEL_BF16_PINNED)
+    out2, *_ = _run_linear(X, W, dY, kind, a_bits, w_bits, shrink, num, den, layout, scatter,
+                           dx_kernel=ef.DX_KERNEL_BF16)
+    check_backward(out, ref, idx, idx_ref, X, W, qp, kind, scatter, kind == "bf16", W.shape)
     # same operands, same bf16 rounding, fp32 accumulation in the same K order: only the epilogue's output rounding
     # can differ, and not even that - the two kernels must agree exactly
     assert np.array_equal(host(out["dx"]), host(out2["dx"]))
@@ -517,12 +455,54 @@ def _close_fp32_update(got, want, old, name):
     assert not bad.any(), (name, int(bad.sum()), float(np.abs(got - want).max()))
 
 
+def _adam_state(c_out, seed, fresh):
+    """Adam state of the weight scales: zeros before the first step, or moments and per-channel step counts as they
+    would be after some earlier steps (channels unfrozen at different times have different counts)."""
+    if fresh:
+        return np.zeros(c_out, np.float32), np.zeros(c_out, np.float32), np.zeros(c_out, np.int32)
+    m = synth.normal(seed, 7, (c_out,), std=0.05).astype(np.float32)
+    v = (synth.normal(seed, 8, (c_out,), std=0.05) ** 2).astype(np.float32)
+    t = (np.arange(c_out) * 7 % 23).astype(np.int32)
+    return m, v, t
+
+
+def _check_fused_step(W, S0, ii, plain, w2, s2, mom_w0, mw, adam0, adam_dev, hp):
+    """Weights: SGD rule of the oracle on rows idx.  Scales: Adam rule of the oracle.  Everything else untouched."""
+    c_out = W.shape[0]
+    Wn, mwn = orc.sgd_step_rows(W, ii, host(plain["dw"]).reshape(len(ii), *W.shape[1:]), hp["lr_w"], hp["momentum"],
+                                hp["weight_decay"], mom_w0 if hp["momentum"] else None)
+    m0, v0, t0 = adam0
+    Sn, mn, vn, tn = orc.adam_step_rows(S0, ii, host(plain["ds_w"]), float(np.float32(hp["lr_s"])), m0, v0, t0,
+                                        float(np.float32(hp["beta1"])), float(np.float32(hp["beta2"])),
+                                        float(np.float32(hp["eps"])))
+    _close_fp32_update(host(w2).reshape(W.shape), Wn, W, "w")
+    frozen = np.setdiff1d(np.arange(c_out), ii)
+    assert np.array_equal(host(w2).reshape(W.shape)[frozen], W[frozen].astype(np.float64))
+    if hp["momentum"]:
+        _close_fp32_update(host(mw).reshape(W.shape), mwn, mom_w0, "mom_w")
+        assert np.array_equal(host(mw).reshape(W.shape)[frozen], mom_w0[frozen].astype(np.float64))
+    # Adam on the scales: the kernel forms the update in double precision from the fp32 inputs, so what is left is
+    # the fp32 rounding of the stored moments and of the new scale (half an ulp each) and the accuracy of pow / sqrt
+    md, vd, td = (host(t_) for t_ in adam_dev)
+    # (relative to the operands of the final subtraction, old scale and step: the two may nearly cancel)
+    errs = dict(s_w=np.max(np.abs(host(s2) - Sn) / (np.abs(S0) + np.abs(Sn - S0))),
+                adam_m=np.max(np.abs(md[ii] - mn[ii]) / np.maximum(np.abs(mn[ii]), 1e-30)),
+                adam_v=np.max(np.abs(vd[ii] - vn[ii]) / np.maximum(np.abs(vn[ii]), 1e-30)))
+    print("fused step, relative errors (ulp of fp32 = 6e-8):", {k_: float("%.2e" % v_) for k_, v_ in errs.items()})
+    assert errs["s_w"] <= 6.1e-8 and errs["adam_m"] <= 6.1e-8 and errs["adam_v"] <= 6.1e-8, errs
+    assert np.array_equal(td, tn)
+    assert np.array_equal(host(s2)[frozen], S0[frozen].astype(np.float64))
+    assert np.array_equal(md[frozen], m0[frozen].astype(np.float64))
+    assert np.array_equal(vd[frozen], v0[frozen].astype(np.float64))
+    assert np.array_equal(td[frozen], t0[frozen])
+
+
 # (453, 140, 232): a weight whose update nearly cancels it (found by a soak over random shapes)
-@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4), (0.0, 5e-4)])
+@pytest.mark.parametrize("momentum,wd,fresh", [(0.0, 0.0, True), (0.9, 5e-4, False), (0.0, 5e-4, False)])
 @pytest.mark.parametrize("shape", [(300, 208, 136), (260, 70, 43), (453, 140, 232)])
-def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
-    # the fused optimizer step must equal the plain call followed by the SGD rule on the rows idx, and leave
-    # everything else untouched
+def test_linear_bwd_fused_optimizer_step(shape, momentum, wd, fresh):
+    # the fused optimizer step must equal the plain call followed by the oracle's rules on the rows idx (SGD on the
+    # weight rows, Adam on their scales: Sec. 4 "Setup"), and leave everything else untouched
     T, c_in, c_out = shape
     X, W, dY = synth.linear_layer(5100 + T, T, c_in, c_out, act_dtype="bf16")
     xd, wd_t, dyd = act_tensor(X, "bf16"), dev(W), act_tensor(dY, "bf16")
@@ -533,48 +513,34 @@ def test_linear_bwd_fused_sgd_step(shape, momentum, wd):
     args = (dyd, fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"], fw["codes"], fw["clip_bits"])
     plain = ef.linear_bwd(*args, wd_t, fw["scale"], idx)
     torch.cuda.synchronize()
+    S0 = fw["scale"].cpu().numpy()
     mom_w0 = synth.normal(77, 5, (c_out, c_in), std=0.01).astype(np.float32)
-    mom_s0 = synth.normal(77, 6, (c_out,), std=0.01).astype(np.float32)
+    adam0 = _adam_state(c_out, 79, fresh)
     w2, s2 = wd_t.clone(), fw["scale"].clone()
-    mw, ms = dev(mom_w0), dev(mom_s0)
-    step = dict(lr_w=0.05, lr_s=0.01, momentum=momentum, weight_decay=wd, mom_w=mw if momentum else None,
-                mom_s=ms if momentum else None)
-    fused = ef.linear_bwd(*args, w2, s2, idx, sgd=step)
+    mw = dev(mom_w0)
+    adam_dev = tuple(dev(a_) for a_ in adam0)
+    hp = dict(lr_w=0.05, momentum=momentum, weight_decay=wd, lr_s=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    step = dict(hp, mom_w=mw if momentum else None, adam_m=adam_dev[0], adam_v=adam_dev[1], adam_t=adam_dev[2])
+    fused = ef.linear_bwd(*args, w2, s2, idx, step=step)
     torch.cuda.synchronize()
     for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
         assert torch.equal(plain[key], fused[key]), key
     ii = idx.cpu().numpy().astype(np.int64)
-    Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
-                                         momentum, wd, mom_w0 if momentum else None, mom_s0 if momentum else None)
-    close = _close_fp32_update
-    close(host(w2), Wn, W, "w")
-    close(host(s2), Sn, host(fw["scale"]), "s_w")
-    frozen = np.setdiff1d(np.arange(c_out), ii)
-    assert np.array_equal(host(w2)[frozen], W[frozen].astype(np.float64))
-    assert np.array_equal(host(s2)[frozen], host(fw["scale"])[frozen])
-    if momentum:
-        close(host(mw), mwn, mom_w0, "mom_w")
-        close(host(ms), msn, mom_s0, "mom_s")
-        assert np.array_equal(host(mw)[frozen], mom_w0[frozen].astype(np.float64))
+    _check_fused_step(W, S0, ii, plain, w2, s2, mom_w0, mw, adam0, adam_dev, hp)
     # gradients are optional outputs of the fused call
     w3, s3 = wd_t.clone(), fw["scale"].clone()
-    L = ef.lib()
-    ws = torch.empty(L.efqat_linear_bwd_workspace_bytes(T, c_in, c_out, k, 1, 0), dtype=torch.uint8, device="cuda")
-    from paper_2411_11038_amd.binding import SgdStep
-    st = SgdStep(0.05, 0.01, 0.0, wd, None, None)
-    import ctypes
-    rc = L.efqat_linear_bwd_sgd(dyd.data_ptr(), 1, 0, T, c_in, c_out, fx["codes"].data_ptr(), fx["clip_bits"].data_ptr(),
-                                xd.data_ptr(), 1, fx["scale"].data_ptr(), fx["zero_point"].data_ptr(),
-                                fw["codes"].data_ptr(), fw["clip_bits"].data_ptr(), w3.data_ptr(), s3.data_ptr(),
-                                idx.data_ptr(), k, fused["dx"].data_ptr(), 1, None, 0, None, fused["ds_x"].data_ptr(),
-                                fused["dz_x"].data_ptr(), ctypes.byref(st), ws.data_ptr(), ws.numel(), None)
+    adam3 = tuple(dev(a_) for a_ in adam0)
+    mw3 = dev(mom_w0)
+    out3 = dict(dx=fused["dx"], dw=None, ds_w=None, ds_x=fused["ds_x"], dz_x=fused["dz_x"])
+    ef.linear_bwd(*args, w3, s3, idx, out=out3,
+                  step=dict(hp, mom_w=mw3 if momentum else None, adam_m=adam3[0], adam_v=adam3[1], adam_t=adam3[2]))
     torch.cuda.synchronize()
-    assert rc == 0
-    if not momentum:
-        assert torch.equal(w3, w2) and torch.equal(s3, s2)
+    assert torch.equal(w3, w2) and torch.equal(s3, s2)
+    for a_, b_ in zip(adam3, adam_dev):
+        assert torch.equal(a_, b_)
 
 
-def test_conv_bwd_fused_sgd_step():
+def test_conv_bwd_fused_optimizer_step():
     N, H, Wd, c_in, c_out, kh, kw = 2, 7, 6, 16, 24, 3, 3
     X, W, dY = synth.conv_layer(5200, N, H, Wd, c_in, c_out, kh, kw, 1, 1, act_dtype="bf16")
     xd, wd_t, dyd = act_tensor(X, "bf16"), dev(W), act_tensor(dY, "bf16")
@@ -585,22 +551,21 @@ def test_conv_bwd_fused_sgd_step():
     xc, wc = fx["codes"].view(X.shape), fw["codes"].view(W.shape)
     args = (dyd, xc, fx["clip_bits"], xd, fx["scale"], fx["zero_point"], wc, fw["clip_bits"])
     plain = ef.conv_bwd(*args, wd_t, fw["scale"], idx, stride=1, pad=1)
+    torch.cuda.synchronize()
+    S0 = fw["scale"].cpu().numpy()
     w2, s2 = wd_t.clone(), fw["scale"].clone()
     mom_w0 = synth.normal(78, 5, W.shape, std=0.01).astype(np.float32)
-    mom_s0 = synth.normal(78, 6, (c_out,), std=0.01).astype(np.float32)
-    mw, ms = dev(mom_w0), dev(mom_s0)
+    adam0 = _adam_state(c_out, 80, False)
+    mw = dev(mom_w0)
+    adam_dev = tuple(dev(a_) for a_ in adam0)
+    hp = dict(lr_w=0.05, momentum=0.9, weight_decay=1e-3, lr_s=1e-6, beta1=0.8, beta2=0.95, eps=1e-6)
     fused = ef.conv_bwd(*args, w2, s2, idx, stride=1, pad=1,
-                        sgd=dict(lr_w=0.05, lr_s=0.01, momentum=0.9, weight_decay=1e-3, mom_w=mw, mom_s=ms))
+                        step=dict(hp, mom_w=mw, adam_m=adam_dev[0], adam_v=adam_dev[1], adam_t=adam_dev[2]))
     torch.cuda.synchronize()
     for key in ("dx", "dw", "ds_w", "ds_x", "dz_x"):
         assert torch.equal(plain[key], fused[key]), key
     ii = idx.cpu().numpy().astype(np.int64)
-    Wn, Sn, mwn, msn = orc.sgd_step_rows(W, host(fw["scale"]), ii, host(plain["dw"]), host(plain["ds_w"]), 0.05, 0.01,
-                                         0.9, 1e-3, mom_w0, mom_s0)
-    _close_fp32_update(host(w2), Wn, W, "w")
-    _close_fp32_update(host(s2), Sn, host(fw["scale"]), "s_w")
-    _close_fp32_update(host(mw), mwn, mom_w0, "mom_w")
-    _close_fp32_update(host(ms), msn, mom_s0, "mom_s")
+    _check_fused_step(W, S0, ii, plain, w2, s2, mom_w0, mw, adam0, adam_dev, hp)
 
 
 def test_linear_bwd_dx_independent_of_fraction_and_fp32_dx():
@@ -658,18 +623,14 @@ def test_conv_bwd_matches_oracle(case):
     _conv_case(case)
 
 
-# strided convolutions stage an im2col matrix of dY; with the option set, that matrix is the A operand of the
-# 192 x 192 pinned-order kernel
+# strided convolutions stage an im2col matrix of dY; with dx_kernel = BF16_PINNED that matrix is the A operand of
+# the 192 x 192 pinned-order kernel
 @pytest.mark.parametrize("case", [CONV_CASES[2], CONV_CASES[4], CONV_CASES[5], CONV_CASES[14]],
                          ids=lambda c: "N%d_%dx%d_%d-%d_k%dx%d_s%dp%d_%s_L%d" % (
                              c[0], c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8], c[9], c[13]))
 def test_conv_bwd_pinned_dx_kernel_on_im2col_matrix(case):
     assert case[7] == 2
-    try:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_BF16_PINNED)
-        _conv_case(case)
-    finally:
-        ef.set_option(ef.OPT_DX_KERNEL, ef.DX_KERNEL_AUTO)
+    _conv_case(case, dx_kernel=ef.DX_KERNEL_BF16_PINNED)
 
 
 def _random_conv_case(seed):
@@ -692,7 +653,7 @@ def test_conv_bwd_random_shapes_match_oracle(seed):
     _conv_case(_random_conv_case(seed))
 
 
-def _conv_case(case):
+def _conv_case(case, dx_kernel=ef.DX_KERNEL_AUTO):
     N, H, Wd, c_in, c_out, kh, kw, stride, pad, kind, w_bits, shrink, (num, den), layout, scatter = case
     X, W, dY = synth.conv_layer(4000 + H + c_in, N, H, Wd, c_in, c_out, kh, kw, stride, pad, act_dtype=kind)
     xd, wd = act_tensor(X, kind), dev(W)
@@ -708,13 +669,13 @@ def _conv_case(case):
     dy_host = dY if layout == 0 else np.ascontiguousarray(np.moveaxis(dY, -1, 0))
     out = ef.conv_bwd(act_tensor(dy_host, kind), fx["codes"], fx["clip_bits"], xd, fx["scale"], fx["zero_point"],
                       fw["codes"], fw["clip_bits"], wd, fw["scale"], idx if k else None, stride=stride, pad=pad,
-                      dy_layout=layout, scatter=scatter)
+                      dy_layout=layout, scatter=scatter, dx_kernel=dx_kernel)
     torch.cuda.synchronize()
     ref = orc.conv_bwd(dY, X, sx, zx, 8, W, sw, w_bits, idx_ref, stride, pad)
     assert np.array_equal(fx["codes"].cpu().numpy().astype(np.int64), ref["x_codes"])
     assert np.array_equal(clip_words(fx["clip_bits"]), pack_mask(ref["x_mask"].reshape(-1, c_in)))
     assert np.array_equal(clip_words(fw["clip_bits"]), pack_mask(ref["w_mask"].reshape(c_out, -1)))
-    _check_bwd(out, ref, idx, idx_ref, X, W, (sx, zx, sw), kind, scatter, kind == "bf16", W.shape)
+    check_backward(out, ref, idx, idx_ref, X, W, (sx, zx, sw), kind, scatter, kind == "bf16", W.shape)
 
 
 # ---------------------------------------------------------------- low-precision forward (int8 matrix cores)

@@ -11,6 +11,9 @@ with the initialisation scales a trained network of that family has.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 _M64 = np.uint64(0xFFFFFFFFFFFFFFFF)
@@ -36,16 +39,31 @@ def uniform01(seed: int, stream: int, n: int, offset: int = 0) -> np.ndarray:
     return ((bits >> np.uint64(11)).astype(np.float64) + 0.5) * (1.0 / 9007199254740992.0)
 
 
+def _normal_chunk(seed: int, stream: int, lo: int, m: int) -> np.ndarray:
+    u1 = uniform01(seed, 2 * stream, m, lo)
+    u2 = uniform01(seed, 2 * stream + 1, m, lo)
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+
+
 def normal(seed: int, stream: int, shape, std: float = 1.0, mean: float = 0.0) -> np.ndarray:
-    """fp64 N(mean, std^2) samples by Box-Muller on the counter-based uniforms."""
+    """fp64 N(mean, std^2) samples by Box-Muller on the counter-based uniforms.  Sample i depends only on
+    (seed, stream, i), so large arrays are filled chunk by chunk on a few host threads with identical results."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float64)
     chunk = 1 << 22
-    for lo in range(0, n, chunk):
+    los = list(range(0, n, chunk))
+
+    def fill(lo):
         m = min(chunk, n - lo)
-        u1 = uniform01(seed, 2 * stream, m, lo)
-        u2 = uniform01(seed, 2 * stream + 1, m, lo)
-        out[lo:lo + m] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        out[lo:lo + m] = _normal_chunk(seed, stream, lo, m)
+
+    workers = min(len(los), 16, len(os.sched_getaffinity(0)))
+    if workers > 1:
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(fill, los))
+    else:
+        for lo in los:
+            fill(lo)
     return (out * std + mean).reshape(shape)
 
 
