@@ -139,6 +139,13 @@ class Layer:
         fw2 = dict(self.fw, codes=self.fw["codes"].view(self.c_out, -1))
         ef.fakequant_fwd(w2, ef.W_PER_ROW_SYM, self.w_bits, True, ws=self.ws_w, out=fw2)
 
+    def quant_w_select(self, ef, k):
+        """The weight side of a step in one call (one read of the master weights): codes, mask, scales, scores, idx."""
+        idx = self.idx_full[:k]
+        ef.weight_quant_select(self.w, self.w_bits, k, ws=self.ws_w,
+                               out=dict(self.fw, scores=self.scores, idx=idx))
+        return idx
+
     def prepare_w(self, ef):
         if self.w_op is not None:
             ef.linear_bwd_weight_operand(self.fw["codes"].view(self.c_out, -1), self.fw["scale"], self.T,
@@ -216,7 +223,7 @@ CLASSES = [("dx", 0), ("dw", 1), ("prep", 3), ("finish", 4), ("quant_act", 5), (
 def make_step(torch, ef, layers, ks, streams):
     """One step over `layers` with ks[i] selected channels each: quantize X and W, select, restricted backward.
 
-    The weight-side calls of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
+    The weight-side call of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
     do not depend on its activations, so with streams == 2 they are issued on a second stream of the same (default)
     priority and joined before the layer's backward, together with the bf16 weight operand of the dX product
     (efqat_linear_bwd_weight_operand, handed to efqat_linear_bwd_ex); ev_bwd keeps the next step from rewriting a
@@ -230,14 +237,13 @@ def make_step(torch, ef, layers, ks, streams):
     def step():
         for i, (l, k) in enumerate(zip(layers, ks)):
             if side_stream is None:
-                l.forward_quant(ef)
-                idx = l.select(ef, k)
+                l.quant_x(ef)
+                idx = l.quant_w_select(ef, k)
             else:
                 side_stream.wait_event(ev_bwd[i])
                 with torch.cuda.stream(side_stream):
-                    l.quant_w(ef)
+                    idx = l.quant_w_select(ef, k)
                     l.prepare_w(ef)                      # the bf16 W_q^T operand of the dX product, where one is used
-                    idx = l.select(ef, k)
                     ev_w[i].record(side_stream)
                 l.quant_x(ef)
                 main_stream.wait_event(ev_w[i])
@@ -365,7 +371,7 @@ def compact_block(torch, ef, synth, workload, w_bits, layout, num, den, steps, w
     for _ in range(warmup):
         step()
     sec = time_region(torch, step, steps)
-    prof = profiled(torch, ef, step, max(3, steps // 2))
+    prof = profiled(torch, ef, make_step(torch, ef, layers, ks, 1), max(3, steps // 2))   # one stream: see main()
     flops = sum(l.flops(k) for l, k in zip(layers, ks))
     dx_fl = sum(l.work(k)["dx"][0] for l, k in zip(layers, ks))
     blk = dict(workload=describe(workload, layers, num, den, w_bits, cfg["a_bits"], layout), k=ks,
@@ -394,8 +400,9 @@ def measured_traffic(workload, layout):
     return None
 
 
-def cpu_baseline(layers, num, den, a_bits, w_bits):
-    """The oracle, as it stands, on the host cores: whole steps (every layer, all tokens) of the headline workload."""
+def cpu_baseline(host_data, num, den, a_bits, w_bits):
+    """The oracle, as it stands, on the host cores: whole steps (every layer, all tokens) of the headline workload.
+    host_data: (name, c_out, conv geometry or None, (X, W, dY), flops(k)) per layer."""
     from oracle import efqat_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -407,23 +414,21 @@ def cpu_baseline(layers, num, den, a_bits, w_bits):
     fl = 0.0
     reps = 0
     while reps < 12 and (reps == 0 or time.perf_counter() - t0 < 10.0):
-        for lay in layers:
-            X, W, dY = lay.host
+        for name, c_out, conv, (X, W, dY), flops in host_data:
             sx, zx = orc.act_qparams_minmax(X, a_bits)
             sw = orc.weight_scale_minmax(W, w_bits)
-            k = orc.k_from_ratio(lay.c_out, num, den)
+            k = orc.k_from_ratio(c_out, num, den)
             idx = orc.top_k_channels(orc.channel_importance(W), k)
-            if lay.conv is None:
+            if conv is None:
                 orc.linear_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx)
             else:
-                orc.conv_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx, stride=lay.conv["stride"],
-                             pad=lay.conv["pad"])
-            fl += lay.flops(k)
+                orc.conv_bwd(dY, X, sx, zx, a_bits, W, sw, w_bits, idx, stride=conv["stride"], pad=conv["pad"])
+            fl += flops(k)
         reps += 1
     dt = time.perf_counter() - t0
     return dict(value=fl / dt / 1e12, unit="TFLOP/s", cores=int(threads), kind="oracle",
                 sample="%d whole step(s) of the same workload (%s; all tokens; r=%d/%d; quantize, select, backward), "
-                       "fp64 NumPy, %.1f s" % (reps, ", ".join(l.name for l in layers), num, den, dt))
+                       "fp64 NumPy, %.1f s" % (reps, ", ".join(h[0] for h in host_data), num, den, dt))
 
 
 def main():
@@ -461,8 +466,10 @@ def main():
     # the timed region: exactly --steps steps, nothing but the library's launches on the stream
     sec = time_region(torch, step, args.steps)
     # a second pass of the same steps with HIP events recorded by the library around every kernel class (on the stream
-    # the kernels run on) gives the kernel durations of the roofline block
-    prof = profiled(torch, ef, step, args.steps)
+    # the kernels run on) gives the kernel durations of the roofline block.  This pass issues the step on ONE stream:
+    # with the weight side on a second stream its small kernels queue behind the products that fill the chip, and the
+    # time between their events would be that wait, not their own duration.
+    prof = profiled(torch, ef, make_step(torch, ef, layers, ks, 1), args.steps)
     flops = sum(l.flops(k) for l, k in zip(layers, ks))
     value = flops / sec / 1e12
 
@@ -554,17 +561,18 @@ def main():
         roofline["extras"] = extras
         del dbs, bws
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(layers, num, den, cfg["a_bits"], w_bits)
     workload_name = describe(args.workload, layers, num, den, w_bits, cfg["a_bits"], args.dy_layout)
+    # for the CPU baseline, run last (nothing here may keep a layer's device buffers alive)
+    host_data = [(l.name, l.c_out, l.conv, l.host,
+                  (lambda T, ci, taps, co: (lambda k: 2.0 * T * ci * taps * (co + k)))(l.T, l.c_in, l.taps, l.c_out))
+                 for l in layers]
     del layers, step
     torch.cuda.empty_cache()
 
     # the other configurations and the other dY layout, compact
     if not args.no_attach and not args.no_sweep:
         blocks = []
-        st, wu = max(5, args.steps // 2), max(2, args.warmup // 2)
+        st, wu = max(5, args.steps // 2), max(5, args.warmup)
         plan = [(args.workload, w_bits, 1 - args.dy_layout)]
         for wl in ("cfg2", "cfg3", "cfg4"):
             if wl == args.workload:
@@ -597,8 +605,10 @@ def main():
         for _ in range(5):
             b.copy_(a)                                  # reads 256 MiB, writes 256 MiB per launch
         torch.cuda.synchronize()
-    if cpu is not None:
-        out["cpu_baseline"] = cpu
+    # the oracle on the host cores comes last: the GPU idles meanwhile, and GPU timings taken right after such a pause
+    # would see its clocks ramp up again
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host_data, num, den, cfg["a_bits"], w_bits)
     print(json.dumps(out))
 
 

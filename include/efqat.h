@@ -128,6 +128,19 @@ int efqat_channel_select(const float* w, int64_t c_out, int64_t block, int64_t k
 int efqat_channel_select_static(const float* w, int64_t c_out, int64_t block, int64_t k, int32_t* idx,
                                 void* stream);
 
+/* Weight side of one training step in a single call: efqat_fakequant_fwd(mode W_PER_ROW_SYM, fp32
+ * weights) followed by efqat_channel_select on the same weights, with identical results (Eq. 3 / Eq. 4
+ * codes, clip masks and scales; Eq. 6 scores; Top-K).  With init_minmax != 0 and rows of at most 16384
+ * weights (a multiple of 32, 16-byte aligned) the master weights are read once: the kernel that holds a
+ * row in registers for its scale and codes also sums its magnitudes.
+ *   w        in   float [c_out][block]
+ *   scale    in/out float[c_out];  codes out int8 [c_out][block];  clip_bits out uint32 [c_out][ceil(block/32)]
+ *   k        0..c_out;  scores out, nullable double[c_out];  idx out int32[k] ascending */
+size_t efqat_weight_quant_select_workspace_bytes(int64_t c_out);
+int efqat_weight_quant_select(const float* w, int64_t c_out, int64_t block, int bits, int init_minmax,
+                              float* scale, int8_t* codes, uint32_t* clip_bits, int64_t k, double* scores,
+                              int32_t* idx, void* ws, size_t ws_bytes, void* stream);
+
 /* EfQAT-CWPN (Table 2): one Top-K over the channels of several layers together.
  *   scores      in   double[total] = the per-layer score arrays of efqat_channel_select,
  *                    concatenated in layer order (device)

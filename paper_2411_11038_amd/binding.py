@@ -15,6 +15,7 @@ EXPORTS = [
     "efqat_version", "efqat_strerror", "efqat_k_from_ratio",
     "efqat_fakequant_fwd_workspace_bytes", "efqat_fakequant_fwd",
     "efqat_channel_select_workspace_bytes", "efqat_channel_select", "efqat_channel_select_static",
+    "efqat_weight_quant_select_workspace_bytes", "efqat_weight_quant_select",
     "efqat_network_select_workspace_bytes", "efqat_network_select",
     "efqat_layer_select_workspace_bytes", "efqat_layer_select",
     "efqat_bias_grad_workspace_bytes", "efqat_bias_grad",
@@ -71,6 +72,10 @@ def lib():
     L.efqat_channel_select.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
     L.efqat_channel_select_static.restype = ci
     L.efqat_channel_select_static.argtypes = [vp, i64, i64, i64, vp, vp]
+    L.efqat_weight_quant_select_workspace_bytes.restype = sz
+    L.efqat_weight_quant_select_workspace_bytes.argtypes = [i64]
+    L.efqat_weight_quant_select.restype = ci
+    L.efqat_weight_quant_select.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, i64, vp, vp, vp, sz, vp]
     L.efqat_network_select_workspace_bytes.restype = sz
     L.efqat_network_select_workspace_bytes.argtypes = [i64]
     L.efqat_network_select.restype = ci
@@ -221,6 +226,38 @@ def channel_select(w: torch.Tensor, k: int, want_scores: bool = True, ws=None, o
                                 ws.numel(), _stream())
     _check(rc, "efqat_channel_select")
     return idx, scores
+
+
+def weight_quant_select(w: torch.Tensor, bits: int, k: int, init_minmax: bool = True, scale=None, ws=None, out=None):
+    """efqat_weight_quant_select: fake-quant of the fp32 weights w [c_out, ...] and channel selection in one call.
+    Returns dict(codes, clip_bits, scale, scores, idx).  `out` may carry preallocated tensors (same keys)."""
+    L = lib()
+    c_out = w.shape[0]
+    block = w[0].numel()
+    dev = w.device
+    out = out or {}
+    if scale is None:
+        scale = out.get("scale")
+    if scale is None:
+        scale = torch.empty(c_out, dtype=torch.float32, device=dev)
+    codes = out.get("codes")
+    if codes is None:
+        codes = torch.empty(w.shape, dtype=torch.int8, device=dev)
+    clip = out.get("clip_bits")
+    if clip is None:
+        clip = torch.empty((c_out, (block + 31) // 32), dtype=torch.int32, device=dev)
+    scores = out.get("scores")
+    if scores is None:
+        scores = torch.empty(c_out, dtype=torch.float64, device=dev)
+    idx = out.get("idx")
+    if idx is None:
+        idx = torch.empty(max(k, 0), dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _ws(L.efqat_weight_quant_select_workspace_bytes(c_out), w)
+    rc = L.efqat_weight_quant_select(_p(w), c_out, block, bits, int(bool(init_minmax)), _p(scale), _p(codes), _p(clip),
+                                     k, _p(scores), _p(idx) if k > 0 else None, _p(ws), ws.numel(), _stream())
+    _check(rc, "efqat_weight_quant_select")
+    return dict(codes=codes, clip_bits=clip, scale=scale, scores=scores, idx=idx)
 
 
 def channel_select_static(w: torch.Tensor, k: int, out=None):

@@ -189,6 +189,12 @@ struct ProfScope {
   ProfScope& operator=(const ProfScope&) = delete;
 };
 
+// Eq. 6 scores of every row of w [c_out][block] (double precision), and the Top-K launch, shared by the select and
+// the combined weight-side entry points
+int launch_row_importance(const float* w, int64_t c_out, int64_t block, double* scores, hipStream_t st);
+void launch_topk(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st);
+int launch_topk_profiled(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st);
+
 // Forward product on int8 matrix cores: y[m][n] = S_x * S_w[n] * sum_k (x_codes[m][k] - round(Z_x)) * w_codes[n][k].
 // K, lda, ldb multiples of 16; wsum[n] = sum_k w_codes[n][k].
 int launch_gemm_fwd_i8(const uint8_t* x_codes, int64_t lda, const int8_t* w_codes, int64_t ldb, int64_t M, int64_t N,

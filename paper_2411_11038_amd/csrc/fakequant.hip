@@ -37,13 +37,25 @@ __global__ __launch_bounds__(256) void k_minmax_partial(const T* __restrict__ x,
   const int64_t nthreads = (int64_t)gridDim.x * blockDim.x;
   if (vec) {
     const int64_t n8 = n >> 3;
-    for (int64_t i = tid; i < n8; i += nthreads) {
+    int64_t i = tid;
+    // four 16-byte (bf16) / 32-byte (fp32) loads in flight per lane: with one, a CU has too few bytes outstanding to
+    // cover the memory latency at the HBM rate
+    for (; i + 3 * nthreads < n8; i += 4 * nthreads) {
+      float v[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) load8<T>(x + (i + u * nthreads) * 8, v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { lo = fminf(lo, v[u][j]); hi = fmaxf(hi, v[u][j]); }
+    }
+    for (; i < n8; i += nthreads) {
       float v[8];
       load8<T>(x + i * 8, v);
 #pragma unroll
       for (int j = 0; j < 8; ++j) { lo = fminf(lo, v[j]); hi = fmaxf(hi, v[j]); }
     }
-    for (int64_t i = (n8 << 3) + tid; i < n; i += nthreads) {
+    for (i = (n8 << 3) + tid; i < n; i += nthreads) {
       float v = load_as_f32<T>(x, i);
       lo = fminf(lo, v); hi = fmaxf(hi, v);
     }
@@ -266,7 +278,8 @@ __global__ __launch_bounds__(256) void k_quantize_act_flat(const T* __restrict__
 template <int NIT, int WPR>
 __global__ __launch_bounds__(256) void k_quantize_w_row_init(const float* __restrict__ w, int64_t rows, int64_t cols,
                                                              int bits, float* __restrict__ scale,
-                                                             int8_t* __restrict__ codes, uint32_t* __restrict__ clip) {
+                                                             int8_t* __restrict__ codes, uint32_t* __restrict__ clip,
+                                                             double* __restrict__ scores) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = WPR == 4 ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
   const int part = WPR == 4 ? wave : 0;               // which quarter of the row's chunks (interleaved by 64)
@@ -289,12 +302,27 @@ __global__ __launch_bounds__(256) void k_quantize_w_row_init(const float* __rest
     }
   }
   m = wave_max(m);
+  // optional by-product (Eq. 6): the row's mean |w| in double precision, fixed summation order, from the registers
+  double asum = 0.0;
+  if (scores) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if ((it * WPR + part) * 64 + lane < n8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asum += (double)fabsf(v[it][j]);
+      }
+    }
+    asum = wave_sum(asum);
+  }
   if (WPR == 4) {
     __shared__ float s_m[4];
-    if (lane == 0) s_m[wave] = m;
+    __shared__ double s_a[4];
+    if (lane == 0) { s_m[wave] = m; s_a[wave] = asum; }
     __syncthreads();
     m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    asum = (s_a[0] + s_a[1]) + (s_a[2] + s_a[3]);
   }
+  if (scores && on && lane == 0 && part == 0) scores[row] = asum / (double)cols;
   float s = __fdiv_rn(m, hi);
   if (!(s > 0.0f)) s = 1.0f;                          // all-zero row
   if (on && lane == 0 && part == 0) scale[row] = s;
@@ -326,10 +354,12 @@ __global__ __launch_bounds__(256) void k_quantize_w_row_init(const float* __rest
 // ----------------------------------------------------------------------------------------------
 static inline bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// scores (weights with min/max initialisation only): where the row-in-registers kernel runs, it also writes the
+// Eq. 6 importance of every row and *scores_done is set; otherwise the caller computes them in a pass of its own.
 template <typename T>
 static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int bits, int init_minmax,
                          float* scale, float* zp, void* codes, uint32_t* clip, bf16_t* xq, void* ws,
-                         hipStream_t st) {
+                         hipStream_t st, double* scores = nullptr, bool* scores_done = nullptr) {
   const int64_t n = rows * cols;
   ProfScope prof(mode == EFQAT_QUANT_ACT_PER_TENSOR_ASYM ? PROF_QACT : PROF_QW, st);
   const int vec_flat = aligned_to(x, 16) ? 1 : 0;
@@ -365,7 +395,8 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
     const int per_wave = (int)ceil_div(cols, 8 * 64 * (wide ? 4 : 1));     // 8-element chunks per lane
     const dim3 grid((unsigned)(wide ? rows : ceil_div(rows, 4)));
 #define EFQAT_ROW_INIT(NIT, WPR) \
-  hipLaunchKernelGGL((k_quantize_w_row_init<NIT, WPR>), grid, dim3(256), 0, st, wf, rows, cols, bits, scale, cd, clip)
+  hipLaunchKernelGGL((k_quantize_w_row_init<NIT, WPR>), grid, dim3(256), 0, st, wf, rows, cols, bits, scale, cd, clip, \
+                     scores)
     if (wide) {
       if (per_wave <= 1) EFQAT_ROW_INIT(1, 4); else if (per_wave <= 2) EFQAT_ROW_INIT(2, 4);
       else if (per_wave <= 4) EFQAT_ROW_INIT(4, 4); else if (per_wave <= 6) EFQAT_ROW_INIT(6, 4); else EFQAT_ROW_INIT(8, 4);
@@ -373,6 +404,7 @@ static int run_fakequant(const T* x, int64_t rows, int64_t cols, int mode, int b
       if (per_wave <= 2) EFQAT_ROW_INIT(2, 1); else if (per_wave <= 4) EFQAT_ROW_INIT(4, 1); else EFQAT_ROW_INIT(8, 1);
     }
 #undef EFQAT_ROW_INIT
+    if (scores && scores_done) *scores_done = true;
   } else if (init_minmax)
     hipLaunchKernelGGL((k_quantize<T, EFQAT_QUANT_W_PER_ROW_SYM, true>), dim3((unsigned)blocks), dim3(256), 0, st, x,
                        rows, cols, vec_row, bits, scale, zp, (uint8_t*)codes, clip, xq);
@@ -415,4 +447,34 @@ extern "C" int efqat_fakequant_fwd(const void* x, int dtype, int64_t rows, int64
                                 clip_bits, (bf16_t*)xq, ws, st);
   return run_fakequant<bf16_t>((const bf16_t*)x, rows, cols, mode, bits, init_minmax, scale, zero_point, codes,
                                clip_bits, (bf16_t*)xq, ws, st);
+}
+
+// Weight side of one step in a single call: Eq. 4 + Eq. 3 (codes, clip mask, scales), Eq. 6 and the Top-K.
+extern "C" size_t efqat_weight_quant_select_workspace_bytes(int64_t c_out) {
+  return efqat_channel_select_workspace_bytes(c_out);
+}
+
+extern "C" int efqat_weight_quant_select(const float* w, int64_t c_out, int64_t block, int bits, int init_minmax,
+                                         float* scale, int8_t* codes, uint32_t* clip_bits, int64_t k, double* scores,
+                                         int32_t* idx, void* ws, size_t ws_bytes, void* stream) {
+  if (c_out <= 0 || block <= 0 || c_out > INT32_MAX || c_out > INT64_MAX / block) return EFQAT_ERR_BAD_SHAPE;
+  if (bits < 2 || bits > 8) return EFQAT_ERR_BAD_BITS;
+  if (k < 0 || k > c_out) return EFQAT_ERR_BAD_K;
+  if (!w || !scale || !codes || !clip_bits || !ws || (k > 0 && !idx)) return EFQAT_ERR_NULL_PTR;
+  if (ws_bytes < efqat_weight_quant_select_workspace_bytes(c_out)) return EFQAT_ERR_WORKSPACE;
+  if (((uintptr_t)ws % 256) != 0 || ((uintptr_t)w % 4) != 0 || ((uintptr_t)clip_bits % 4) != 0 ||
+      ((uintptr_t)scale % 4) != 0 || ((uintptr_t)idx % 4) != 0 || ((uintptr_t)scores % 8) != 0)
+    return EFQAT_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  double* sc = scores ? scores : (double*)ws;
+  bool scores_done = false;
+  int rc = run_fakequant<float>(w, c_out, block, EFQAT_QUANT_W_PER_ROW_SYM, bits, init_minmax, scale, nullptr, codes,
+                                clip_bits, nullptr, nullptr, st, init_minmax ? sc : nullptr, &scores_done);
+  if (rc) return rc;
+  if (!scores_done) {                                  // rows too long for the register kernel, or given scales
+    rc = launch_row_importance(w, c_out, block, sc, st);
+    if (rc) return rc;
+  }
+  if (k == 0) return EFQAT_OK;
+  return launch_topk_profiled(sc, c_out, k, idx, st);
 }

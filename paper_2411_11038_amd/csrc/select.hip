@@ -31,9 +31,12 @@ __global__ __launch_bounds__(256) void k_row_importance(const float* __restrict_
 // to T that still belong to the selection (as soon as at most 64 candidates remain they are ranked directly); then one ordered sweep writes every index whose score is > T, plus the first `need` indices
 // (ascending) whose score equals T: ties go to the lower index, output is ascending.  Integer counting only,
 // so the result does not depend on thread scheduling.
+// Where the keys live between the passes: up to KPT per thread in registers (n <= KPT * NTH); else, with in_lds, in a
+// dynamic LDS array of n keys (8 n bytes); else they are re-read from memory in every pass.
 template <int NTH, int KPT>
 __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ scores, int64_t n, int64_t k,
-                                                     int32_t* __restrict__ idx) {
+                                                     int32_t* __restrict__ idx, int in_lds) {
+  extern __shared__ __attribute__((aligned(16))) unsigned long long lkeys[];
   constexpr int NW = NTH / 64;                        // wavefronts
   __shared__ unsigned int hist[NW][256];              // one histogram per wavefront: less atomic contention
   __shared__ unsigned int total[256];
@@ -50,8 +53,11 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
   constexpr int EPL = (KPT * NW + 63) / 64;           // scan entries per lane of the ordered output
   unsigned long long keys[KPT];
   const bool cached = n <= (int64_t)KPT * NTH;
-  // Leading bits on which all keys agree need no pass: find them from the OR and AND of all keys.
-  unsigned long long vor = 0ull, vand = ~0ull;
+  // Keys are taken relative to the smallest one (order and equality are unchanged): the scores of a layer lie in a
+  // narrow band, and without the offset a band that straddles a power of two would put its highest differing bit
+  // in the exponent, so that the first digit window would split the keys into two or three crowded bins.  With it
+  // the first window starts at the top bit of (max - min) and spreads the keys over all 256 bins.
+  unsigned long long vmin = ~0ull;
   if (cached) {
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
@@ -59,25 +65,50 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
       keys[q] = 0ull;
       if (i < n) {
         keys[q] = (unsigned long long)__double_as_longlong(scores[i]);
-        vor |= keys[q]; vand &= keys[q];
+        vmin = keys[q] < vmin ? keys[q] : vmin;
       }
     }
   } else {
     for (int64_t i = tid; i < n; i += NTH) {
       const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
-      vor |= key; vand &= key;
+      if (in_lds) lkeys[i] = key;                      // each thread re-reads only what it wrote until the next barrier
+      vmin = key < vmin ? key : vmin;
     }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
-    vor |= __shfl_xor(vor, o, kWave);
-    vand &= __shfl_xor(vand, o, kWave);
+    const unsigned long long t = __shfl_xor(vmin, o, kWave);
+    vmin = t < vmin ? t : vmin;
   }
-  if (lane == 0) { s_or[wv] = vor; s_and[wv] = vand; }
+  if (lane == 0) s_and[wv] = vmin;
   __syncthreads();
-  vor = 0ull; vand = ~0ull;
-  for (int i = 0; i < NW; ++i) { vor |= s_or[i]; vand &= s_and[i]; }
-  const unsigned long long diff = vor ^ vand;          // bits that differ between some two keys
+  vmin = ~0ull;
+  for (int i = 0; i < NW; ++i) vmin = s_and[i] < vmin ? s_and[i] : vmin;
+  const unsigned long long kmin = vmin;
+  // Leading bits on which all (offset) keys agree need no pass: they are the zero bits above the top bit of the OR.
+  unsigned long long vor = 0ull;
+  if (cached) {
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      const int64_t i = (int64_t)q * NTH + tid;
+      if (i < n) { keys[q] -= kmin; vor |= keys[q]; }
+    }
+  } else if (in_lds) {
+    for (int64_t i = tid; i < n; i += NTH) { const unsigned long long key = lkeys[i] - kmin; lkeys[i] = key; vor |= key; }
+  } else {
+    for (int64_t i = tid; i < n; i += NTH) vor |= (unsigned long long)__double_as_longlong(scores[i]) - kmin;
+  }
+  // offset key of element i for the passes below (not for the register-resident case)
+  auto key_at = [&](int64_t i) -> unsigned long long {
+    return in_lds ? lkeys[i] : (unsigned long long)__double_as_longlong(scores[i]) - kmin;
+  };
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) vor |= __shfl_xor(vor, o, kWave);
+  if (lane == 0) s_or[wv] = vor;
+  __syncthreads();
+  vor = 0ull;
+  for (int i = 0; i < NW; ++i) vor |= s_or[i];
+  const unsigned long long diff = vor;                 // the smallest offset key is 0: every set bit differs somewhere
   // The first 8-bit digit window ends at the highest bit on which two keys differ, so the first pass already
   // spreads the keys over the bins; below it the windows follow each other down to bit 0 (the last one may be
   // narrower).  `top` = first bit above the current window; the bits from `top` upwards are the prefix.
@@ -105,7 +136,7 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
       }
     } else {
       for (int64_t i = tid; i < n; i += NTH) {
-        const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
+        const unsigned long long key = key_at(i);
         const bool match = (top >= 64) || ((key >> top) == prefix);
         if (match) atomicAdd(&hist[wv][(key >> shift) & dmask], 1u);
       }
@@ -157,7 +188,7 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
         }
       } else {
         for (int64_t i = tid; i < n; i += NTH) {
-          const unsigned long long key = (unsigned long long)__double_as_longlong(scores[i]);
+          const unsigned long long key = key_at(i);
           if ((key >> top) == np) {
             const int slot = atomicAdd(&s_ncand, 1);
             cand_key[slot] = key; cand_idx[slot] = (int)i;
@@ -195,13 +226,14 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
     // counts its "greater" and "equal" flags per chunk q, one wavefront turns the KPT x NW counts into exclusive
     // prefixes in index order, then every selected key knows its output position.  Two barriers, no global re-read.
     const unsigned long long below = (1ull << lane) - 1ull;
-    unsigned long long bg[KPT], be[KPT];
+    // (the flags are formed again in the last loop rather than kept: 2 * KPT wave masks would not fit the registers
+    // of a 1024-thread block)
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
       const int64_t c = (int64_t)q * NTH + tid;
-      bg[q] = __ballot(c < n && keys[q] > T);
-      be[q] = __ballot(c < n && keys[q] == T);
-      if (lane == 0) { scan_gt[q * NW + wv] = __popcll(bg[q]); scan_eq[q * NW + wv] = __popcll(be[q]); }
+      const unsigned long long bgq = __ballot(c < n && keys[q] > T);
+      const unsigned long long beq = __ballot(c < n && keys[q] == T);
+      if (lane == 0) { scan_gt[q * NW + wv] = __popcll(bgq); scan_eq[q * NW + wv] = __popcll(beq); }
     }
     __syncthreads();
     if (wv == 0) {
@@ -231,9 +263,10 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
 #pragma unroll
     for (int q = 0; q < KPT; ++q) {
       const int64_t c = (int64_t)q * NTH + tid;
-      const bool gt = (bg[q] >> lane) & 1ull, eq = (be[q] >> lane) & 1ull;
-      const long long gt_before = scan_gt[q * NW + wv] + __popcll(bg[q] & below);
-      const long long eq_before = scan_eq[q * NW + wv] + __popcll(be[q] & below);
+      const bool gt = c < n && keys[q] > T, eq = c < n && keys[q] == T;
+      const unsigned long long bgq = __ballot(gt), beq = __ballot(eq);
+      const long long gt_before = scan_gt[q * NW + wv] + __popcll(bgq & below);
+      const long long eq_before = scan_eq[q * NW + wv] + __popcll(beq & below);
       if (gt || (eq && eq_before < need)) {
         const long long pos = gt_before + (eq_before < need ? eq_before : need);
         if (pos < k) idx[pos] = (int32_t)c;
@@ -246,7 +279,7 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
   for (int64_t c0 = 0; c0 < n; c0 += NTH) {
     const int64_t c = c0 + tid;
     unsigned long long key = 0ull;
-    if (c < n) key = (unsigned long long)__double_as_longlong(scores[c]);
+    if (c < n) key = key_at(c);
     const bool gt = (c < n) && key > T;
     const bool eq = (c < n) && key == T;
     const unsigned long long bg = __ballot(gt), be = __ballot(eq);
@@ -272,12 +305,44 @@ __global__ __launch_bounds__(NTH) void k_topk_radix(const double* __restrict__ s
 }
 
 // Short inputs (BERT / ResNet channel counts) fit the registers of four wavefronts, whose barriers are cheaper; the
-// number of keys per thread is a template argument so that a short input does not walk through empty slots.
-static void launch_topk(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st) {
-  if (n <= 256) hipLaunchKernelGGL((k_topk_radix<256, 1>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
-  else if (n <= 4 * 256) hipLaunchKernelGGL((k_topk_radix<256, 4>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
-  else if (n <= 12 * 256) hipLaunchKernelGGL((k_topk_radix<256, 12>), dim3(1), dim3(256), 0, st, scores, n, k, idx);
-  else hipLaunchKernelGGL((k_topk_radix<1024, 12>), dim3(1), dim3(1024), 0, st, scores, n, k, idx);
+// number of keys per thread is a template argument so that a short input does not walk through empty slots.  Longer
+// inputs (LLM-sized layers) keep their keys in LDS, up to 16384 of them (128 KB); beyond that they are re-read.
+constexpr int64_t kTopkLdsKeys = 16384;
+void launch_topk(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st) {
+  if (n <= 256) hipLaunchKernelGGL((k_topk_radix<256, 1>), dim3(1), dim3(256), 0, st, scores, n, k, idx, 0);
+  else if (n <= 4 * 256) hipLaunchKernelGGL((k_topk_radix<256, 4>), dim3(1), dim3(256), 0, st, scores, n, k, idx, 0);
+  else if (n <= 12 * 256) hipLaunchKernelGGL((k_topk_radix<256, 12>), dim3(1), dim3(256), 0, st, scores, n, k, idx, 0);
+  else {
+    // set once per process (initialisation of a function-local static is thread-safe); a failure leaves the default
+    // LDS limit in place and the launch below then reports it
+    static const hipError_t attr = hipFuncSetAttribute((const void*)k_topk_radix<1024, 1>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)(kTopkLdsKeys * sizeof(unsigned long long)));
+    (void)attr;
+    const int in_lds = n <= kTopkLdsKeys ? 1 : 0;
+    const size_t lds = in_lds ? (size_t)n * sizeof(unsigned long long) : 0;
+    hipLaunchKernelGGL((k_topk_radix<1024, 1>), dim3(1), dim3(1024), lds, st, scores, n, k, idx, in_lds);
+  }
+}
+
+int launch_topk_profiled(const double* scores, int64_t n, int64_t k, int32_t* idx, hipStream_t st) {
+  {
+    ProfScope prof(PROF_TOPK, st);
+    launch_topk(scores, n, k, idx, st);
+  }
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
+}
+
+int launch_row_importance(const float* w, int64_t c_out, int64_t block, double* scores, hipStream_t st) {
+  const int vec = (((uintptr_t)w % 16) == 0 && block % 4 == 0) ? 1 : 0;
+  {
+    ProfScope prof(PROF_IMPORTANCE, st);
+    hipLaunchKernelGGL(k_row_importance, dim3((unsigned)ceil_div(c_out, 4)), dim3(256), 0, st, w, c_out, block, vec,
+                       scores);
+  }
+  EFQAT_LAUNCH_CHECK();
+  return EFQAT_OK;
 }
 
 // CWPN helpers: per-layer counts of selected channels, and global -> per-layer local indices.

@@ -69,6 +69,11 @@ def test_argument_validation_needs_no_device():
     assert L.efqat_layer_select(fake, fake, 0, 0, None, fake, fake, fake, 1 << 20, None) == -2
     assert L.efqat_layer_select(fake, fake, 4, 2, None, None, fake, fake, 1 << 20, None) == -1
     assert L.efqat_layer_select(fake, fake, 4, 2, None, fake, fake, fake, 8, None) == -6
+    # weight quantizer + select in one call
+    def wqs(w=fake, c_out=8, block=4, bits=8, k=2, idx=fake, ws=fake, wsb=1 << 20, scale=fake):
+        return L.efqat_weight_quant_select(w, c_out, block, bits, 1, scale, fake, fake, k, None, idx, ws, wsb, None)
+    assert wqs(w=None) == -1 and wqs(idx=None) == -1 and wqs(scale=None) == -1
+    assert wqs(c_out=0) == -2 and wqs(bits=9) == -3 and wqs(k=9) == -4 and wqs(wsb=8) == -6 and wqs(ws=fake + 8) == -9
     # select with the built-in scratch: argument errors come before anything touches a device
     assert L.efqat_channel_select_static(fake, 8, 4, 9, fake, None) == -4
     assert L.efqat_channel_select_static(fake, 0, 4, 0, fake, None) == -2

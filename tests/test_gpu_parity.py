@@ -145,11 +145,13 @@ def test_network_select_cwpn():
 
 
 @pytest.mark.parametrize("n,spread_bits,k", [(1000, 9, 137), (3072, 3, 768), (5000, 20, 1), (14000, 13, 9000),
-                                             (700, 0, 50)])
+                                             (700, 0, 50), (11008, 30, 2752), (16384, 11, 16000), (16385, 12, 77),
+                                             (40000, 17, 12345), (20000, 0, 300)])
 def test_topk_on_scores_that_differ_only_in_their_low_bits(n, spread_bits, k):
     # keys whose highest differing bit is low: the first digit window is clamped to bits 0..7 or is followed by a
     # narrower last window; many exact ties (every value occurs several times), which must go to the lower index.
-    # 14000 scores do not fit the registers of the block and take the re-reading path.
+    # More than 3072 scores do not fit the registers of the block: up to 16384 are kept in LDS, more are re-read
+    # from memory in every pass.
     base = np.float64(0.8171).view(np.uint64)
     r = synth.normal(900 + n, 0, (n,))
     low = (np.abs(r) * 1e6).astype(np.uint64) % np.uint64(1 << spread_bits) if spread_bits else np.zeros(n, np.uint64)
@@ -160,6 +162,18 @@ def test_topk_on_scores_that_differ_only_in_their_low_bits(n, spread_bits, k):
     ref = orc.top_k_channels(scores, k)
     assert kpl.cpu().numpy().tolist() == [k]
     assert idx.cpu().numpy().tolist() == ref.astype(np.int64).tolist()
+
+
+@pytest.mark.parametrize("n,k", [(300, 40), (2000, 999), (9000, 4500), (30000, 100)])
+def test_topk_on_scores_spread_over_many_binades(n, k):
+    # importances of very different magnitude (exponents differ): keys are ranked relative to the smallest one
+    r = synth.normal(950 + n, 0, (n,))
+    scores = np.abs(r) * 10.0 ** (np.arange(n) % 13 - 6)
+    scores[7] = scores[3]; scores[n - 1] = 0.0
+    flat = dev(scores); off_d = dev(np.array([0, n], dtype=np.int64))
+    idx, kpl = ef.network_select(flat, off_d, k)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == orc.top_k_channels(scores, k).astype(np.int64).tolist()
 
 
 def test_layer_select_lwpn():
@@ -212,6 +226,40 @@ def test_network_and_layer_select_on_random_networks(trial):
         np.testing.assert_allclose(ls.cpu().numpy(), imp, rtol=1e-12)
         assert lidx.cpu().numpy().tolist() == [int(v) for v in sel]
         assert kpl.cpu().numpy().tolist() == [int(v) for v in kpl_ref]
+
+
+@pytest.mark.parametrize("shape,bits,num,den", [((3072, 768), 8, 1, 4), ((768, 3072), 4, 1, 20), ((256, 3, 3, 256), 4, 1, 4),
+                                                 ((130, 70), 8, 1, 3), ((64, 20000), 8, 1, 2), ((11008, 4096), 4, 1, 100),
+                                                 ((40, 96), 8, 0, 1)],
+                         ids=lambda v: str(v))
+def test_weight_quant_select_equals_the_two_calls(shape, bits, num, den):
+    # one call for the weight side of a step (quantizer with the row in registers, which also sums |w|; Top-K) against
+    # the separate entry points and the oracle; (130, 70) and (64, 20000) take the fall-back kernels
+    W = synth.normal(333 + shape[0], 1, shape, std=0.02).astype(np.float32)
+    W[5] = W[2]                                              # equal scores: the tie goes to the lower index
+    wd = dev(W)
+    k = ef.k_from_ratio(shape[0], num, den)
+    one = ef.weight_quant_select(wd, bits, k)
+    fw = ef.fakequant_fwd(wd.view(shape[0], -1), ef.W_PER_ROW_SYM, bits, init_minmax=True)
+    idx, scores = ef.channel_select(wd, k)
+    torch.cuda.synchronize()
+    assert torch.equal(one["codes"].view(shape[0], -1), fw["codes"]) and torch.equal(one["clip_bits"], fw["clip_bits"])
+    assert torch.equal(one["scale"], fw["scale"]) and torch.equal(one["idx"], idx)
+    imp = orc.channel_importance(W)
+    np.testing.assert_allclose(one["scores"].cpu().numpy(), imp, rtol=1e-12)
+    np.testing.assert_allclose(scores.cpu().numpy(), imp, rtol=1e-12)
+    assert one["idx"].cpu().numpy().tolist() == orc.top_k_channels(imp, k).tolist()
+    sw = orc.weight_scale_minmax(W, bits)
+    codes, mask, _ = orc.fakequant_weight(W, sw, bits)
+    assert np.array_equal(one["scale"].cpu().numpy(), sw)
+    assert np.array_equal(one["codes"].cpu().numpy().astype(np.int64), codes)
+    assert np.array_equal(clip_words(one["clip_bits"]), pack_mask(mask.reshape(shape[0], -1)))
+    # given scales (no initialisation): the scores come from the pass of their own
+    two = ef.weight_quant_select(wd, bits, k, init_minmax=False, scale=dev((sw * np.float32(0.75)).astype(np.float32)))
+    torch.cuda.synchronize()
+    codes2, mask2, _ = orc.fakequant_weight(W, (sw * np.float32(0.75)).astype(np.float32), bits)
+    assert np.array_equal(two["codes"].cpu().numpy().astype(np.int64), codes2)
+    assert torch.equal(two["idx"], idx)
 
 
 BIAS_CASES = [
