@@ -51,6 +51,9 @@ def parse_args():
                     help="2: the weight-side calls of each layer run on a second stream, joined before its backward; "
                          "1: one stream; 0: two streams except for the small workloads (cfg1, cfg4), whose kernels are "
                          "shorter than the cross-stream joins cost")
+    ap.add_argument("--dw-stream", type=int, default=-1, choices=[-1, 0, 1],
+                    help="1: the backward calls get a second stream (side_stream) for their weight-gradient branch; "
+                         "-1: only for the workload that gains from it (cfg5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-attach", action="store_true",
@@ -175,19 +178,19 @@ class Layer:
         ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws_w, out=dict(scores=self.scores, idx=idx))
         return idx
 
-    def backward(self, ef, idx, prepared=False):
+    def backward(self, ef, idx, prepared=False, side=None):
         k = int(idx.numel())
         out = dict(dx=self.dx, dw=self.dw[:max(k, 1)], ds_w=self.ds_w[:max(k, 1)], ds_x=self.ds_x, dz_x=self.dz_x)
         if self.conv is None:
             ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                           self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
                           idx if k else None, dy_layout=self.layout, ws=self.ws, out=out,
-                          w_operand=self.w_op if prepared else None)
+                          w_operand=self.w_op if prepared else None, side_stream=side)
         else:
             ef.conv_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                         self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
                         idx if k else None, stride=self.conv["stride"], pad=self.conv["pad"],
-                        dy_layout=self.layout, ws=self.ws, out=out)
+                        dy_layout=self.layout, ws=self.ws, out=out, side_stream=side)
 
     def flops(self, k):
         # Eq. 7 / Eq. 8 op counts (x2 for multiply + add): dX over every channel, dW over the k selected ones
@@ -220,7 +223,25 @@ CLASSES = [("dx", 0), ("dw", 1), ("prep", 3), ("finish", 4), ("quant_act", 5), (
            ("topk", 8)]
 
 
-def make_step(torch, ef, layers, ks, streams):
+_DW_SIDE = {"stream": None}
+
+
+def dw_side_stream(torch, on=True):
+    """The stream handed to the backward calls as side_stream (one per process), or None when switched off."""
+    if not on:
+        return None
+    if _DW_SIDE["stream"] is None:
+        _DW_SIDE["stream"] = torch.cuda.Stream()
+    return _DW_SIDE["stream"]
+
+
+def dw_stream_default(workload):
+    # measured: the LLM-sized layers gain 1 - 2 % from running the two products side by side; on the smaller
+    # workloads the dX product is a single round of workgroups and the fork / join costs what the overlap gains
+    return workload == "cfg5"
+
+
+def make_step(torch, ef, layers, ks, streams, dw_side=False):
     """One step over `layers` with ks[i] selected channels each: quantize X and W, select, restricted backward.
 
     The weight-side call of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
@@ -231,6 +252,7 @@ def make_step(torch, ef, layers, ks, streams):
     streams == 1 issues everything on one stream through the plain entry points."""
     main_stream = torch.cuda.current_stream()
     side_stream = torch.cuda.Stream() if streams == 2 else None
+    dw_stream = dw_side_stream(torch, dw_side)
     ev_w = [torch.cuda.Event() for _ in layers]
     ev_bwd = [torch.cuda.Event() for _ in layers]
 
@@ -247,7 +269,7 @@ def make_step(torch, ef, layers, ks, streams):
                     ev_w[i].record(side_stream)
                 l.quant_x(ef)
                 main_stream.wait_event(ev_w[i])
-            l.backward(ef, idx, prepared=side_stream is not None)
+            l.backward(ef, idx, prepared=side_stream is not None, side=dw_stream)
             if side_stream is not None:
                 ev_bwd[i].record(main_stream)
     return step
@@ -302,7 +324,7 @@ def kernel_rows(layers, ks, prof):
     return rows
 
 
-def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer):
+def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer, side=False):
     """The backward call alone at every fraction: total time, speedup over r = 100 %, cost over r = 0 against k."""
     for l in layers:
         l.forward_quant(ef)
@@ -312,13 +334,14 @@ def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer):
         kk = [ef.k_from_ratio(l.c_out, n_, d_) for l in layers]
         idxs = [l.select(ef, k) for l, k in zip(layers, kk)]
 
-        def bwd():
+        def bwd(side=None):
             for l, idx in zip(layers, idxs):
-                l.backward(ef, idx)
+                l.backward(ef, idx, side=side)
+        timed = (lambda: bwd(dw_side_stream(torch))) if side else bwd
         for _ in range(max(2, warmup)):
-            bwd()
-        t = time_region(torch, bwd, max(3, steps))
-        prof = profiled(torch, ef, bwd, max(3, steps // 2))
+            timed()
+        t = time_region(torch, timed, max(3, steps))
+        prof = profiled(torch, ef, bwd, max(3, steps // 2))      # per class: on one stream, nothing overlaps
         times[(n_, d_)] = t
         fl = sum(l.flops(k) for l, k in zip(layers, kk))
         row = dict(r="%d/%d" % (n_, d_), k=kk, ms=round(t * 1e3, 5), tflops=round(fl / t / 1e12, 1),
@@ -327,7 +350,7 @@ def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer):
         if per_layer:
             lay = []
             for l, idx, k_ in zip(layers, idxs, kk):
-                one = lambda: l.backward(ef, idx)
+                one = lambda: l.backward(ef, idx, side=dw_side_stream(torch, side))
                 for _ in range(2):
                     one()
                 tl = time_region(torch, one, max(3, steps))
@@ -367,7 +390,7 @@ def compact_block(torch, ef, synth, workload, w_bits, layout, num, den, steps, w
     layers = build_layers(ef, torch, synth, workload, w_bits, layout, fracs)
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
     streams = 1 if workload in ("cfg1", "cfg4") else 2
-    step = make_step(torch, ef, layers, ks, streams)
+    step = make_step(torch, ef, layers, ks, streams, dw_stream_default(workload))
     for _ in range(warmup):
         step()
     sec = time_region(torch, step, steps)
@@ -378,7 +401,8 @@ def compact_block(torch, ef, synth, workload, w_bits, layout, num, den, steps, w
                step_ms=round(sec * 1e3, 5), tflops=round(flops / sec / 1e12, 1),
                dx_frac_of_mfma_peak=round(dx_fl / (prof["dx"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                kernels=kernel_rows(layers, ks, prof),
-               sweep=sweep_backward(torch, ef, layers, cfg["fractions"], steps, warmup, per_layer=False))
+               sweep=sweep_backward(torch, ef, layers, cfg["fractions"], steps, warmup, per_layer=False,
+                                    side=dw_stream_default(workload)))
     if workload == "cfg3":
         blk["note"] = ("the four linears of one encoder layer; the 12 layers of the stack repeat exactly this work "
                        "(x12 in time and flops)")
@@ -457,9 +481,11 @@ def main():
     layers = build_layers(ef, torch, synth, args.workload, w_bits, args.dy_layout, fracs)
     ks = [ef.k_from_ratio(l.c_out, num, den) for l in layers]
 
+    if args.dw_stream < 0:
+        args.dw_stream = int(dw_stream_default(args.workload))
     if args.streams == 0:
         args.streams = 1 if args.workload in ("cfg1", "cfg4") else 2
-    step = make_step(torch, ef, layers, ks, args.streams)
+    step = make_step(torch, ef, layers, ks, args.streams, bool(args.dw_stream))
 
     for _ in range(args.warmup):
         step()
@@ -490,7 +516,8 @@ def main():
                     kernels=kernel_rows(layers, ks, prof))
 
     if not args.no_sweep:
-        roofline["sweep"] = sweep_backward(torch, ef, layers, cfg["fractions"], args.steps, args.warmup, per_layer=True)
+        roofline["sweep"] = sweep_backward(torch, ef, layers, cfg["fractions"], args.steps, args.warmup, per_layer=True,
+                                           side=bool(args.dw_stream))
 
     # The backward call at the headline fraction on inputs of different structure (not part of `value`): a contiguous
     # block of channels (the best case for the compaction of dY columns; the selected set of i.i.d. rows is scattered,
@@ -596,6 +623,7 @@ def main():
                data="synthetic",
                config=dict(workload=workload_name, k=ks,
                            step="fakequant(X,W) + select + restricted backward, every layer", streams=args.streams,
+                           dw_side_stream=bool(args.dw_stream),
                            paper_context="paper: 1.44-1.64x whole-network backward speedup on A10/A100 (not this machine)"),
                roofline=roofline)
     if args.calibrate_copy:

@@ -298,10 +298,21 @@ typedef struct efqat_opt_step {
   int32_t* adam_t;     /* device, int32 [c_out]: steps taken per channel (zero before the first) */
 } efqat_opt_step;
 
-/* efqat_linear_bwd with three optional extras (all NULL / 0: exactly efqat_linear_bwd):
- *   w_operand  the dX weight operand made beforehand (see above); needs dx_kernel == AUTO
- *   step       fused optimizer step (see above); w and s_w are then updated in place
- *   dx_kernel  EFQAT_DX_KERNEL_*
+/* efqat_linear_bwd with four optional extras (all NULL / 0: exactly efqat_linear_bwd):
+ *   w_operand    the dX weight operand made beforehand (see above); needs dx_kernel == AUTO
+ *   step         fused optimizer step (see above); w and s_w are then updated in place
+ *   dx_kernel    EFQAT_DX_KERNEL_*
+ *   side_stream  a second HIP stream of the caller (default priority) on the same device.  The two
+ *                products of Eq. 5 do not depend on each other: with a second stream the compaction
+ *                of the selected dY columns and the dW product are enqueued there, behind
+ *                everything `stream` held when the call was made, and run beside the dX product, so
+ *                that the partly filled last round of workgroups of either product is filled by the
+ *                other.  The call joins the branch back into `stream` before the pass that finishes
+ *                dW, dS_w, dS_x and dZ_x: as without it, every output is ready in `stream` order,
+ *                and results are bit-identical.  The fork and join use two HIP events that the
+ *                library creates at the first such call of a host thread on a device and keeps
+ *                (no other state; nothing is created on later calls).  Ignored when k == 0, when it
+ *                equals `stream`, and on the layouts whose dW product runs on staged copies.
  * Workspace: efqat_linear_bwd_workspace_bytes_ex with the same dx_kernel. */
 size_t efqat_linear_bwd_workspace_bytes_ex(int64_t T, int64_t c_in, int64_t c_out, int64_t k,
                                            int dy_dtype, int dy_layout, int dx_kernel);
@@ -311,7 +322,7 @@ int efqat_linear_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t T, 
                         const uint32_t* w_clip, float* w, float* s_w, const int32_t* idx, int64_t k,
                         void* dx, int dx_dtype, float* dw, int scatter, float* ds_w, float* ds_x,
                         float* dz_x, const void* w_operand, const efqat_opt_step* step, int dx_kernel,
-                        void* ws, size_t ws_bytes, void* stream);
+                        void* ws, size_t ws_bytes, void* stream, void* side_stream);
 
 /* ------------------------------------------------------------------ conv backward
  * Same as efqat_linear_bwd for Y[n][ho][wo][co] = sum_{kh,kw,ci}
@@ -332,7 +343,8 @@ int efqat_conv_bwd(const void* dy, int dy_dtype, int dy_layout, int64_t N, int64
                    int64_t k, void* dx, int dx_dtype, float* dw, int scatter, float* ds_w,
                    float* ds_x, float* dz_x, void* ws, size_t ws_bytes, void* stream);
 
-/* efqat_conv_bwd with the optional fused optimizer step and dX kernel choice of efqat_linear_bwd_ex. */
+/* efqat_conv_bwd with the optional fused optimizer step, dX kernel choice and second stream of
+ * efqat_linear_bwd_ex. */
 size_t efqat_conv_bwd_workspace_bytes_ex(int64_t N, int64_t H, int64_t W, int64_t c_in, int64_t c_out,
                                          int64_t KH, int64_t KW, int64_t stride, int64_t pad,
                                          int64_t k, int dy_dtype, int dy_layout, int dx_kernel);
@@ -342,7 +354,8 @@ int efqat_conv_bwd_ex(const void* dy, int dy_dtype, int dy_layout, int64_t N, in
                       const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
                       float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
                       float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
-                      const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream);
+                      const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream,
+                      void* side_stream);
 
 /* ------------------------------------------------------------------ low-precision forward
  * The forward product of Sec. 3.1, Y = X_q W_q^T, computed from the 8-bit codes on the int8 matrix

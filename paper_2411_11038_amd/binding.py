@@ -97,7 +97,7 @@ def lib():
     L.efqat_linear_bwd.argtypes = [vp, ci, ci, i64, i64, i64] + bwd_common + [vp, sz, vp]
     L.efqat_linear_bwd_ex.restype = ci
     L.efqat_linear_bwd_ex.argtypes = ([vp, ci, ci, i64, i64, i64] + bwd_common + [vp, C.POINTER(OptStep), ci]
-                                      + [vp, sz, vp])
+                                      + [vp, sz, vp, vp])
     L.efqat_linear_bwd_weight_operand_bytes.restype = sz
     L.efqat_linear_bwd_weight_operand_bytes.argtypes = [i64, i64, i64, ci, ci]
     L.efqat_linear_bwd_weight_operand.restype = ci
@@ -109,7 +109,7 @@ def lib():
     L.efqat_conv_bwd.restype = ci
     L.efqat_conv_bwd.argtypes = [vp, ci, ci] + [i64] * 9 + bwd_common + [vp, sz, vp]
     L.efqat_conv_bwd_ex.restype = ci
-    L.efqat_conv_bwd_ex.argtypes = [vp, ci, ci] + [i64] * 9 + bwd_common + [C.POINTER(OptStep), ci] + [vp, sz, vp]
+    L.efqat_conv_bwd_ex.argtypes = [vp, ci, ci] + [i64] * 9 + bwd_common + [C.POINTER(OptStep), ci] + [vp, sz, vp, vp]
     L.efqat_linear_fwd_workspace_bytes.restype = sz
     L.efqat_linear_fwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.efqat_linear_fwd.restype = ci
@@ -362,12 +362,15 @@ def linear_bwd_weight_operand(w_codes, s_w, T, dy_dtype=BF16, dy_layout=DY_TOKEN
 
 
 def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, dy_layout=DY_TOKEN_MAJOR,
-               dx_dtype=None, scatter=False, ws=None, out=None, step=None, w_operand=None, dx_kernel=DX_KERNEL_AUTO):
+               dx_dtype=None, scatter=False, ws=None, out=None, step=None, w_operand=None, dx_kernel=DX_KERNEL_AUTO,
+               side_stream=None):
     """Backward of one quantized linear layer restricted to the rows idx.  Returns
     dict(dx, dw, ds_w, ds_x, dz_x).  `out` may carry preallocated outputs (same keys).
     step: dict for the fused optimizer step (see _step_struct): w and s_w are then updated in place.
     w_operand: the tensor made by linear_bwd_weight_operand for these weights.
-    dx_kernel: DX_KERNEL_* (tests and measurements).  Any of the three routes the call to efqat_linear_bwd_ex."""
+    dx_kernel: DX_KERNEL_* (tests and measurements).
+    side_stream: a torch.cuda.Stream on which the weight-gradient branch may run beside the dX product.
+    Any of the four routes the call to efqat_linear_bwd_ex."""
     L = lib()
     T, c_in = x_codes.shape
     c_out = w_codes.shape[0]
@@ -383,12 +386,12 @@ def linear_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, d
             _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
             _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 and dw is not None else None,
             int(bool(scatter)), _p(ds_w) if k > 0 and ds_w is not None else None, _p(ds_x), _p(dz_x))
-    if step is None and w_operand is None and dx_kernel == DX_KERNEL_AUTO:
+    if step is None and w_operand is None and dx_kernel == DX_KERNEL_AUTO and side_stream is None:
         rc = L.efqat_linear_bwd(*args, _p(ws), ws.numel(), _stream())
     else:
         st = _step_struct(step) if step is not None else None
         rc = L.efqat_linear_bwd_ex(*args, _p(w_operand), C.byref(st) if st is not None else None, dx_kernel,
-                                   _p(ws), ws.numel(), _stream())
+                                   _p(ws), ws.numel(), _stream(), side_stream.cuda_stream if side_stream else None)
     _check(rc, "efqat_linear_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)
 
@@ -409,7 +412,7 @@ def linear_fwd(x_codes, s_x, z_x, w_codes, s_w, y_dtype=torch.bfloat16, ws=None,
 
 def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, stride=1, pad=0,
              dy_layout=DY_TOKEN_MAJOR, dx_dtype=None, scatter=False, ws=None, out=None, step=None,
-             dx_kernel=DX_KERNEL_AUTO):
+             dx_kernel=DX_KERNEL_AUTO, side_stream=None):
     """Backward of one quantized conv layer (x NHWC, w OHWI) restricted to output channels idx."""
     L = lib()
     N, H, W, c_in = x_codes.shape
@@ -427,11 +430,11 @@ def conv_bwd(dy, x_codes, x_clip, x, s_x, z_x, w_codes, w_clip, w, s_w, idx, str
             _p(x_clip), _p(x), _dt(x), _p(s_x), _p(z_x), _p(w_codes), _p(w_clip), _p(w), _p(s_w),
             _p(idx) if k > 0 else None, k, _p(dx), _dt(dx), _p(dw) if k > 0 and dw is not None else None,
             int(bool(scatter)), _p(ds_w) if k > 0 and ds_w is not None else None, _p(ds_x), _p(dz_x))
-    if step is None and dx_kernel == DX_KERNEL_AUTO:
+    if step is None and dx_kernel == DX_KERNEL_AUTO and side_stream is None:
         rc = L.efqat_conv_bwd(*args, _p(ws), ws.numel(), _stream())
     else:
         st = _step_struct(step) if step is not None else None
         rc = L.efqat_conv_bwd_ex(*args, C.byref(st) if st is not None else None, dx_kernel, _p(ws), ws.numel(),
-                                 _stream())
+                                 _stream(), side_stream.cuda_stream if side_stream else None)
     _check(rc, "efqat_conv_bwd")
     return dict(dx=dx, dw=dw, ds_w=ds_w, ds_x=ds_x, dz_x=dz_x)

@@ -489,7 +489,27 @@ struct BwdIo {
   void* dx; int dx_dtype; float* dw; int scatter; float* ds_w; float* ds_x; float* dz_x;
   StepArgs sgd;    // fused optimizer step (sgd.w == nullptr: none)
   const void* w_operand = nullptr;   // optional: the bf16 W_q^T matrix (then 256 zero bytes) made beforehand
+  hipStream_t side = nullptr;        // optional: second stream for the weight-gradient branch
 };
+
+// Fork / join events of the optional second stream: one pair per host thread and device, made at first use and kept
+// (recording an event again while an earlier wait on it is still queued is well defined: a wait refers to the
+// record that preceded it).
+struct SideEvents { hipEvent_t fork, join; };
+static int side_events(SideEvents* out) {
+  constexpr int kMaxDev = 64;
+  thread_local SideEvents ev[kMaxDev];
+  thread_local bool have[kMaxDev] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return EFQAT_ERR_HIP;
+  if (!have[dev]) {
+    if (hipEventCreateWithFlags(&ev[dev].fork, hipEventDisableTiming) != hipSuccess) return EFQAT_ERR_HIP;
+    if (hipEventCreateWithFlags(&ev[dev].join, hipEventDisableTiming) != hipSuccess) return EFQAT_ERR_HIP;
+    have[dev] = true;
+  }
+  *out = ev[dev];
+  return EFQAT_OK;
+}
 
 // Everything that can still fail once the plan is known, checked before the first launch: pointer alignment of the
 // operands that the chosen kernels copy 16 bytes at a time, and the grid limits of the staging kernels.
@@ -539,6 +559,22 @@ static int run_bwd(const BwdIo& io, const BwdPlan& p, int64_t T_in, int64_t T_ou
     rc = transpose_to_bf16<int8_t>(io.w_codes, (int64_t)taps * c_in, c_out, c_in, nullptr, io.s_w, nullptr, wqT,
                                    p.Kx, 0, p.ldc, st, p.b_zero ? (uint32_t*)zero_page : nullptr, taps, &ex);
     if (rc) return rc;
+  }
+
+  // ---- optional second stream.  The weight-gradient branch (compaction of the selected columns of dY, dW product)
+  // reads the call's inputs and the zero page only, so it may run beside the dX product: blocks of the two products
+  // then share the compute units, and neither leaves a partly filled last round behind.  It is forked here, behind
+  // everything the caller's stream held before the call and behind the zero page, and joined before the second
+  // pass of the weight gradient.
+  const bool use_side = io.side && io.side != st && io.k > 0 && (p.tn || p.rdw);
+  hipStream_t st2 = st;
+  SideEvents ev{};
+  if (use_side) {
+    rc = side_events(&ev);
+    if (rc) return rc;
+    if (hipEventRecord(ev.fork, st) != hipSuccess || hipStreamWaitEvent(io.side, ev.fork, 0) != hipSuccess)
+      return EFQAT_ERR_HIP;
+    st2 = io.side;
   }
 
   // ---- dY as a token-major bf16 matrix [T_out][ldc] (A operand of the dX product)
@@ -605,13 +641,13 @@ static int run_bwd(const BwdIo& io, const BwdPlan& p, int64_t T_in, int64_t T_ou
     const bf16_t* At = (const bf16_t*)io.dy;
     int64_t ldat = c_out, acols = c_out;
     if (!p.tn_direct) {
-      ProfScope gat(PROF_PREP, st);
+      ProfScope gat(PROF_PREP, st2);
       const dim3 ggrid((unsigned)ceil_div(p.kp, 128), (unsigned)std::min<int64_t>(ceil_div(T_out, kGatherRows), 65535));
       if (io.dy_dtype == EFQAT_F32)
-        hipLaunchKernelGGL((k_gather_cols<float>), ggrid, dim3(256), 0, st, (const float*)io.dy, c_out, T_out, io.idx,
+        hipLaunchKernelGGL((k_gather_cols<float>), ggrid, dim3(256), 0, st2, (const float*)io.dy, c_out, T_out, io.idx,
                            io.k, sel, p.kp);
       else
-        hipLaunchKernelGGL((k_gather_cols<bf16_t>), ggrid, dim3(256), 0, st, (const bf16_t*)io.dy, c_out, T_out,
+        hipLaunchKernelGGL((k_gather_cols<bf16_t>), ggrid, dim3(256), 0, st2, (const bf16_t*)io.dy, c_out, T_out,
                            io.idx, io.k, sel, p.kp);
       EFQAT_LAUNCH_CHECK();
       At = sel; ldat = p.kp; acols = p.kp;
@@ -619,16 +655,16 @@ static int run_bwd(const BwdIo& io, const BwdPlan& p, int64_t T_in, int64_t T_ou
     if (p.cdw) {
       const ConvDwMap cm{cg->H, cg->W, cg->Ho, cg->Wo, cg->KW, cg->stride, cg->pad, (int)c_in};
       rc = launch_gemm_tn_conv(At, ldat, acols, io.x_codes, cm, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
-                               part_dw, st);
+                               part_dw, st2);
     } else {
       rc = launch_gemm_tn(At, ldat, acols, io.x_codes, c_in, c_in, zero_page, io.z_x, io.k, p.Nw, T_out, p.plan_dw,
-                          part_dw, st);
+                          part_dw, st2);
     }
     if (rc) return rc;
   } else if (p.rdw) {
     // ---- channel-major dY: the selected rows are gathered by the tile loads, the codes are read as they lie
     rc = launch_gemm_dw_rows((const bf16_t*)io.dy, T_out, io.idx, io.x_codes, c_in, zero_page, io.z_x, io.k, p.Nw,
-                             T_out, p.plan_dw, part_dw, st);
+                             T_out, p.plan_dw, part_dw, st2);
     if (rc) return rc;
   } else {
   ProfScope stg(PROF_PREP, st);                        // staged bf16 operands of the fall-back product
@@ -673,6 +709,8 @@ static int run_bwd(const BwdIo& io, const BwdPlan& p, int64_t T_in, int64_t T_ou
   rc = launch_gemm_nt(Aw, ldaw, a_rows, xcT, p.ldt, io.k, p.Nw, Kw, p.plan_dw, part_dw, nullptr, st);
   if (rc) return rc;
   }
+  if (use_side && (hipEventRecord(ev.join, st2) != hipSuccess || hipStreamWaitEvent(st, ev.join, 0) != hipSuccess))
+    return EFQAT_ERR_HIP;
   const int fvec = (p.Nw % 4 == 0 && ((uintptr_t)io.w % 16) == 0 && ((uintptr_t)io.dw % 16) == 0 &&
                     ((uintptr_t)io.w_codes % 4) == 0 && ((uintptr_t)io.sgd.mom_w % 16) == 0) ? 1 : 0;
   ProfScope fin(PROF_FINISH, st);
@@ -794,10 +832,11 @@ extern "C" int efqat_linear_bwd_ex(const void* dy, int dy_dtype, int dy_layout, 
                                    float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
                                    float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
                                    const void* w_operand, const efqat_opt_step* step, int dx_kernel, void* ws,
-                                   size_t ws_bytes, void* stream) {
+                                   size_t ws_bytes, void* stream, void* side_stream) {
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
   io.w_operand = w_operand;
+  io.side = (hipStream_t)side_stream;
   return linear_bwd_entry(io, T, c_in, c_out, step, w, s_w, dx_kernel, ws, ws_bytes, stream);
 }
 
@@ -907,8 +946,10 @@ extern "C" int efqat_conv_bwd_ex(const void* dy, int dy_dtype, int dy_layout, in
                                  const float* s_x, const float* z_x, const int8_t* w_codes, const uint32_t* w_clip,
                                  float* w, float* s_w, const int32_t* idx, int64_t k, void* dx, int dx_dtype,
                                  float* dw, int scatter, float* ds_w, float* ds_x, float* dz_x,
-                                 const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream) {
+                                 const efqat_opt_step* step, int dx_kernel, void* ws, size_t ws_bytes, void* stream,
+                                 void* side_stream) {
   BwdIo io{dy, dy_dtype, dy_layout, x_codes, x_clip, x, x_dtype, s_x, z_x, w_codes, w_clip, w, s_w, idx, k,
            dx, dx_dtype, dw, scatter, ds_w, ds_x, dz_x};
+  io.side = (hipStream_t)side_stream;
   return conv_bwd_entry(io, N, H, W, c_in, c_out, KH, KW, stride, pad, step, w, s_w, dx_kernel, ws, ws_bytes, stream);
 }

@@ -118,7 +118,7 @@ def test_argument_validation_needs_no_device():
     def lin_ex(wop_=None, step=None, dxk=0, ws=fake, wsb=1 << 30, dy=fake, w=fake, dw=fake, c_in=8, xc=fake, wc=fake,
                lay=0, k=2):
         return L.efqat_linear_bwd_ex(dy, 1, lay, 8, c_in, 8, xc, fake, fake, 1, fake, fake, wc, fake, w, fake, fake, k,
-                                     fake, 1, dw, 0, fake, fake, fake, wop_, step, dxk, ws, wsb, None)
+                                     fake, 1, dw, 0, fake, fake, fake, wop_, step, dxk, ws, wsb, None, None)
     assert lin_ex(dy=None) == -1
     assert lin_ex(wop_=fake + 64) == -9
     assert lin_ex(wsb=64) == -6 and lin_ex(wop_=fake, wsb=64) == -6
@@ -154,7 +154,7 @@ def test_argument_validation_needs_no_device():
     assert conv(wsb=64) == -6
     def conv_ex(step=None, dxk=0, wsb=1 << 30):
         return L.efqat_conv_bwd_ex(fake, 1, 0, 1, 4, 4, 8, 8, 3, 3, 1, 1, fake, fake, fake, 1, fake, fake, fake, fake,
-                                   fake, fake, fake, 2, fake, 1, fake, 0, fake, fake, fake, step, dxk, fake, wsb, None)
+                                   fake, fake, fake, 2, fake, 1, fake, 0, fake, fake, fake, step, dxk, fake, wsb, None, None)
     assert conv_ex(dxk=9) == -5 and conv_ex(wsb=64) == -6 and conv_ex(step=st(m=None)) == -1
 
 
