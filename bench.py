@@ -178,19 +178,19 @@ class Layer:
         ef.channel_select(self.w.view(self.c_out, -1), k, ws=self.ws_w, out=dict(scores=self.scores, idx=idx))
         return idx
 
-    def backward(self, ef, idx, prepared=False, side=None):
+    def backward(self, ef, idx, prepared=False, side=None, step=None):
         k = int(idx.numel())
         out = dict(dx=self.dx, dw=self.dw[:max(k, 1)], ds_w=self.ds_w[:max(k, 1)], ds_x=self.ds_x, dz_x=self.dz_x)
         if self.conv is None:
             ef.linear_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                           self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
                           idx if k else None, dy_layout=self.layout, ws=self.ws, out=out,
-                          w_operand=self.w_op if prepared else None, side_stream=side)
+                          w_operand=self.w_op if prepared else None, side_stream=side, step=step)
         else:
             ef.conv_bwd(self.dy, self.fx["codes"], self.fx["clip_bits"], self.x, self.fx["scale"],
                         self.fx["zero_point"], self.fw["codes"], self.fw["clip_bits"], self.w, self.fw["scale"],
                         idx if k else None, stride=self.conv["stride"], pad=self.conv["pad"],
-                        dy_layout=self.layout, ws=self.ws, out=out, side_stream=side)
+                        dy_layout=self.layout, ws=self.ws, out=out, side_stream=side, step=step)
 
     def flops(self, k):
         # Eq. 7 / Eq. 8 op counts (x2 for multiply + add): dX over every channel, dW over the k selected ones
@@ -585,8 +585,50 @@ def main():
         extras["bias_grad"] = dict(ms=round(tb * 1e3, 5), gbps=round(nbytes / tb / 1e9, 1), peak_gbps=PEAK_HBM_GBS,
                                    frac=round(nbytes / tb / 1e9 / PEAK_HBM_GBS, 4),
                                    note="db = column sums of dY, all layers, two launches per layer")
-        roofline["extras"] = extras
         del dbs, bws
+
+        # optimizer step of the unfrozen channels inside the backward call (SGD with momentum on the weight rows,
+        # Adam on their scales) against the plain call; learning rates of 0 keep the weights as they are
+        idxs = [l.select(ef, k) for l, k in zip(layers, ks)]
+        steps_ = [dict(lr_w=0.0, momentum=0.9, weight_decay=5e-4, mom_w=torch.zeros_like(l.w), lr_s=0.0,
+                       adam_m=torch.zeros(l.c_out, device="cuda"), adam_v=torch.zeros(l.c_out, device="cuda"),
+                       adam_t=torch.zeros(l.c_out, dtype=torch.int32, device="cuda")) for l in layers]
+
+        def bwd_plain():
+            for l, idx in zip(layers, idxs):
+                l.backward(ef, idx)
+
+        def bwd_step():
+            for l, idx, st_ in zip(layers, idxs, steps_):
+                l.backward(ef, idx, step=st_)
+        for _ in range(3):
+            bwd_plain(); bwd_step()
+        tp = time_region(torch, bwd_plain, max(3, args.steps // 2))
+        ts = time_region(torch, bwd_step, max(3, args.steps // 2))
+        upd = sum(k * l.c_in * l.taps * 4.0 * 5 for l, k in zip(layers, ks))   # dW, W and momentum read; W, momentum written
+        extras["fused_optimizer_step"] = dict(backward_ms=round(tp * 1e3, 5), backward_with_step_ms=round(ts * 1e3, 5),
+                                              unfused_update_mbytes=round(upd / 1e6, 1),
+                                              note="SGD (momentum 0.9, weight decay) on rows idx of W and Adam on S_w[idx] "
+                                                   "inside the pass that finishes dW; a separate update pass would move "
+                                                   "unfused_update_mbytes through HBM")
+        del steps_, idxs
+
+        # network-level (CWPN) and layer-level (LWPN) selection over a BERT-base-sized stack: 12 encoder layers of
+        # four linears, 82944 output channels
+        louts = [2304, 768, 3072, 768] * 12
+        off = torch.tensor([0] + list(torch.tensor(louts).cumsum(0).tolist()), dtype=torch.int64, device="cuda")
+        g_ = torch.Generator(device="cuda"); g_.manual_seed(7)
+        sc = torch.rand(int(off[-1].item()), generator=g_, device="cuda", dtype=torch.float64)
+        ktot = sc.numel() // 4
+        for _ in range(3):
+            ef.network_select(sc, off, ktot); ef.layer_select(sc, off, len(louts) // 4)
+        tn = time_region(torch, lambda: ef.network_select(sc, off, ktot), 10)
+        tl = time_region(torch, lambda: ef.layer_select(sc, off, len(louts) // 4), 10)
+        extras["network_select"] = dict(ms=round(tn * 1e3, 5), channels=sc.numel(), k_total=ktot, layers=len(louts),
+                                        note="EfQAT-CWPN: one Top-K over the channels of all layers")
+        extras["layer_select"] = dict(ms=round(tl * 1e3, 5), layers=len(louts), k_layers=len(louts) // 4,
+                                      note="EfQAT-LWPN: Top-K over the layers' mean scores")
+        roofline["extras"] = extras
 
     workload_name = describe(args.workload, layers, num, den, w_bits, cfg["a_bits"], args.dy_layout)
     # for the CPU baseline, run last (nothing here may keep a layer's device buffers alive)
