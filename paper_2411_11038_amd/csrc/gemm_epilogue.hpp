@@ -14,6 +14,7 @@ struct GemmArgs {
   int M, N, K;
   int k_per_split;        // multiple of KALIGN
   int tiles_m, tiles_n;
+  int group_m;                        // row tiles per group of the tile order (the kernels of gemm_tn.hip)
   float* out;             // raw fp32 [split][M][N]
   // fused dX epilogue
   const uint8_t* x_codes; const uint32_t* x_clip; const void* x; int x_dtype;
