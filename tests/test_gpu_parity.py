@@ -443,6 +443,9 @@ DX8_CASES = [
     (1030, 768, 1096, 8, 8, 0.8, (1, 20), False),   # 256 tile, 17 full stages + tail
     (384, 256, 136, 8, 8, 0.6, (1, 4), False),      # whole 128 tiles: straight-line epilogue, clipped activations
     (1024, 512, 200, 4, 8, 0.6, (1, 4), True),      # whole 256 tiles, 4-bit activations (many clipped)
+    # more than one round of 256 x 256 tiles on the 256 compute units
+    (2048, 8704, 64, 8, 8, 0.7, (1, 4), False),     # 8 x 34 whole tiles, one K stage
+    (2000, 8752, 72, 8, 4, 0.7, (1, 8), False),     # the same with ragged rows, a ragged last column tile and a K tail
 ]
 
 
