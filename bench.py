@@ -132,10 +132,10 @@ class Layer:
         nop = 0 if conv is not None else L.efqat_linear_bwd_weight_operand_bytes(self.T, c_in, c_out, dyd, layout)
         self.w_op = torch.empty(nop, dtype=torch.uint8, device=dev) if nop else None
 
-    def quant_x(self, ef):
+    def quant_x(self, ef, init=True):
         x2 = self.x.view(self.T_in, self.c_in)
         fx2 = dict(self.fx, codes=self.fx["codes"].view(self.T_in, self.c_in))
-        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, True, ws=self.ws, out=fx2)
+        ef.fakequant_fwd(x2, ef.ACT_PER_TENSOR_ASYM, self.a_bits, init, ws=self.ws, out=fx2)
 
     def quant_w(self, ef):
         w2 = self.w.view(self.c_out, -1)
@@ -241,7 +241,7 @@ def dw_stream_default(workload):
     return workload == "cfg5"
 
 
-def make_step(torch, ef, layers, ks, streams, dw_side=False):
+def make_step(torch, ef, layers, ks, streams, dw_side=False, act_init=True):
     """One step over `layers` with ks[i] selected channels each: quantize X and W, select, restricted backward.
 
     The weight-side call of a layer (quantize W, importance, Top-K: small kernels that leave most of the chip idle)
@@ -259,7 +259,7 @@ def make_step(torch, ef, layers, ks, streams, dw_side=False):
     def step():
         for i, (l, k) in enumerate(zip(layers, ks)):
             if side_stream is None:
-                l.quant_x(ef)
+                l.quant_x(ef, act_init)
                 idx = l.quant_w_select(ef, k)
             else:
                 side_stream.wait_event(ev_bwd[i])
@@ -267,7 +267,7 @@ def make_step(torch, ef, layers, ks, streams, dw_side=False):
                     idx = l.quant_w_select(ef, k)
                     l.prepare_w(ef)                      # the bf16 W_q^T operand of the dX product, where one is used
                     ev_w[i].record(side_stream)
-                l.quant_x(ef)
+                l.quant_x(ef, act_init)
                 main_stream.wait_event(ev_w[i])
             l.backward(ef, idx, prepared=side_stream is not None, side=dw_stream)
             if side_stream is not None:
@@ -545,6 +545,12 @@ def main():
         variants["scales_x0p7_clipped_activation_share"] = [round(l.clipped_fraction(torch), 5) for l in layers]
         for l in layers:
             l.forward_quant(ef)                          # back to the min/max scales
+        # the step as it runs once S_x, Z_x are trained parameters: Eq. 2's min / max pass is an initialisation, the
+        # headline step repeats it every time
+        step_given = make_step(torch, ef, layers, ks, args.streams, bool(args.dw_stream), act_init=False)
+        for _ in range(args.warmup):
+            step_given()
+        variants["step_with_given_activation_scales_ms"] = round(time_region(torch, step_given, args.steps) * 1e3, 5)
         roofline["variants"] = variants
 
     # low-precision forward (int8 matrix cores) and bias gradient of the same layers: not part of the step or of
