@@ -464,7 +464,10 @@ static BwdPlan make_plan(int64_t T_in, int64_t T_out, int64_t c_in, int64_t c_ou
   if (!p.dx8 && !p.cdx && io_bf16 && p.plan_dx.tile != 256 && (p.Mx % 192) == 0 && (c_in % 192) == 0 &&
       p.Mx * c_in <= (int64_t)INT32_MAX && dxk != EFQAT_DX_KERNEL_BF16_PINNED)
     p.plan_dx = gemm_plan(p.Mx, c_in, p.Kx, false, true, false, true);
-  p.kk = !p.dx8 && !p.cdx && p.plan_dx.tile == 192;
+  // 128 x 128 tiles that leave at most one block per compute unit anyway (<= 256 tiles) also take the three-stage
+  // ring: a lone block has nothing else to cover the load latency with (1 x 1 convolution of cfg4: 18 -> 14 us)
+  p.kk = !p.dx8 && !p.cdx &&
+         (p.plan_dx.tile == 192 || (p.plan_dx.tile == 128 && (int64_t)p.plan_dx.tiles_m * p.plan_dx.tiles_n <= 256));
   p.plan_dw = k > 0 ? gemm_plan(k, p.Nw, p.ldt, true, !(p.tn || p.rdw), !p.cdw) : GemmPlan{128, 1, 0, 0};
   WsCarver cv(nullptr);
   p.b_wqT = p.dx8 ? 0 : (size_t)c_in * p.Kx * 2; cv.take(p.b_wqT);

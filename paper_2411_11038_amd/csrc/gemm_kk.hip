@@ -179,8 +179,7 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   auto stage_sync = [&](auto steadyc, bool tail) {
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (decltype(steadyc)::value) {
-      static_assert(LPS == 12, "the wait count below is LPS");
-      asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LPS) : "memory");   // the LPS copies issued since stay in flight
     } else if (tail) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     } else {
@@ -343,6 +342,12 @@ int launch_gemm_kk(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, c
       const bool fast = a.epi_vec && epi->x_dtype == EFQAT_BF16 && epi->dx_dtype == EFQAT_BF16 && (M % 192) == 0 &&
                         (N % 192) == 0 && M * N <= (int64_t)INT32_MAX;
       return fast ? launch_kk_cfg<192, 2, 2, EPI_DXF>(ka, 1, stream) : launch_kk_cfg<192, 2, 2, EPI_DX>(ka, 1, stream);
+    }
+    case 128: {
+      if (!epi) return launch_kk_cfg<128, 2, 2, EPI_RAW>(ka, split_k, stream);
+      const bool fast = a.epi_vec && epi->x_dtype == EFQAT_BF16 && epi->dx_dtype == EFQAT_BF16 && (M % 128) == 0 &&
+                        (N % 128) == 0 && M * N <= (int64_t)INT32_MAX;
+      return fast ? launch_kk_cfg<128, 2, 2, EPI_DXF>(ka, 1, stream) : launch_kk_cfg<128, 2, 2, EPI_DX>(ka, 1, stream);
     }
     default:
       return EFQAT_ERR_BAD_SHAPE;
