@@ -532,8 +532,11 @@ int launch_gemm_nt_conv_dx(const bf16_t* dy_tok, int64_t ldc, const bf16_t* wqT,
   switch (plan.tile) {
     case 192: return nt_epilogue_fast(a, epi, 192) ? launch_cfg<192, 192, EPI_DXF, false, true>(a, 1, stream)
                                                    : launch_cfg<192, 192, EPI_DX, false, true>(a, 1, stream);
-    case 128: return nt_epilogue_fast(a, epi, 128) ? launch_cfg<128, 128, EPI_DXF, false, true>(a, 1, stream)
-                                                   : launch_cfg<128, 128, EPI_DX, false, true>(a, 1, stream);
+    case 128:
+      // at most one block per compute unit anyway: the three-stage ring hides the load latency a lone block sees
+      if ((int64_t)a.tiles_m * a.tiles_n <= 256) return launch_gemm_kk_conv128(a, nt_epilogue_fast(a, epi, 128), stream);
+      return nt_epilogue_fast(a, epi, 128) ? launch_cfg<128, 128, EPI_DXF, false, true>(a, 1, stream)
+                                           : launch_cfg<128, 128, EPI_DX, false, true>(a, 1, stream);
     default: return EFQAT_ERR_BAD_SHAPE;
   }
 }

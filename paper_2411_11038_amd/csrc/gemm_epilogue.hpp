@@ -30,6 +30,9 @@ struct GemmArgs {
   const void* cv_zero;
 };
 
+// dX product of a stride-1 convolution on 128 x 128 tiles by the kernel with the three-stage ring (gemm_kk.hip)
+int launch_gemm_kk_conv128(const GemmArgs& a, bool fast, hipStream_t stream);
+
 // Block barrier that orders LDS traffic only.  __syncthreads() also fences global memory, i.e. waits for every
 // outstanding global load and store of the wavefront; between the staging writes and reads of an epilogue that
 // would expose a memory round trip per barrier.  Global accesses keep their own dependency tracking.

@@ -46,7 +46,10 @@ struct GemmKkArgs {
   const void* zero_page;   // >= 256 zero bytes
 };
 
-template <int T, int WGM, int WGN, int EPI>
+// CONV: the A operand is gathered from a token-major dY with the im2col map of a stride-1 convolution, as in
+// k_gemm_nt (see GemmArgs): every copy slot keeps (n, h, w) of its input pixel and forms its source address per stage
+// from the stage's tap; K = taps * ldc is a whole number of stages.
+template <int T, int WGM, int WGN, int EPI, bool CONV = false>
 __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 #if defined(__HIP_DEVICE_COMPILE__)
   using C = KkCfg<T, WGM, WGN>;
@@ -84,12 +87,32 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
   const int c_lch = (lane & 7) ^ (((wave * 8 + c_lrow) >> 1) & 7);   // same for every slot: 32 j = 0 (mod 16)
   const char* a_ptr[C::A_G];
   const char* b_ptr[C::B_G];
+  int cv_q0[CONV ? C::A_G : 1], cv_hw[CONV ? C::A_G : 1];   // CONV: n * Ho * Wo and (h << 16 | w) of the slot's pixel
 #pragma unroll
   for (int j = 0; j < C::A_G; ++j) {
     int gm = m0 + (wave + 4 * j) * 8 + c_lrow;
     gm = gm < g.M ? gm : g.M - 1;
-    a_ptr[j] = (const char*)g.A + ((int64_t)gm * g.lda + k_begin) * 2 + c_lch * 16;
+    if constexpr (CONV) {
+      const int hw = g.cv_H * g.cv_W;
+      const int n = gm / hw, rem = gm - n * hw;
+      const int h = rem / g.cv_W, w = rem - h * g.cv_W;
+      cv_q0[j] = n * g.cv_Ho * g.cv_Wo;
+      cv_hw[j] = (h << 16) | w;
+      a_ptr[j] = nullptr;
+    } else {
+      a_ptr[j] = (const char*)g.A + ((int64_t)gm * g.lda + k_begin) * 2 + c_lch * 16;
+    }
   }
+  // CONV: source of this lane's 16 bytes of A slot j in stage kt (the zero page when the tap falls outside the image)
+  auto a_src_conv = [&](int j, int kt) -> const char* {
+    const int sidx = k_begin / 64 + kt;                // 64-channel stage index along K = (tap, channel)
+    const int tap = (int)(((uint64_t)(uint32_t)sidx * g.cv_m_spt) >> 32), cst = sidx - tap * g.cv_spt;
+    const int kh = (int)(((uint64_t)(uint32_t)tap * g.cv_m_kw) >> 32), kw = tap - kh * g.cv_KW;
+    const int ho = (cv_hw[j] >> 16) + g.cv_pad - kh, wo = (cv_hw[j] & 0xFFFF) + g.cv_pad - kw;
+    const bool ok = (unsigned)ho < (unsigned)g.cv_Ho && (unsigned)wo < (unsigned)g.cv_Wo;
+    const int64_t pix = (int64_t)cv_q0[j] + ho * g.cv_Wo + wo;
+    return ok ? (const char*)g.A + (pix * g.lda + cst * 64) * 2 + c_lch * 16 : zero;
+  };
 #pragma unroll
   for (int j = 0; j < C::B_G; ++j) {
     int gn = n0 + (wave + 4 * j) * 8 + c_lrow;
@@ -106,8 +129,12 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 #pragma unroll
     for (int t = t0; t < t1; ++t) {
       if (t < C::A_G) {
-        dma16(off ? zero : a_ptr[t], sa + (wave + 4 * t) * 1024);
-        a_ptr[t] += 128;
+        if constexpr (CONV) {
+          dma16(a_src_conv(t, kt), sa + (wave + 4 * t) * 1024);
+        } else {
+          dma16(off ? zero : a_ptr[t], sa + (wave + 4 * t) * 1024);
+          a_ptr[t] += 128;
+        }
       } else {
         const int u = t - C::A_G;
         dma16(off ? zero : b_ptr[u], sb + (wave + 4 * u) * 1024);
@@ -297,16 +324,16 @@ __global__ __launch_bounds__(256) void k_gemm_kk(const GemmKkArgs ga) {
 #endif
 }
 
-template <int T, int WGM, int WGN, int EPI>
+template <int T, int WGM, int WGN, int EPI, bool CONV = false>
 static int launch_kk_cfg(const GemmKkArgs& a, int split_k, hipStream_t st) {
   using C = KkCfg<T, WGM, WGN>;
   // set once per process (initialisation of a function-local static is thread-safe)
-  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_kk<T, WGM, WGN, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  static const hipError_t attr = hipFuncSetAttribute((const void*)k_gemm_kk<T, WGM, WGN, EPI, CONV>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
   if (attr != hipSuccess) return EFQAT_ERR_HIP;
   dim3 grid((unsigned)(a.g.tiles_m * a.g.tiles_n), (unsigned)split_k);
   {
     ProfScope prof(EPI == EPI_RAW ? PROF_DW : PROF_DX, st);
-    hipLaunchKernelGGL((k_gemm_kk<T, WGM, WGN, EPI>), grid, dim3(256), C::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((k_gemm_kk<T, WGM, WGN, EPI, CONV>), grid, dim3(256), C::LDS_BYTES, st, a);
   }
   EFQAT_LAUNCH_CHECK();
   return EFQAT_OK;
@@ -352,6 +379,17 @@ int launch_gemm_kk(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, c
     default:
       return EFQAT_ERR_BAD_SHAPE;
   }
+}
+
+// dX product of a stride-1 convolution on 128 x 128 tiles with the three-stage ring; `a` as launch_gemm_nt_conv_dx
+// fills it (K a whole number of 64-channel stages, no split-K).
+int launch_gemm_kk_conv128(const GemmArgs& a, bool fast, hipStream_t stream) {
+  if ((a.K % 64) != 0 || !a.cv_zero || ((uintptr_t)a.cv_zero % 16) != 0) return EFQAT_ERR_BAD_SHAPE;
+  GemmKkArgs ka{};
+  ka.g = a;
+  ka.g.k_per_split = a.K;
+  ka.zero_page = a.cv_zero;
+  return fast ? launch_kk_cfg<128, 2, 2, EPI_DXF, true>(ka, 1, stream) : launch_kk_cfg<128, 2, 2, EPI_DX, true>(ka, 1, stream);
 }
 
 }  // namespace efqat
