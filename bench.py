@@ -324,6 +324,32 @@ def kernel_rows(layers, ks, prof):
     return rows
 
 
+def products_per_layer(torch, ef, layers, ks, steps):
+    """The two product kernels layer by layer, each against its own roofline time max(flops / MFMA peak, bytes / HBM
+    peak): a short-K product such as the 3072 -> 768 FFN layer moves more bytes in its epilogue than its flops cover."""
+    for l in layers:
+        l.forward_quant(ef)
+    rows = []
+    for l, k in zip(layers, ks):
+        idx = l.select(ef, k)
+        one = lambda: l.backward(ef, idx)
+        for _ in range(3):
+            one()
+        pl = profiled(torch, ef, one, max(3, steps // 2))
+        row = dict(layer=l.name, k=k)
+        for name in ("dx", "dw"):
+            fl, by = l.work(k)[name]
+            ms, n = pl[name]
+            if n == 0:
+                continue
+            t_m, t_h = fl / (PEAK_BF16_TFLOPS * 1e12) * 1e3, by / (PEAK_HBM_GBS * 1e9) * 1e3
+            row[name] = dict(ms=round(ms, 5), tflops=round(fl / ms / 1e9, 1), mbytes=round(by / 1e6, 1),
+                             bound="mfma" if t_m >= t_h else "hbm", roof_ms=round(max(t_m, t_h), 5),
+                             frac=round(max(t_m, t_h) / ms, 4))
+        rows.append(row)
+    return rows
+
+
 def sweep_backward(torch, ef, layers, fracs, steps, warmup, per_layer, side=False):
     """The backward call alone at every fraction: total time, speedup over r = 100 %, cost over r = 0 against k."""
     for l in layers:
@@ -401,6 +427,7 @@ def compact_block(torch, ef, synth, workload, w_bits, layout, num, den, steps, w
                step_ms=round(sec * 1e3, 5), tflops=round(flops / sec / 1e12, 1),
                dx_frac_of_mfma_peak=round(dx_fl / (prof["dx"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                kernels=kernel_rows(layers, ks, prof),
+               products_per_layer=products_per_layer(torch, ef, layers, ks, steps),
                sweep=sweep_backward(torch, ef, layers, cfg["fractions"], steps, warmup, per_layer=False,
                                     side=dw_stream_default(workload)))
     if workload == "cfg3":
@@ -516,6 +543,7 @@ def main():
                     kernels=kernel_rows(layers, ks, prof))
 
     if not args.no_sweep:
+        roofline["products_per_layer"] = products_per_layer(torch, ef, layers, ks, args.steps)
         roofline["sweep"] = sweep_backward(torch, ef, layers, cfg["fractions"], args.steps, args.warmup, per_layer=True,
                                            side=bool(args.dw_stream))
 
