@@ -585,7 +585,7 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
     }
   }
   intx2_t braw[2][C::TN];
-  float scf[2][8], mvf[2][8];                       // the 8 scales of a lane's K positions, and -128 * scale
+  float scf[2][8];                                  // the 8 scales of a lane's K positions
   uint32_t bw[2][C::TN][4];                         // converted B fragments: 4 words of two bf16 each
   // LDS read number r of a sub-step: B codes, the scales, then the A fragments
   constexpr int NSC = DW ? 0 : 2;                   // LDS reads of scales per sub-step
@@ -617,15 +617,10 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
 #pragma unroll
     for (int r = 0; r < NRD; ++r) lds_read(bufc, sub, rb, r);
   };
-  // Weight codes -> bf16(S_w[c] * code): code + 128 is an unsigned byte, so S_w * code = fma(byte, S_w, -128 S_w),
-  // rounded once like the product itself.  Piece p of fragment j makes elements 2p and 2p + 1 (5 VALU operations).
+  // Weight codes -> bf16(S_w[c] * code): the signed byte is converted in one operation (the conversion selects and
+  // sign-extends the byte of its source) and multiplied by its scale in fp32, then rounded once like the product
+  // itself.  Piece p of fragment j makes elements 2p and 2p + 1 (5 VALU operations).
   constexpr int NPIECE = 4 * C::TN;
-  auto conv_offsets = [&](int rb) {
-    if constexpr (!DW) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) mvf[rb][t] = -128.0f * scf[rb][t];
-    }
-  };
   auto conv_piece = [&](int rb, int piece) {
     const int j = piece >> 2, pp = piece & 3;
     const int sh = 16 * (pp & 1);
@@ -633,14 +628,13 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
       const uint32_t w = (uint32_t)braw[rb][j][pp >> 1];
       bw[rb][j][pp] = pack_bf16x2((float)((w >> sh) & 0xFFu) - zq, (float)((w >> (sh + 8)) & 0xFFu) - zq);
     } else {
-      const uint32_t w = (uint32_t)braw[rb][j][pp >> 1] ^ 0x80808080u;
-      const float f0 = fmaf((float)((w >> sh) & 0xFFu), scf[rb][2 * pp], mvf[rb][2 * pp]);
-      const float f1 = fmaf((float)((w >> (sh + 8)) & 0xFFu), scf[rb][2 * pp + 1], mvf[rb][2 * pp + 1]);
+      const uint32_t w = (uint32_t)braw[rb][j][pp >> 1];
+      const float f0 = (float)(int8_t)((w >> sh) & 0xFFu) * scf[rb][2 * pp];
+      const float f1 = (float)(int8_t)((w >> (sh + 8)) & 0xFFu) * scf[rb][2 * pp + 1];
       bw[rb][j][pp] = pack_bf16x2(f0, f1);
     }
   };
   auto convert = [&](int rb) {
-    conv_offsets(rb);
 #pragma unroll
     for (int piece = 0; piece < NPIECE; ++piece) conv_piece(rb, piece);
   };
@@ -678,7 +672,6 @@ __global__ __launch_bounds__(256) void k_gemm_dx8(const GemmDx8Args ga) {
         for (int r = (qq * NRD) / HF; r < ((qq + 1) * NRD) / HF; ++r) lds_read(bufn, sub_next, rb ^ 1, r);
       }
       if (qq < t1 - t0) issue_range(Unchecked{}, kt_i, buf_i, t0 + qq, t0 + qq + 1);
-      if (qq == HF - 1) conv_offsets(rb ^ 1);
       if (qq >= MF - HF) {
         const int q2 = qq - (MF - HF);
 #pragma unroll
